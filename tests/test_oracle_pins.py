@@ -1,0 +1,384 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests re-types the oracle's own loops: every expected value is either a
+number the paper prints (tests/golden/), a closed form, a library routine on a special
+case, or a different algorithm (gray-code ordering, Kronecker products, a butterfly,
+finite differences, average pooling).
+"""
+import numpy as np
+import pytest
+import scipy.linalg
+
+import oracle
+from _golden import flop_example, lp_ranks, selection_prefix_p8, walsh_rows
+
+
+# ---------- independent helpers (numpy / scipy only) ----------
+
+def nat_of_sequency(s, bits):
+    """Sylvester row index of the Walsh function with s sign changes: bit-reversed Gray code."""
+    g = s ^ (s >> 1)
+    return int(format(g, f"0{bits}b")[::-1], 2) if bits else 0
+
+
+def walsh_np(p):
+    bits = p.bit_length() - 1
+    had = scipy.linalg.hadamard(p) if p > 1 else np.ones((1, 1), dtype=int)
+    return had[[nat_of_sequency(s, bits) for s in range(p)]]
+
+
+def basis_np(p, idx):
+    """[p*p, r] flattened 2-D bases through a Kronecker product."""
+    wal = walsh_np(p)
+    full = np.kron(wal, wal)          # full[u*p+v, h*p+w] = wal[u,h]*wal[v,w]
+    return full[np.asarray(idx)].T.astype(np.float64)
+
+
+def to_patches(a, p):
+    """[N,H,W,C] -> [Q, p*p, C], patch-major, row-major inside the patch."""
+    N, H, W, C = a.shape
+    a = a.reshape(N, H // p, p, W // p, p, C).transpose(0, 1, 3, 2, 4, 5)
+    return a.reshape(-1, p * p, C)
+
+
+def from_patches(a, shape, p):
+    N, H, W, C = shape
+    a = a.reshape(N, H // p, W // p, p, p, C).transpose(0, 1, 3, 2, 4, 5)
+    return a.reshape(N, H, W, C)
+
+
+def fwht_inplace(v):
+    """Textbook radix-2 butterfly along axis 0 (natural / Sylvester order), adds and subtracts only."""
+    n = v.shape[0]
+    h = 1
+    while h < n:
+        for i in range(0, n, 2 * h):
+            a = v[i:i + h].copy()
+            b = v[i + h:i + 2 * h].copy()
+            v[i:i + h] = a + b
+            v[i + h:i + 2 * h] = a - b
+        h *= 2
+    return v
+
+
+def rand_case(seed, N=2, H=8, W=16, Cin=5, Cout=7):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((N, H, W, Cin)), rng.standard_normal((N, H, W, Cout)),
+            rng.standard_normal((Cout, Cin)))
+
+
+def relerr(a, b):
+    return np.linalg.norm(np.asarray(a) - np.asarray(b)) / max(np.linalg.norm(np.asarray(b)), 1e-300)
+
+
+# ---------- Hadamard / Walsh / bases ----------
+
+@pytest.mark.parametrize("p", [1, 2, 4, 8, 16])
+def test_sylvester_is_orthogonal_and_matches_library(p):
+    had = oracle.sylvester(p).astype(np.int64)
+    assert set(np.unique(had)) <= {-1, 1}
+    assert np.array_equal(had @ had.T, p * np.eye(p, dtype=np.int64))
+    if p > 1:
+        assert np.array_equal(had, scipy.linalg.hadamard(p))
+
+
+def test_walsh_rows_match_the_printed_rows():
+    rows = walsh_rows()
+    for p in (4, 8):
+        wal = oracle.walsh(p).astype(np.int64)
+        for s in range(p):
+            assert np.array_equal(wal[s], rows[(p, s)]), (p, s)
+
+
+@pytest.mark.parametrize("p", [2, 4, 8, 16])
+def test_walsh_is_sequency_ordered_gray_code_permutation(p):
+    wal = oracle.walsh(p).astype(np.int64)
+    assert np.array_equal(wal, walsh_np(p))
+    for s in range(p):
+        assert int((np.diff(wal[s]) != 0).sum()) == s
+    assert np.all(wal[0] == 1)          # index 0 = lowest frequency = constant
+
+
+@pytest.mark.parametrize("p", [2, 4, 8])
+def test_all_bases_are_complete_orthogonal_and_pm1(p):
+    idx = np.arange(p * p)
+    B = oracle.basis_matrix(p, idx).astype(np.int64)
+    assert set(np.unique(B)) == {-1, 1}
+    assert np.array_equal(B.T @ B, p * p * np.eye(p * p, dtype=np.int64))
+    assert np.array_equal(B @ B.T, p * p * np.eye(p * p, dtype=np.int64))
+    assert np.array_equal(B, basis_np(p, idx).astype(np.int64))
+
+
+def test_basis_matrix_column_order_follows_idx():
+    p = 8
+    idx = [19, 0, 7, 56, 9]
+    B = oracle.basis_matrix(p, idx)
+    assert np.array_equal(B, basis_np(p, idx).astype(np.int8))
+    assert np.all(B[:, 1] == 1)
+
+
+def test_u_is_the_grid_height_axis_and_v_the_width_axis():
+    p = 8
+    wal = walsh_np(p)
+    # a patch that varies only along the width (w) with sequency 3: energy must sit in (u=0, v=3)
+    patch = np.tile(wal[3][None, :], (p, 1)).astype(np.float64)     # [h, w]
+    X = patch.reshape(1, p, p, 1)
+    coef = oracle.project(X, p, np.arange(p * p))[:, 0]
+    expect = np.zeros(p * p)
+    expect[0 * p + 3] = p * p
+    assert np.array_equal(coef, expect)
+    # and the transposed patch must sit in (u=3, v=0)
+    coef_t = oracle.project(patch.T.copy().reshape(1, p, p, 1), p, np.arange(p * p))[:, 0]
+    expect_t = np.zeros(p * p)
+    expect_t[3 * p + 0] = p * p
+    assert np.array_equal(coef_t, expect_t)
+
+
+# ---------- selection (Eq. 8, Eq. 9) ----------
+
+def test_shell_sizes_match_the_ranks_the_paper_lists():
+    for order, k, R in lp_ranks():
+        p = 8
+        idx = oracle.select_bases(p, R, order)
+        pairs = {(int(i) // p, int(i) % p) for i in idx}
+        if order == "l1":
+            assert R == k * (k + 1) // 2
+            assert pairs == {(u, v) for u in range(p) for v in range(p) if u + v <= k - 1}
+        else:
+            assert R == k * k
+            assert pairs == {(u, v) for u in range(p) for v in range(p) if max(u, v) <= k - 1}
+
+
+@pytest.mark.parametrize("order", ["l1", "linf"])
+def test_selection_prefix_matches_the_written_out_order(order):
+    want = selection_prefix_p8()[order]
+    got = oracle.select_bases(8, len(want), order)
+    assert [(int(i) // 8, int(i) % 8) for i in got] == want
+
+
+@pytest.mark.parametrize("p", [2, 4, 8, 16])
+@pytest.mark.parametrize("order", ["l1", "linf"])
+def test_selection_is_a_nested_permutation_starting_at_dc(p, order):
+    full = oracle.select_bases(p, p * p, order)
+    assert sorted(full.tolist()) == list(range(p * p))
+    assert full[0] == 0
+    for r in (1, 2, 3, p, p * p - 1):
+        if 1 <= r <= p * p:
+            assert np.array_equal(oracle.select_bases(p, r, order), full[:r])
+    u, v = full // p, full % p
+    key = u + v if order == "l1" else np.maximum(u, v)
+    assert np.all(np.diff(key) >= 0)      # shells are never interleaved
+
+
+def test_p4_r4_is_the_2x2_low_corner_in_both_orders():
+    for order in ("l1", "linf"):
+        assert oracle.select_bases(4, 4, order).tolist() == [0, 1, 4, 5]
+
+
+def test_bad_selection_arguments_are_rejected():
+    for args in [(3, 1, 0), (8, 0, 0), (8, 65, 0), (8, 4, 2)]:
+        with pytest.raises(ValueError):
+            oracle.select_bases(*args)
+    with pytest.raises(ValueError):
+        oracle.basis_matrix(4, [0, 0])
+    with pytest.raises(ValueError):
+        oracle.basis_matrix(4, [16])
+
+
+# ---------- exact backward (Eq. 2) ----------
+
+def test_full_bp_is_the_two_matmuls():
+    x, gy, w = rand_case(1)
+    gx, gW = oracle.full_bp_backward(x, gy, w)
+    X, G = x.reshape(-1, x.shape[-1]), gy.reshape(-1, gy.shape[-1])
+    assert relerr(gx.reshape(X.shape), G @ w) < 1e-14
+    assert relerr(gW, G.T @ X) < 1e-14
+
+
+def test_full_bp_is_the_gradient_of_the_forward_pass():
+    # y = x w^T (Eq. 1), loss = sum(y * g): central differences on a few coordinates
+    x, gy, w = rand_case(2, N=1, H=2, W=2, Cin=3, Cout=4)
+    gx, gW = oracle.full_bp_backward(x, gy, w)
+
+    def loss(xx, ww):
+        return float(np.sum((xx.reshape(-1, 3) @ ww.T) * gy.reshape(-1, 4)))
+
+    eps = 1e-6
+    for pos in [(0, 0, 0, 0), (0, 1, 0, 2), (0, 1, 1, 1)]:
+        d = np.zeros_like(x)
+        d[pos] = eps
+        assert abs((loss(x + d, w) - loss(x - d, w)) / (2 * eps) - gx[pos]) < 1e-7
+    for pos in [(0, 0), (3, 2), (1, 1)]:
+        d = np.zeros_like(w)
+        d[pos] = eps
+        assert abs((loss(x, w + d) - loss(x, w - d)) / (2 * eps) - gW[pos]) < 1e-7
+
+
+# ---------- Algorithm 1 ----------
+
+@pytest.mark.parametrize("p", [2, 4, 8])
+def test_all_bases_kept_reproduces_exact_backprop(p):
+    x, gy, w = rand_case(3 + p)
+    for order in ("l1", "linf"):
+        idx = oracle.select_bases(p, p * p, order)
+        gx, gW = oracle.lbp_wht_backward(x, gy, w, p, idx)
+        gx0, gW0 = oracle.full_bp_backward(x, gy, w)
+        assert relerr(gx, gx0) < 1e-13
+        assert relerr(gW, gW0) < 1e-13
+
+
+@pytest.mark.parametrize("p,r,order", [(4, 4, "l1"), (8, 8, "l1"), (8, 16, "linf"), (8, 10, "l1"), (2, 3, "l1")])
+def test_lbp_equals_backprop_of_the_orthogonally_projected_gradient(p, r, order):
+    # with P = B B^T / p^2 (symmetric idempotent of trace r):
+    #   gx = (P gy) W per patch,  gW = (P gy)^T x = gy^T (P x)
+    x, gy, w = rand_case(10 + r)
+    idx = oracle.select_bases(p, r, order)
+    B = basis_np(p, idx)
+    P = B @ B.T / (p * p)
+    assert np.allclose(P @ P, P) and np.allclose(P, P.T) and abs(np.trace(P) - r) < 1e-12
+    gyp = from_patches(np.einsum("ts,qsc->qtc", P, to_patches(gy, p)), gy.shape, p)
+    xp = from_patches(np.einsum("ts,qsc->qtc", P, to_patches(x, p)), x.shape, p)
+    G, Gp = gy.reshape(-1, gy.shape[-1]), gyp.reshape(-1, gy.shape[-1])
+    X, Xp = x.reshape(-1, x.shape[-1]), xp.reshape(-1, x.shape[-1])
+    gx, gW = oracle.lbp_wht_backward(x, gy, w, p, idx)
+    assert relerr(gx.reshape(X.shape), Gp @ w) < 1e-13
+    assert relerr(gW, Gp.T @ X) < 1e-13
+    assert relerr(gW, G.T @ Xp) < 1e-13
+
+
+def test_rank_one_is_average_pool_matmul_nearest_upsample():
+    import torch
+    import torch.nn.functional as F
+    p = 4
+    x, gy, w = rand_case(20, N=2, H=8, W=12, Cin=6, Cout=5)
+    gx, gW = oracle.lbp_wht_backward(x, gy, w, p, [0])
+    gy_t = torch.from_numpy(gy).permute(0, 3, 1, 2)                # N,C,H,W
+    x_t = torch.from_numpy(x).permute(0, 3, 1, 2)
+    gy_pool = F.avg_pool2d(gy_t, p)                                # patch means
+    x_sum = F.avg_pool2d(x_t, p) * (p * p)                         # patch sums
+    gx_low = torch.einsum("nohw,oi->nihw", gy_pool, torch.from_numpy(w))
+    gx_ref = F.interpolate(gx_low, scale_factor=p, mode="nearest").permute(0, 2, 3, 1).numpy()
+    gW_ref = torch.einsum("nohw,nihw->oi", gy_pool, x_sum).numpy()
+    assert relerr(gx, gx_ref) < 1e-13
+    assert relerr(gW, gW_ref) < 1e-13
+
+
+def test_gradient_inside_the_span_is_backpropagated_exactly():
+    p, r = 4, 5
+    rng = np.random.default_rng(30)
+    idx = oracle.select_bases(p, r, "l1")
+    B = basis_np(p, idx)
+    N, H, W, Cin, Cout = 2, 8, 8, 4, 6
+    coeff = rng.standard_normal((N * (H // p) * (W // p), r, Cout))
+    gy = from_patches(np.einsum("tk,qkc->qtc", B, coeff), (N, H, W, Cout), p)
+    x = rng.standard_normal((N, H, W, Cin))
+    w = rng.standard_normal((Cout, Cin))
+    gx, gW = oracle.lbp_wht_backward(x, gy, w, p, idx)
+    gx0, gW0 = oracle.full_bp_backward(x, gy, w)
+    assert relerr(gx, gx0) < 1e-13 and relerr(gW, gW0) < 1e-13
+
+
+def test_projection_keeps_energy_when_all_bases_are_kept():
+    p = 8
+    rng = np.random.default_rng(31)
+    X = rng.standard_normal((1, 8, 16, 3))
+    coef = oracle.project(X, p, np.arange(p * p))
+    assert abs(np.sum(coef ** 2) - p * p * np.sum(X ** 2)) < 1e-9 * np.sum(coef ** 2)
+
+
+@pytest.mark.parametrize("p", [2, 4, 8])
+def test_projection_matches_a_butterfly_transform(p):
+    # the 2-D transform of a row-major patch is the 1-D natural-order transform of length p^2;
+    # coefficient (u, v) sits at natural index nat(u)*p + nat(v)
+    rng = np.random.default_rng(40 + p)
+    X = rng.standard_normal((2, 2 * p, p, 3))
+    bits = p.bit_length() - 1
+    idx = oracle.select_bases(p, min(p * p, 11), "l1")
+    got = oracle.project(X, p, idx).reshape(-1, len(idx), 3)
+    patches = to_patches(X, p)
+    for q in range(patches.shape[0]):
+        spec = fwht_inplace(patches[q].copy())
+        for k, i in enumerate(idx):
+            u, v = int(i) // p, int(i) % p
+            nat = nat_of_sequency(u, bits) * p + nat_of_sequency(v, bits)
+            assert np.allclose(got[q, k], spec[nat], rtol=0, atol=1e-12)
+
+
+def test_unproject_inverts_project_with_all_bases_and_is_its_scaled_adjoint():
+    p = 4
+    rng = np.random.default_rng(50)
+    X = rng.standard_normal((2, 8, 4, 3))
+    idx_all = oracle.select_bases(p, p * p, "linf")
+    assert relerr(oracle.unproject(oracle.project(X, p, idx_all), X.shape, p, idx_all), X) < 1e-14
+    idx = oracle.select_bases(p, 6, "l1")
+    Y = rng.standard_normal((2 * 2 * 1 * 6, 3))
+    lhs = np.sum(oracle.project(X, p, idx) * Y)                 # <p(X), Y>
+    rhs = p * p * np.sum(X * oracle.unproject(Y, X.shape, p, idx))   # p^2 <X, p^-1(Y)>
+    assert abs(lhs - rhs) < 1e-10 * abs(lhs)
+
+
+def test_gx_error_never_grows_as_bases_are_added():
+    p = 8
+    x, gy, w = rand_case(60, N=1, H=8, W=8, Cin=4, Cout=6)
+    gx0, _ = oracle.full_bp_backward(x, gy, w)
+    order = oracle.select_bases(p, p * p, "l1")
+    errs = [np.linalg.norm(oracle.lbp_wht_backward(x, gy, w, p, order[:r], want_gw=False)[0] - gx0)
+            for r in (1, 3, 8, 16, 32, 63, 64)]
+    assert all(b <= a + 1e-12 for a, b in zip(errs, errs[1:]))
+    assert errs[-1] < 1e-12
+
+
+def test_spot_check_entry_points_agree_with_the_whole_computation():
+    p = 4
+    x, gy, w = rand_case(70, N=2, H=8, W=12, Cin=6, Cout=5)
+    idx = oracle.select_bases(p, 5, "l1")
+    gx, gW = oracle.lbp_wht_backward(x, gy, w, p, idx)
+    tokens = np.array([0, 7, 95, 96, 191, 100])
+    assert relerr(oracle.lbp_gx_tokens(gy, w, p, idx, tokens), gx.reshape(-1, 6)[tokens]) < 1e-13
+    co, ci = np.array([0, 4, 2, 3]), np.array([5, 0, 2, 1])
+    assert relerr(oracle.lbp_gw_entries(x, gy, p, idx, co, ci), gW[co, ci]) < 1e-13
+    G, X = gy.reshape(-1, 5), x.reshape(-1, 6)
+    assert relerr(oracle.full_gx_tokens(gy, w, tokens), (G @ w)[tokens]) < 1e-14
+    assert relerr(oracle.full_gw_entries(x, gy, co, ci), (G.T @ X)[co, ci]) < 1e-14
+
+
+def test_patches_do_not_mix():
+    # changing gy in one patch changes gx only inside that patch
+    p = 4
+    x, gy, w = rand_case(80, N=1, H=8, W=8, Cin=3, Cout=3)
+    idx = oracle.select_bases(p, 3, "l1")
+    gx_a, _ = oracle.lbp_wht_backward(x, gy, w, p, idx)
+    gy2 = gy.copy()
+    gy2[0, 4:8, 0:4] += 1.0            # patch (a=1, b=0)
+    gx_b, _ = oracle.lbp_wht_backward(x, gy2, w, p, idx)
+    diff = np.abs(gx_b - gx_a).sum(axis=-1)[0]
+    mask = np.zeros((8, 8), dtype=bool)
+    mask[4:8, 0:4] = True
+    assert np.all(diff[~mask] == 0) and np.all(diff[mask] > 0)
+
+
+def test_grid_must_be_a_multiple_of_the_patch():
+    x, gy, w = rand_case(90, N=1, H=6, W=8, Cin=2, Cout=2)
+    with pytest.raises(ValueError):
+        oracle.lbp_wht_backward(x, gy, w, 4, [0])
+
+
+# ---------- cost model (Table 1, Section 3.3) ----------
+
+def test_cost_model_reproduces_the_printed_example():
+    g = flop_example()
+    f = oracle.flop_model(int(g["Cx"]), int(g["Cy"]), int(g["L"]), int(g["r"]))
+    mf = {k: v / 1e6 for k, v in f.items()}
+    lbp = mf["projection"] + mf["low_rank_mm"] + mf["reverse_projection"]
+    overhead = mf["projection"] + mf["reverse_projection"]
+    assert abs(mf["vanilla_bp"] - g["vanilla_bp_mflops"]) < 0.15          # printed value is truncated
+    assert abs(lbp - g["lbp_total_mflops"]) < 0.05
+    assert abs(mf["projection"] - g["projection_mflops"]) < 0.05
+    assert abs(mf["low_rank_mm"] - g["low_rank_mm_mflops"]) < 0.05
+    assert abs(mf["reverse_projection"] - g["reverse_projection_mflops"]) < 0.05
+    assert abs(overhead - g["overhead_mflops"]) < 0.05
+    assert abs(100 * lbp / mf["vanilla_bp"] - g["lbp_over_bp_percent"]) < 0.05
+    assert abs(100 * overhead / mf["vanilla_bp"] - g["overhead_over_bp_percent"]) < 0.05
+    assert abs(100 * overhead / lbp - g["overhead_over_lbp_percent"]) < 0.05
+    # speedup of the matmuls alone is L / r
+    assert abs(f["vanilla_bp"] / f["low_rank_mm"] - g["L"] / g["r"]) < 1e-12
