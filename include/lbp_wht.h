@@ -1,0 +1,152 @@
+/*
+ * lbp_wht.h -- C ABI of the MI355X (gfx950) library for low-rank backpropagation through one
+ * linear layer with Walsh-Hadamard projections (LBP-WHT).
+ *
+ * The call shape follows the problem statement of Algorithm 1 (Section 3.1):
+ *     input  x, w, g_y and the set I of selected WHT bases;
+ *     output the approximated gradients g~_x and g~_w.
+ *
+ * Conventions shared by every entry point
+ *   Layout   token-major, channel innermost, row-major, densely packed:
+ *              x  [N][H][W][Cin]      gy [N][H][W][Cout]     W  [Cout][Cin]
+ *              gx [N][H][W][Cin]      gW [Cout][Cin]
+ *            (Section 2 writes w in R^{Cy x Cx}; y = x w^T per token.)
+ *   Patches  the H x W token grid of every image is tiled into non-overlapping patch x patch
+ *            blocks; the order-`patch` 2-D WHT of Section 3 is applied inside each block, and the
+ *            weight gradient sums over blocks and images.  H and W must be multiples of patch.
+ *   Bases    basis_idx[k] = u*patch + v, with (u, v) the 0-based SEQUENCY indices along the grid's
+ *            H axis (u) and W axis (v): index 0 is the constant basis and a larger index is a
+ *            higher frequency (Section 3.2).  Entries must be distinct and in [0, patch^2).
+ *   Scaling  the forward projection (Eq. 6) is applied unnormalised; gx and gW each carry one factor
+ *            1/patch^2, so that keeping all patch^2 bases reproduces exact backpropagation (Eq. 2).
+ *   Memory   x, gy, W, gx, gW and workspaces are DEVICE pointers owned by the caller, 16-byte
+ *            aligned; `shape` and `basis_idx` are HOST pointers read only during the call.
+ *            Outputs are overwritten (never accumulated into) and must not overlap any input.
+ *   Stream   `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *            enqueued on it; no entry point synchronises the device.
+ *   Errors   every function returning int gives LBP_OK (0) or a negative lbp_status_t.  Argument
+ *            errors are detected on the host before any HIP call is made, so they can be provoked
+ *            and tested on a machine without a GPU.  There is no CPU fallback: without a usable
+ *            gfx950 device the compute entry points return LBP_ERR_HIP.
+ *   Threads  entry points may be called from several host threads; calls that use the library's
+ *            internal workspace on the same device are serialised by the caller's stream order
+ *            only, so concurrent calls on different streams of one device must each bring their
+ *            own workspace (lbp_set_workspace is per process, see below).
+ */
+#ifndef LBP_WHT_H
+#define LBP_WHT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LBP_F32 = 0,   /* IEEE binary32 tensors, fp32 arithmetic                                  */
+    LBP_BF16 = 1   /* bfloat16 tensors, bf16 matrix-core products with fp32 accumulation      */
+} lbp_dtype_t;
+
+typedef enum {
+    LBP_ORDER_L1 = 0,   /* LP_L1  low-pass order (Eq. 8): shells of constant u+v              */
+    LBP_ORDER_LINF = 1  /* LP_Linf low-pass order (Eq. 9): shells of constant max(u,v)        */
+} lbp_order_t;
+
+typedef enum {
+    LBP_OK = 0,
+    LBP_ERR_NULL = -1,     /* a required pointer is NULL                                       */
+    LBP_ERR_SHAPE = -2,    /* non-positive dimension, H or W not a multiple of patch, or a size
+                              beyond what 32-bit row indices address (N*H*W >= 2^31)           */
+    LBP_ERR_PATCH = -3,    /* patch not in {2, 4, 8, 16}                                       */
+    LBP_ERR_RANK = -4,     /* r < 1 or r > patch^2                                             */
+    LBP_ERR_BASIS = -5,    /* a basis index out of [0, patch^2) or listed twice                */
+    LBP_ERR_DTYPE = -6,    /* unknown dtype / gw_dtype, or an unsupported combination          */
+    LBP_ERR_ALIAS = -7,    /* an output buffer overlaps an input or the other output           */
+    LBP_ERR_ALIGN = -8,    /* a device pointer is not 16-byte aligned, or a channel count is not
+                              a multiple of the vector width the kernels need (8 for bf16, 4 for
+                              fp32)                                                            */
+    LBP_ERR_ORDER = -9,    /* order is neither LBP_ORDER_L1 nor LBP_ORDER_LINF                 */
+    LBP_ERR_WORKSPACE = -10, /* caller-provided workspace too small                            */
+    LBP_ERR_HIP = -11      /* a HIP call failed (no device, allocation, launch); the HIP error
+                              code is kept and returned by lbp_last_hip_error()                */
+} lbp_status_t;
+
+typedef struct {
+    int32_t N, H, W;     /* batch size and token grid of one image                             */
+    int32_t Cin, Cout;   /* C_x and C_y of Section 2                                           */
+    int32_t dtype;       /* lbp_dtype_t of x, gy, W and gx                                     */
+    int32_t gw_dtype;    /* lbp_dtype_t of gW: LBP_F32, or the same as dtype                   */
+} lbp_shape_t;
+
+/*
+ * Low-pass basis selection, Section 3.2 (Eq. 8 for LP_L1, Eq. 9 for LP_Linf).
+ * Writes the first r sequency pairs of the chosen order into basis_idx (host, r ints).
+ * Inside a shell the order is: LP_L1 by (u+v, max(u,v), u); LP_Linf by (max(u,v), u+v, u), so for
+ * r = k(k+1)/2 (LP_L1) or r = k^2 (LP_Linf) the set is exactly the paper's LP-k selection.
+ * Pure host integer code; never touches the GPU.
+ */
+int lbp_wht_select_bases(int patch, int r, int order, int32_t *basis_idx);
+
+/*
+ * Algorithm 1 (Section 3.1): x^ = WHT(x; I), g^y = WHT(gy; I), g^w = g^y^T x^, g^x = g^y w,
+ * g~x = WHT^-1(g^x; I), g~w = g^w, with Eq. 6 / Eq. 7 per token patch.
+ *   x, gy, W   inputs (device);  gx, gW outputs (device), either may be NULL to skip it.
+ *   basis_idx  host array of r indices (see "Bases" above); r in [1, patch^2].
+ * Uses the workspace set by lbp_set_workspace, else an internal per-device buffer that grows on
+ * demand (the first call at a new size allocates device memory; later calls do not).
+ */
+int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
+                     int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream);
+
+/*
+ * Exact backward of Eq. 2 (Section 2), the full-rank comparison point built from the same
+ * kernels: gx = gy W (per token), gW = gy^T x (summed over all tokens).  Same argument rules.
+ */
+int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
+                     void *gx, void *gW, void *stream);
+
+/*
+ * The projection p(.) of Eq. 6 alone (first two statements of Algorithm 1), for one tensor:
+ *   in  [N][H][W][C] (device, dtype)  ->  out [(N*H*W/patch^2) * r][C] (device, same dtype),
+ * row (q*r + k) holding coefficient k of patch q = (n*(H/patch) + a)*(W/patch) + b, unnormalised.
+ * It is what the backward runs internally on x and gy; exported so that the projection can be
+ * measured and checked by itself.
+ */
+int lbp_wht_project(const void *in, int N, int H, int W, int C, int dtype, int patch,
+                    const int32_t *basis_idx, int r, void *out, void *stream);
+
+/*
+ * The reverse projection p^-1(.) of Eq. 7 alone, with the 1/patch^2 factor:
+ *   in  [(N*H*W/patch^2) * r][C] (device, ALWAYS fp32: it is the accumulator of g^y w)
+ *   out [N][H][W][C] (device, dtype).
+ */
+int lbp_wht_unproject(const void *in, int N, int H, int W, int C, int dtype, int patch,
+                      const int32_t *basis_idx, int r, void *out, void *stream);
+
+/* Bytes of device workspace lbp_wht_backward / full_bp_backward need for this problem
+ * (r = 0 and patch = 0 ask for full_bp_backward).  0 on invalid arguments. */
+size_t lbp_wht_workspace_bytes(const lbp_shape_t *shape, int patch, int r);
+
+/* Hands the library a caller-owned device buffer to use as workspace on the current device for all
+ * later calls of this process (dev_ptr = NULL returns to the internal buffer).  The caller keeps
+ * ownership and must keep it alive while calls are in flight.  Calls whose need exceeds `bytes`
+ * return LBP_ERR_WORKSPACE. */
+int lbp_set_workspace(void *dev_ptr, size_t bytes);
+
+/* Frees the internal workspaces of all devices (synchronises each device first). */
+int lbp_release_workspace(void);
+
+/* Static description of a status code. */
+const char *lbp_strerror(int code);
+
+/* HIP error code (hipError_t as int) of the most recent LBP_ERR_HIP on this thread, else 0. */
+int lbp_last_hip_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int lbp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LBP_WHT_H */

@@ -1,0 +1,198 @@
+"""ctypes binding of liblbpwht.so (include/lbp_wht.h).  Argument marshalling only: every step of
+the backward pass runs in the library's HIP kernels.  PyTorch is used for device memory and
+streams, nothing else.  There is no fallback: if the library is not built, or a call fails, an
+exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "liblbpwht.so")
+
+LBP_F32, LBP_BF16 = 0, 1
+ORDER_L1, ORDER_LINF = 0, 1
+_ORDERS = {"l1": ORDER_L1, "linf": ORDER_LINF, ORDER_L1: ORDER_L1, ORDER_LINF: ORDER_LINF}
+_DTYPES = {torch.float32: LBP_F32, torch.bfloat16: LBP_BF16}
+
+# every symbol include/lbp_wht.h declares
+EXPORTS = ("lbp_wht_select_bases", "lbp_wht_backward", "full_bp_backward", "lbp_wht_project",
+           "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
+           "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version")
+
+
+class LbpShape(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
+                ("Cin", ctypes.c_int32), ("Cout", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("gw_dtype", ctypes.c_int32)]
+
+
+class LbpError(RuntimeError):
+    def __init__(self, code, message, hip_error=0):
+        super().__init__(f"liblbpwht: {message} (status {code}, hip error {hip_error})")
+        self.code = code
+        self.hip_error = hip_error
+
+
+_lib = None
+
+
+def load():
+    """Loads the built library; raises if it is missing (build with __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is not built; run `python -m paper_2309_15275_amd.build` (needs hipcc)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
+    shp = ctypes.POINTER(LbpShape)
+    lib.lbp_wht_select_bases.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p]
+    lib.lbp_wht_backward.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.full_bp_backward.argtypes = [vp, vp, vp, shp, vp, vp, vp]
+    lib.lbp_wht_project.argtypes = [vp] + [ctypes.c_int] * 6 + [i32p, ctypes.c_int, vp, vp]
+    lib.lbp_wht_unproject.argtypes = [vp] + [ctypes.c_int] * 6 + [i32p, ctypes.c_int, vp, vp]
+    lib.lbp_wht_workspace_bytes.argtypes = [shp, ctypes.c_int, ctypes.c_int]
+    lib.lbp_wht_workspace_bytes.restype = ctypes.c_size_t
+    lib.lbp_set_workspace.argtypes = [vp, ctypes.c_size_t]
+    lib.lbp_release_workspace.argtypes = []
+    lib.lbp_strerror.argtypes = [ctypes.c_int]
+    lib.lbp_strerror.restype = ctypes.c_char_p
+    lib.lbp_last_hip_error.argtypes = []
+    lib.lbp_version.argtypes = []
+    for name in EXPORTS:
+        getattr(lib, name)          # AttributeError here means the library is stale
+    _lib = lib
+    return lib
+
+
+def _check(code):
+    if code != 0:
+        lib = load()
+        raise LbpError(code, lib.lbp_strerror(code).decode(), lib.lbp_last_hip_error())
+
+
+def strerror(code):
+    return load().lbp_strerror(int(code)).decode()
+
+
+def version():
+    return int(load().lbp_version())
+
+
+def _idx_array(basis_idx):
+    vals = [int(v) for v in basis_idx]
+    return (ctypes.c_int32 * max(len(vals), 1))(*vals), len(vals)
+
+
+def select_bases(patch, r, order="l1"):
+    """Low-pass selection of Section 3.2; returns a list of r indices u*patch + v."""
+    if order not in _ORDERS:
+        _check(-9)
+    out = (ctypes.c_int32 * max(int(r), 1))()
+    _check(load().lbp_wht_select_bases(int(patch), int(r), _ORDERS[order], out))
+    return list(out[:r])
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev_tensor(t, name, dtype=None):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous CUDA/HIP tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def make_shape(x, gy, w, gw_dtype=torch.float32):
+    N, H, W, Cin = x.shape
+    Cout = gy.shape[-1]
+    if tuple(gy.shape[:3]) != (N, H, W) or tuple(w.shape) != (Cout, Cin):
+        raise ValueError("shapes must be x[N,H,W,Cin], gy[N,H,W,Cout], w[Cout,Cin]")
+    if x.dtype not in _DTYPES or gw_dtype not in _DTYPES:
+        raise TypeError("dtype must be float32 or bfloat16")
+    return LbpShape(N, H, W, Cin, Cout, _DTYPES[x.dtype], _DTYPES[gw_dtype])
+
+
+def lbp_wht_backward(x, gy, w, patch, basis_idx, gx=None, gW=None, want_gx=True, want_gw=True,
+                     gw_dtype=torch.float32, stream=None):
+    """Algorithm 1 on the GPU.  x [N,H,W,Cin], gy [N,H,W,Cout], w [Cout,Cin] device tensors of one
+    dtype (float32 or bfloat16).  Returns (gx, gW); outputs are allocated when not passed in."""
+    shape = make_shape(x, gy, w, gw_dtype)
+    if want_gx and gx is None:
+        gx = torch.empty_like(x)
+    if want_gw and gW is None:
+        gW = torch.empty(w.shape, dtype=gw_dtype, device=w.device)
+    idx, r = _idx_array(basis_idx)
+    with torch.cuda.device(x.device):
+        _check(load().lbp_wht_backward(
+            _dev_tensor(x, "x"), _dev_tensor(gy, "gy", x.dtype), _dev_tensor(w, "w", x.dtype),
+            ctypes.byref(shape), int(patch), idx, r,
+            _dev_tensor(gx, "gx", x.dtype) if gx is not None else None,
+            _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
+    return gx, gW
+
+
+def full_bp_backward(x, gy, w, gx=None, gW=None, want_gx=True, want_gw=True,
+                     gw_dtype=torch.float32, stream=None):
+    """Exact backward of Eq. 2 on the GPU, same conventions as lbp_wht_backward."""
+    shape = make_shape(x, gy, w, gw_dtype)
+    if want_gx and gx is None:
+        gx = torch.empty_like(x)
+    if want_gw and gW is None:
+        gW = torch.empty(w.shape, dtype=gw_dtype, device=w.device)
+    with torch.cuda.device(x.device):
+        _check(load().full_bp_backward(
+            _dev_tensor(x, "x"), _dev_tensor(gy, "gy", x.dtype), _dev_tensor(w, "w", x.dtype),
+            ctypes.byref(shape),
+            _dev_tensor(gx, "gx", x.dtype) if gx is not None else None,
+            _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
+    return gx, gW
+
+
+def wht_project(t, patch, basis_idx, out=None, stream=None):
+    """p(.) of Eq. 6: t [N,H,W,C] -> [P*r, C] of the same dtype, unnormalised."""
+    N, H, W, C = t.shape
+    idx, r = _idx_array(basis_idx)
+    if out is None:
+        out = torch.empty((N * H * W // (patch * patch) * r, C), dtype=t.dtype, device=t.device)
+    with torch.cuda.device(t.device):
+        _check(load().lbp_wht_project(_dev_tensor(t, "t"), N, H, W, C, _DTYPES[t.dtype], int(patch),
+                                      idx, r, _dev_tensor(out, "out", t.dtype), _stream_ptr(stream)))
+    return out
+
+
+def wht_unproject(coef, shape, dtype, patch, basis_idx, out=None, stream=None):
+    """p^-1(.) of Eq. 7 with the 1/patch^2 factor: coef fp32 [P*r, C] -> [N,H,W,C] of `dtype`."""
+    N, H, W, C = shape
+    idx, r = _idx_array(basis_idx)
+    if out is None:
+        out = torch.empty((N, H, W, C), dtype=dtype, device=coef.device)
+    with torch.cuda.device(coef.device):
+        _check(load().lbp_wht_unproject(_dev_tensor(coef, "coef", torch.float32), N, H, W, C,
+                                        _DTYPES[dtype], int(patch), idx, r,
+                                        _dev_tensor(out, "out", dtype), _stream_ptr(stream)))
+    return out
+
+
+def workspace_bytes(shape, patch, r):
+    return int(load().lbp_wht_workspace_bytes(ctypes.byref(shape), int(patch), int(r)))
+
+
+def set_workspace(buf):
+    """buf: a uint8 device tensor to use as workspace, or None for the internal buffer."""
+    if buf is None:
+        _check(load().lbp_set_workspace(None, 0))
+    else:
+        with torch.cuda.device(buf.device):
+            _check(load().lbp_set_workspace(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size()))
+
+
+def release_workspace():
+    _check(load().lbp_release_workspace())

@@ -1,0 +1,361 @@
+// C-ABI entry points (include/lbp_wht.h): host-side validation first, then kernel launches on
+// the caller's stream.  No torch types, no CPU fallback: without a usable device every compute
+// entry point returns LBP_ERR_HIP.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+
+#include "kernels.h"
+#include "lbp_host.h"
+
+namespace {
+
+thread_local int t_last_hip_error = 0;
+
+int hip_fail(hipError_t e)
+{
+    t_last_hip_error = (int)e;
+    (void)hipGetLastError();   // clear the sticky launch error, it has been recorded
+    return LBP_ERR_HIP;
+}
+
+constexpr int kMaxDevices = 64;
+
+struct DeviceState {
+    void *internal_ws = nullptr;
+    size_t internal_bytes = 0;
+    void *user_ws = nullptr;
+    size_t user_bytes = 0;
+    int num_cus = 0;
+};
+
+std::mutex g_mutex;
+DeviceState g_dev[kMaxDevices];
+
+// Current device and its state; LBP_ERR_HIP if there is none.
+int current_device(int *dev, DeviceState **st)
+{
+    int d = -1;
+    hipError_t e = hipGetDevice(&d);
+    if (e != hipSuccess) return hip_fail(e);
+    if (d < 0 || d >= kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (g_dev[d].num_cus == 0) {
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d);
+        if (e != hipSuccess) return hip_fail(e);
+        g_dev[d].num_cus = cus > 0 ? cus : 256;
+    }
+    *dev = d;
+    *st = &g_dev[d];
+    return LBP_OK;
+}
+
+// Workspace of at least `bytes` on the current device: the caller's if one was set, else the
+// internal grow-only buffer.
+int get_workspace(DeviceState *st, size_t bytes, char **out)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (st->user_ws) {
+        if (st->user_bytes < bytes) return LBP_ERR_WORKSPACE;
+        *out = (char *)st->user_ws;
+        return LBP_OK;
+    }
+    if (st->internal_bytes < bytes) {
+        if (st->internal_ws) {
+            // earlier calls may still be reading the old buffer on some stream
+            hipError_t e = hipDeviceSynchronize();
+            if (e != hipSuccess) return hip_fail(e);
+            e = hipFree(st->internal_ws);
+            st->internal_ws = nullptr;
+            st->internal_bytes = 0;
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        size_t want = bytes + bytes / 4;
+        hipError_t e = hipMalloc(&st->internal_ws, want);
+        if (e != hipSuccess) {
+            st->internal_ws = nullptr;
+            return hip_fail(e);
+        }
+        st->internal_bytes = want;
+    }
+    *out = (char *)st->internal_ws;
+    return LBP_OK;
+}
+
+lbp::WhtPath wht_path_from_env()
+{
+    const char *s = std::getenv("LBP_WHT_PATH");
+    if (!s) return lbp::WhtPath::kAuto;
+    if (!std::strcmp(s, "generic")) return lbp::WhtPath::kGeneric;
+    if (!std::strcmp(s, "register")) return lbp::WhtPath::kRegister;
+    return lbp::WhtPath::kAuto;
+}
+
+// Pointer, alias and alignment rules common to both backward entry points.
+int validate_buffers(const void *x, const void *gy, const void *W, const lbp_shape_t *s, void *gx,
+                     void *gW)
+{
+    if (!x || !gy || !W) return LBP_ERR_NULL;
+    if (!gx && !gW) return LBP_ERR_NULL;
+    const void *ptrs[5] = {x, gy, W, gx, gW};
+    int rc = lbp::validate_alignment(ptrs, 5);
+    if (rc) return rc;
+    size_t esz = lbp::dtype_size(s->dtype);
+    size_t M = (size_t)s->N * s->H * s->W;
+    size_t nx = M * s->Cin * esz, ngy = M * s->Cout * esz, nw = (size_t)s->Cout * s->Cin * esz;
+    size_t ngx = nx, ngw = (size_t)s->Cout * s->Cin * lbp::dtype_size(s->gw_dtype);
+    const void *ins[3] = {x, gy, W};
+    size_t in_bytes[3] = {nx, ngy, nw};
+    for (int i = 0; i < 3; ++i) {
+        if (lbp::ranges_overlap(gx, ngx, ins[i], in_bytes[i])) return LBP_ERR_ALIAS;
+        if (lbp::ranges_overlap(gW, ngw, ins[i], in_bytes[i])) return LBP_ERR_ALIAS;
+    }
+    if (lbp::ranges_overlap(gx, ngx, gW, ngw)) return LBP_ERR_ALIAS;
+    return LBP_OK;
+}
+
+#define LBP_HIP(expr)                                  \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return hip_fail(e_);     \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int lbp_version(void) { return 100; }
+
+const char *lbp_strerror(int code) { return lbp::status_string(code); }
+
+int lbp_last_hip_error(void) { return t_last_hip_error; }
+
+int lbp_wht_select_bases(int patch, int r, int order, int32_t *basis_idx)
+{
+    return lbp::select_bases(patch, r, order, basis_idx);
+}
+
+size_t lbp_wht_workspace_bytes(const lbp_shape_t *shape, int patch, int r)
+{
+    if (lbp::validate_shape(shape, patch) != LBP_OK) return 0;
+    if (patch != 0 && (r < 1 || r > patch * patch)) return 0;
+    lbp::WorkspacePlan ws;
+    // sized for the largest split-K factor any device could ask for at this shape
+    if (lbp::plan_workspace(shape, patch, r, 1024, &ws) != LBP_OK) return 0;
+    return ws.total;
+}
+
+int lbp_set_workspace(void *dev_ptr, size_t bytes)
+{
+    if (dev_ptr && (reinterpret_cast<uintptr_t>(dev_ptr) & 255u)) return LBP_ERR_ALIGN;
+    int dev;
+    DeviceState *st;
+    int rc = current_device(&dev, &st);
+    if (rc) return rc;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    st->user_ws = dev_ptr;
+    st->user_bytes = dev_ptr ? bytes : 0;
+    return LBP_OK;
+}
+
+int lbp_release_workspace(void)
+{
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess) {
+        (void)hipGetLastError();
+        return LBP_OK;   // no device: nothing was ever allocated
+    }
+    int prev = 0;
+    LBP_HIP(hipGetDevice(&prev));
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (int d = 0; d < count && d < kMaxDevices; ++d) {
+        if (!g_dev[d].internal_ws) continue;
+        LBP_HIP(hipSetDevice(d));
+        LBP_HIP(hipDeviceSynchronize());
+        LBP_HIP(hipFree(g_dev[d].internal_ws));
+        g_dev[d].internal_ws = nullptr;
+        g_dev[d].internal_bytes = 0;
+    }
+    LBP_HIP(hipSetDevice(prev));
+    return LBP_OK;
+}
+
+int lbp_wht_project(const void *in, int N, int H, int W, int C, int dtype, int patch,
+                    const int32_t *basis_idx, int r, void *out, void *stream)
+{
+    if (!in || !out || !basis_idx) return LBP_ERR_NULL;
+    int rc = lbp::validate_grid(N, H, W, C, dtype, patch);
+    if (rc) return rc;
+    lbp::BasisPlan plan;
+    rc = lbp::make_basis_plan(patch, basis_idx, r, &plan);
+    if (rc) return rc;
+    const void *ptrs[2] = {in, out};
+    rc = lbp::validate_alignment(ptrs, 2);
+    if (rc) return rc;
+    size_t esz = lbp::dtype_size(dtype);
+    size_t M = (size_t)N * H * W;
+    if (lbp::ranges_overlap(in, M * C * esz, out, M / (patch * patch) * r * C * esz)) return LBP_ERR_ALIAS;
+    int dev;
+    DeviceState *st;
+    rc = current_device(&dev, &st);
+    if (rc) return rc;
+    LBP_HIP(lbp::launch_project(in, out, N, H, W, C, dtype, plan, wht_path_from_env(), (hipStream_t)stream));
+    return LBP_OK;
+}
+
+int lbp_wht_unproject(const void *in, int N, int H, int W, int C, int dtype, int patch,
+                      const int32_t *basis_idx, int r, void *out, void *stream)
+{
+    if (!in || !out || !basis_idx) return LBP_ERR_NULL;
+    int rc = lbp::validate_grid(N, H, W, C, dtype, patch);
+    if (rc) return rc;
+    lbp::BasisPlan plan;
+    rc = lbp::make_basis_plan(patch, basis_idx, r, &plan);
+    if (rc) return rc;
+    const void *ptrs[2] = {in, out};
+    rc = lbp::validate_alignment(ptrs, 2);
+    if (rc) return rc;
+    size_t M = (size_t)N * H * W;
+    if (lbp::ranges_overlap(in, M / (patch * patch) * r * C * 4, out, M * C * lbp::dtype_size(dtype)))
+        return LBP_ERR_ALIAS;
+    int dev;
+    DeviceState *st;
+    rc = current_device(&dev, &st);
+    if (rc) return rc;
+    LBP_HIP(lbp::launch_unproject((const float *)in, out, N, H, W, C, dtype, plan, wht_path_from_env(),
+                                  (hipStream_t)stream));
+    return LBP_OK;
+}
+
+int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
+                     int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream)
+{
+    if (!shape || !basis_idx) return LBP_ERR_NULL;
+    if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
+    int rc = lbp::validate_shape(shape, patch);
+    if (rc) return rc;
+    lbp::BasisPlan plan;
+    rc = lbp::make_basis_plan(patch, basis_idx, r, &plan);
+    if (rc) return rc;
+    rc = validate_buffers(x, gy, W, shape, gx, gW);
+    if (rc) return rc;
+
+    int dev;
+    DeviceState *st;
+    rc = current_device(&dev, &st);
+    if (rc) return rc;
+    lbp::WorkspacePlan ws;
+    rc = lbp::plan_workspace(shape, patch, r, st->num_cus, &ws);
+    if (rc) return rc;
+    char *base = nullptr;
+    rc = get_workspace(st, ws.total, &base);
+    if (rc) return rc;
+
+    hipStream_t s = (hipStream_t)stream;
+    const lbp::WhtPath path = wht_path_from_env();
+    const int N = shape->N, H = shape->H, Wd = shape->W, Cin = shape->Cin, Cout = shape->Cout;
+    const int dt = shape->dtype;
+    const long M = (long)N * H * Wd;
+    const long Mr = M / ((long)patch * patch) * r;
+    const float inv_pp = 1.0f / (float)(patch * patch);
+    void *gy_r = base + ws.gy_r;
+    void *x_r = base + ws.x_r;
+    float *gx_r = (float *)(base + ws.gx_r);
+    float *part = (float *)(base + ws.splitk);
+
+    // g^y = WHT(gy; I)   (second statement of Algorithm 1; needed by both products)
+    LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s));
+    if (gW) {
+        // x^ = WHT(x; I), then g~w = g^w = g^y^T x^  (with the 1/p^2 of the normalisation)
+        LBP_HIP(lbp::launch_project(x, x_r, N, H, Wd, Cin, dt, plan, path, s));
+        lbp::GemmArgs g;
+        g.A = gy_r; g.B = x_r;
+        g.M = Cout; g.N = Cin; g.K = (int)Mr;
+        g.lda = Cout; g.ldb = Cin;
+        g.a_kfast = false;
+        g.dtype = dt;
+        g.splits = ws.splits_gw;
+        g.C = part;
+        LBP_HIP(lbp::launch_gemm(g, s));
+        LBP_HIP(lbp::launch_splitk_reduce(part, ws.splits_gw, (long)Cout * Cin, inv_pp, gW,
+                                          shape->gw_dtype, s));
+    }
+    if (gx) {
+        // g^x = g^y w, then g~x = WHT^-1(g^x; I)
+        lbp::GemmArgs g;
+        g.A = gy_r; g.B = W;
+        g.M = (int)Mr; g.N = Cin; g.K = Cout;
+        g.lda = Cout; g.ldb = Cin;
+        g.a_kfast = true;
+        g.dtype = dt;
+        g.splits = 1;
+        g.C = gx_r;
+        LBP_HIP(lbp::launch_gemm(g, s));
+        LBP_HIP(lbp::launch_unproject(gx_r, gx, N, H, Wd, Cin, dt, plan, path, s));
+    }
+    return LBP_OK;
+}
+
+int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
+                     void *gx, void *gW, void *stream)
+{
+    if (!shape) return LBP_ERR_NULL;
+    int rc = lbp::validate_shape(shape, 0);
+    if (rc) return rc;
+    rc = validate_buffers(x, gy, W, shape, gx, gW);
+    if (rc) return rc;
+    int dev;
+    DeviceState *st;
+    rc = current_device(&dev, &st);
+    if (rc) return rc;
+    const int Cin = shape->Cin, Cout = shape->Cout, dt = shape->dtype;
+    const long M = (long)shape->N * shape->H * shape->W;
+    lbp::WorkspacePlan ws;
+    rc = lbp::plan_workspace(shape, 0, 0, st->num_cus, &ws);
+    if (rc) return rc;
+    // gx needs an fp32 staging buffer of M x Cin when the tensors are bf16
+    size_t gx_stage = gx && dt == LBP_BF16 ? ((size_t)M * Cin * 4 + 255) / 256 * 256 : 0;
+    char *base = nullptr;
+    rc = get_workspace(st, ws.total + gx_stage, &base);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    float *part = (float *)(base + ws.splitk);
+
+    if (gW) {   // gW = gy^T x  (Eq. 2)
+        lbp::GemmArgs g;
+        g.A = gy; g.B = x;
+        g.M = Cout; g.N = Cin; g.K = (int)M;
+        g.lda = Cout; g.ldb = Cin;
+        g.a_kfast = false;
+        g.dtype = dt;
+        g.splits = ws.splits_gw;
+        g.C = part;
+        LBP_HIP(lbp::launch_gemm(g, s));
+        LBP_HIP(lbp::launch_splitk_reduce(part, ws.splits_gw, (long)Cout * Cin, 1.0f, gW,
+                                          shape->gw_dtype, s));
+    }
+    if (gx) {   // gx = gy W  (Eq. 2)
+        lbp::GemmArgs g;
+        g.A = gy; g.B = W;
+        g.M = (int)M; g.N = Cin; g.K = Cout;
+        g.lda = Cout; g.ldb = Cin;
+        g.a_kfast = true;
+        g.dtype = dt;
+        g.splits = 1;
+        if (dt == LBP_F32) {
+            g.C = (float *)gx;
+            LBP_HIP(lbp::launch_gemm(g, s));
+        } else {
+            float *stage = (float *)(base + ws.total);
+            g.C = stage;
+            LBP_HIP(lbp::launch_gemm(g, s));
+            LBP_HIP(lbp::launch_splitk_reduce(stage, 1, M * Cin, 1.0f, gx, LBP_BF16, s));
+        }
+    }
+    return LBP_OK;
+}
+
+}  // extern "C"

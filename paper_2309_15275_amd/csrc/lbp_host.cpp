@@ -1,0 +1,208 @@
+// Host-side logic: validation, basis selection (Section 3.2, Eq. 8-9), sequency -> natural
+// index conversion, workspace planning.  No HIP calls in this file.
+#include "lbp_host.h"
+
+#include <algorithm>
+#include <cstring>
+#include <tuple>
+#include <vector>
+
+namespace lbp {
+
+int patch_log2(int patch)
+{
+    switch (patch) {
+        case 2: return 1;
+        case 4: return 2;
+        case 8: return 3;
+        case 16: return 4;
+        default: return -1;
+    }
+}
+
+int sequency_to_natural(int s, int log2p)
+{
+    // Walsh function number s (s sign changes) is Sylvester row bitreverse(gray(s)).
+    unsigned gray = (unsigned)s ^ ((unsigned)s >> 1);
+    unsigned nat = 0;
+    for (int b = 0; b < log2p; ++b)
+        if (gray & (1u << b)) nat |= 1u << (log2p - 1 - b);
+    return (int)nat;
+}
+
+int select_bases(int patch, int r, int order, int32_t *basis_idx)
+{
+    if (patch_log2(patch) < 0) return LBP_ERR_PATCH;
+    if (r < 1 || r > patch * patch) return LBP_ERR_RANK;
+    if (order != LBP_ORDER_L1 && order != LBP_ORDER_LINF) return LBP_ERR_ORDER;
+    if (!basis_idx) return LBP_ERR_NULL;
+    // (shell, tie-break towards the diagonal, smaller u first, index)
+    std::vector<std::tuple<int, int, int, int>> all;
+    all.reserve((size_t)patch * patch);
+    for (int u = 0; u < patch; ++u)
+        for (int v = 0; v < patch; ++v) {
+            int sum = u + v, mx = std::max(u, v);
+            if (order == LBP_ORDER_L1)
+                all.emplace_back(sum, mx, u, u * patch + v);
+            else
+                all.emplace_back(mx, sum, u, u * patch + v);
+        }
+    std::sort(all.begin(), all.end());
+    for (int k = 0; k < r; ++k) basis_idx[k] = std::get<3>(all[(size_t)k]);
+    return LBP_OK;
+}
+
+static int trailing_zeros_capped(int v, int cap)
+{
+    int n = 0;
+    while (n < cap && !(v & (1 << n))) ++n;
+    return n;
+}
+
+int make_basis_plan(int patch, const int32_t *basis_idx, int r, BasisPlan *plan)
+{
+    int lp = patch_log2(patch);
+    if (lp < 0) return LBP_ERR_PATCH;
+    if (r < 1 || r > patch * patch) return LBP_ERR_RANK;
+    if (!basis_idx || !plan) return LBP_ERR_NULL;
+    bool seen[kMaxBases];
+    std::memset(seen, 0, sizeof seen);
+    std::memset(plan, 0, sizeof *plan);
+    plan->patch = patch;
+    plan->log2p = lp;
+    plan->r = r;
+    int mh = lp, mw = lp;
+    int nat_u[kMaxBases], nat_v[kMaxBases];
+    for (int k = 0; k < r; ++k) {
+        int idx = basis_idx[k];
+        if (idx < 0 || idx >= patch * patch || seen[idx]) return LBP_ERR_BASIS;
+        seen[idx] = true;
+        nat_u[k] = sequency_to_natural(idx / patch, lp);
+        nat_v[k] = sequency_to_natural(idx % patch, lp);
+        plan->nat[k] = (uint8_t)(nat_u[k] * patch + nat_v[k]);
+        mh = std::min(mh, trailing_zeros_capped(nat_u[k], lp));
+        mw = std::min(mw, trailing_zeros_capped(nat_v[k], lp));
+    }
+    plan->mh = mh;
+    plan->mw = mw;
+    if (patch <= 8) {
+        int wbits = lp - mw;   // bits of the pooled width index
+        for (int k = 0; k < r; ++k) {
+            int j = ((nat_u[k] >> mh) << wbits) | (nat_v[k] >> mw);
+            plan->pooled_mask |= 1ull << j;
+            plan->pooled_pos[j] = (uint8_t)k;
+        }
+    }
+    return LBP_OK;
+}
+
+size_t dtype_size(int dtype)
+{
+    return dtype == LBP_F32 ? 4 : dtype == LBP_BF16 ? 2 : 0;
+}
+
+static int channel_multiple(int dtype) { return dtype == LBP_BF16 ? 8 : 4; }
+
+int validate_grid(int N, int H, int W, int C, int dtype, int patch)
+{
+    if (dtype_size(dtype) == 0) return LBP_ERR_DTYPE;
+    if (N < 1 || H < 1 || W < 1 || C < 1) return LBP_ERR_SHAPE;
+    if (patch != 0) {
+        if (patch_log2(patch) < 0) return LBP_ERR_PATCH;
+        if (H % patch || W % patch) return LBP_ERR_SHAPE;
+    }
+    long long tokens = (long long)N * H * W;
+    if (tokens >= (1ll << 31)) return LBP_ERR_SHAPE;
+    if (C % channel_multiple(dtype)) return LBP_ERR_ALIGN;
+    return LBP_OK;
+}
+
+int validate_shape(const lbp_shape_t *s, int patch)
+{
+    if (!s) return LBP_ERR_NULL;
+    if (dtype_size(s->dtype) == 0) return LBP_ERR_DTYPE;
+    if (s->gw_dtype != LBP_F32 && s->gw_dtype != s->dtype) return LBP_ERR_DTYPE;
+    int rc = validate_grid(s->N, s->H, s->W, s->Cin, s->dtype, patch);
+    if (rc) return rc;
+    return validate_grid(s->N, s->H, s->W, s->Cout, s->dtype, patch);
+}
+
+int validate_alignment(const void *const *ptrs, int n)
+{
+    for (int i = 0; i < n; ++i)
+        if (ptrs[i] && (reinterpret_cast<uintptr_t>(ptrs[i]) & 15u)) return LBP_ERR_ALIGN;
+    return LBP_OK;
+}
+
+bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb)
+{
+    if (!a || !b || na == 0 || nb == 0) return false;
+    uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+int choose_splits(long M, long N, long K, int tile_m, int tile_n, int num_cus, int min_k)
+{
+    long tiles = ((M + tile_m - 1) / tile_m) * ((N + tile_n - 1) / tile_n);
+    if (tiles < 1) tiles = 1;
+    long by_fill = num_cus / tiles;
+    long by_k = K / min_k;
+    long s = std::min(by_fill, by_k);
+    if (s < 1) s = 1;
+    if (s > 256) s = 256;
+    return (int)s;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, WorkspacePlan *ws)
+{
+    if (!s || !ws) return LBP_ERR_NULL;
+    std::memset(ws, 0, sizeof *ws);
+    size_t esz = dtype_size(s->dtype);
+    long M = (long)s->N * s->H * s->W;
+    size_t off = 0;
+    if (patch == 0) {
+        // full-rank backward: only the split-K partial sums of gW
+        ws->splits_gx = 1;
+        ws->splits_gw = choose_splits(s->Cout, s->Cin, M, 128, 128, num_cus, 512);
+        ws->splitk = off;
+        off += align_up((size_t)ws->splits_gw * s->Cout * s->Cin * 4, 256);
+        ws->total = off;
+        return LBP_OK;
+    }
+    long Mr = M / ((long)patch * patch) * r;
+    ws->gy_r = off;
+    off += align_up((size_t)Mr * s->Cout * esz, 256);
+    ws->x_r = off;
+    off += align_up((size_t)Mr * s->Cin * esz, 256);
+    ws->gx_r = off;
+    off += align_up((size_t)Mr * s->Cin * 4, 256);
+    ws->splits_gw = choose_splits(s->Cout, s->Cin, Mr, 128, 128, num_cus, 256);
+    ws->splits_gx = 1;
+    ws->splitk = off;
+    off += align_up((size_t)ws->splits_gw * s->Cout * s->Cin * 4, 256);
+    ws->total = off;
+    return LBP_OK;
+}
+
+const char *status_string(int code)
+{
+    switch (code) {
+        case LBP_OK: return "success";
+        case LBP_ERR_NULL: return "a required pointer is NULL";
+        case LBP_ERR_SHAPE: return "bad shape: non-positive dimension, token grid not a multiple of the patch, or too many tokens";
+        case LBP_ERR_PATCH: return "patch must be 2, 4, 8 or 16";
+        case LBP_ERR_RANK: return "rank r must be in [1, patch^2]";
+        case LBP_ERR_BASIS: return "basis index out of range or listed twice";
+        case LBP_ERR_DTYPE: return "dtype or gw_dtype not recognised, or an unsupported combination";
+        case LBP_ERR_ALIAS: return "an output buffer overlaps an input or the other output";
+        case LBP_ERR_ALIGN: return "device pointers must be 16-byte aligned and channel counts a multiple of 8 (bf16) or 4 (fp32)";
+        case LBP_ERR_ORDER: return "order must be LBP_ORDER_L1 or LBP_ORDER_LINF";
+        case LBP_ERR_WORKSPACE: return "caller-provided workspace is too small";
+        case LBP_ERR_HIP: return "a HIP call failed (see lbp_last_hip_error)";
+        default: return "unknown status code";
+    }
+}
+
+}  // namespace lbp

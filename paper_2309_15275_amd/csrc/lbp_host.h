@@ -1,0 +1,79 @@
+// Host-side logic of the LBP-WHT library: argument validation, basis bookkeeping and the
+// small tables the kernels receive by value.  Plain C++, no HIP calls, so that every function
+// here can run (and be tested) on a machine without a GPU.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+
+#include "../../include/lbp_wht.h"
+
+namespace lbp {
+
+constexpr int kMaxPatch = 16;
+constexpr int kMaxBases = kMaxPatch * kMaxPatch;
+
+// Sylvester (natural-order) row index of the Walsh function with `s` sign changes, for an
+// order-2^log2p transform: the Gray code of s, bit-reversed.
+int sequency_to_natural(int s, int log2p);
+
+// -1 if p is not one of 2, 4, 8, 16, else log2(p).
+int patch_log2(int patch);
+
+// Everything the projection kernels need to know about the selected bases, passed to them by
+// value in the kernel arguments (no device copy, no host/device synchronisation).
+//
+// A 2-D basis (u, v) in sequency order is natural-order coefficient nat(u)*p + nat(v) of the
+// length-p^2 Hadamard transform of the row-major flattened patch.  If every selected nat(u) has
+// its `mh` lowest bits clear and every nat(v) its `mw` lowest bits clear, the wanted coefficients
+// equal those of the (p>>mh) x (p>>mw) transform of the patch sum-pooled over 2^mh x 2^mw token
+// groups; `pooled_mask`/`pooled_pos` describe the selection in that smaller transform.
+struct BasisPlan {
+    int32_t patch;
+    int32_t log2p;
+    int32_t r;
+    int32_t mh, mw;                 // pooling levels along H and W (0..log2p)
+    uint8_t nat[kMaxBases];         // nat[k]: natural-order index of basis k in the p^2 transform
+    uint64_t pooled_mask;           // bit j set: pooled natural coefficient j is selected (p <= 8)
+    uint8_t pooled_pos[64];         // pooled natural coefficient j -> its position k (p <= 8)
+};
+
+// Checks patch / r / basis_idx and fills `plan`.  Returns LBP_OK or the matching error.
+int make_basis_plan(int patch, const int32_t *basis_idx, int r, BasisPlan *plan);
+
+int select_bases(int patch, int r, int order, int32_t *basis_idx);
+
+// Element size in bytes of a dtype code, 0 if unknown.
+size_t dtype_size(int dtype);
+
+// Shape / dtype / divisibility checks shared by the entry points.  patch == 0 skips the patch
+// related checks (full-rank backward).
+int validate_shape(const lbp_shape_t *shape, int patch);
+
+// One tensor of a projection call.
+int validate_grid(int N, int H, int W, int C, int dtype, int patch);
+
+// LBP_ERR_ALIGN unless every listed pointer is 16-byte aligned (NULL entries are skipped).
+int validate_alignment(const void *const *ptrs, int n);
+
+// [a, a+na) and [b, b+nb) overlap?
+bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb);
+
+// Workspace layout of one backward call; offsets in bytes from the workspace base, each
+// 256-byte aligned.  Sizes of 0 mean "not used".
+struct WorkspacePlan {
+    size_t gy_r, x_r, gx_r, splitk;   // offsets
+    size_t total;                      // bytes
+    int splits_gw;                     // split-K factor of the weight-gradient product
+    int splits_gx;                     // split-K factor of the input-gradient product (full rank: 1)
+};
+
+// num_cus: compute units of the device (used to pick split-K factors); pass 256 when unknown.
+int plan_workspace(const lbp_shape_t *shape, int patch, int r, int num_cus, WorkspacePlan *ws);
+
+// Split-K factor for an M x N output with reduction length K: enough slices that the tiles fill
+// `num_cus` compute units once or twice, each slice at least `min_k` long.
+int choose_splits(long M, long N, long K, int tile_m, int tile_n, int num_cus, int min_k);
+
+const char *status_string(int code);
+
+}  // namespace lbp

@@ -1,0 +1,439 @@
+// Walsh-Hadamard projection p(.) (Eq. 6) and reverse projection p^-1(.) (Eq. 7) per token patch,
+// for gfx950.  Both are HBM-bandwidth bound: every input element is read once and every output
+// element written once, with additions and subtractions only in between (Section 3, fourth
+// property of the WHT) plus one exact power-of-two scale in the reverse direction.
+//
+// Two implementations of each direction:
+//   * "register" kernels (patch 2, 4, 8): one lane owns one 32-bit column of channels (two bf16 or
+//     one fp32) of one patch, loads the patch's p*p tokens straight into registers (every load of
+//     a wavefront covers 256 contiguous bytes), sum-pools away the butterfly stages that no
+//     selected basis needs, runs the remaining butterfly in registers and stores the r selected
+//     coefficients.  Lanes are numbered (patch, channel column) so that thin layers (few
+//     channels) still fill wavefronts: neighbouring patches of one patch-row are neighbours in
+//     memory.
+//   * "generic" kernels (any patch up to 16, any selection): the matrix form of Eq. 6 / Eq. 7,
+//     signs from the parity of popcount(natural index & token index).  Slower, used for patch 16
+//     and kept selectable for testing.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace lbp {
+namespace {
+
+struct NatTable {
+    uint8_t v[kMaxBases];
+};
+
+struct PooledSel {
+    uint64_t mask;
+    uint8_t pos[64];
+};
+
+// Decomposition of a patch number into the first token of the patch.
+struct GridGeom {
+    int Wt;        // tokens per grid row (W)
+    int HWt;       // tokens per image (H*W)
+    int PW;        // patches per grid row
+    int PHW;       // patches per image
+    int patch;
+    __device__ __forceinline__ long first_token(long q) const
+    {
+        long n = q / PHW;
+        int rem = (int)(q - n * PHW);
+        int a = rem / PW, b = rem - a * PW;
+        return n * HWt + (long)a * patch * Wt + (long)b * patch;
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// register kernels
+// ------------------------------------------------------------------------------------------
+
+// Sum-pool a P x P patch over 2^MH x 2^MW token groups, then transform the pooled patch.
+template <int P, int MH, int MW>
+__device__ __forceinline__ void pooled_transform(const float (&v)[P * P],
+                                                 float (&c)[(P >> MH) * (P >> MW)])
+{
+    constexpr int PH = P >> MH, PWd = P >> MW;
+#pragma unroll
+    for (int hh = 0; hh < PH; ++hh) {
+#pragma unroll
+        for (int ww = 0; ww < PWd; ++ww) {
+            float s = 0.f;
+#pragma unroll
+            for (int dh = 0; dh < (1 << MH); ++dh) {
+#pragma unroll
+                for (int dw = 0; dw < (1 << MW); ++dw)
+                    s += v[((hh << MH) + dh) * P + (ww << MW) + dw];
+            }
+            c[hh * PWd + ww] = s;
+        }
+    }
+    fwht_inplace<PH * PWd>(c);
+}
+
+template <int LP, int MH, int MW, bool BF16>
+__global__ __launch_bounds__(256) void wht_project_reg_kernel(const uint32_t *__restrict__ in,
+                                                              uint32_t *__restrict__ out,
+                                                              long items, int Cd, GridGeom g,
+                                                              PooledSel sel, int r)
+{
+    constexpr int P = 1 << LP;
+    constexpr int NC = (P >> MH) * (P >> MW);
+    long item = (long)blockIdx.x * 256 + threadIdx.x;
+    if (item >= items) return;
+    long q = item / Cd;
+    int cd = (int)(item - q * Cd);
+    const uint32_t *src = in + (size_t)g.first_token(q) * Cd + cd;
+
+    uint32_t raw[P * P];
+#pragma unroll
+    for (int h = 0; h < P; ++h) {
+#pragma unroll
+        for (int w = 0; w < P; ++w) raw[h * P + w] = src[((size_t)h * g.Wt + w) * Cd];
+    }
+
+    float v[P * P];
+    float c0[NC];
+#pragma unroll
+    for (int t = 0; t < P * P; ++t) v[t] = BF16 ? bf16_lo_to_f32(raw[t]) : __uint_as_float(raw[t]);
+    pooled_transform<P, MH, MW>(v, c0);
+
+    uint32_t *dst = out + (size_t)q * r * Cd + cd;
+    if (BF16) {
+        float c1[NC];
+#pragma unroll
+        for (int t = 0; t < P * P; ++t) v[t] = bf16_hi_to_f32(raw[t]);
+        pooled_transform<P, MH, MW>(v, c1);
+#pragma unroll
+        for (int j = 0; j < NC; ++j)
+            if ((sel.mask >> j) & 1ull) dst[(size_t)sel.pos[j] * Cd] = pack_bf16x2(c0[j], c1[j]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < NC; ++j)
+            if ((sel.mask >> j) & 1ull) dst[(size_t)sel.pos[j] * Cd] = __float_as_uint(c0[j]);
+    }
+}
+
+// Reverse direction: lane = (patch, 32-bit output column).  Reads the r selected fp32
+// coefficients, zero-fills the others, transforms, replicates over the pooled token groups.
+template <int LP, int MH, int MW, bool BF16>
+__global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__restrict__ in,
+                                                                uint32_t *__restrict__ out,
+                                                                long items, int Cd, GridGeom g,
+                                                                PooledSel sel, int r)
+{
+    constexpr int P = 1 << LP;
+    constexpr int PWd = P >> MW;
+    constexpr int NC = (P >> MH) * PWd;
+    constexpr float scale = 1.0f / (float)(P * P);
+    long item = (long)blockIdx.x * 256 + threadIdx.x;
+    if (item >= items) return;
+    long q = item / Cd;
+    int cd = (int)(item - q * Cd);
+    uint32_t *dst = out + (size_t)g.first_token(q) * Cd + cd;
+
+    if (BF16) {
+        const int C = Cd * 2;
+        const float2 *src = reinterpret_cast<const float2 *>(in + (size_t)q * r * C) + cd;
+        float c0[NC], c1[NC];
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            float2 t = make_float2(0.f, 0.f);
+            if ((sel.mask >> j) & 1ull) t = src[(size_t)sel.pos[j] * Cd];
+            c0[j] = t.x;
+            c1[j] = t.y;
+        }
+        fwht_inplace<NC>(c0);
+        fwht_inplace<NC>(c1);
+#pragma unroll
+        for (int h = 0; h < P; ++h) {
+#pragma unroll
+            for (int w = 0; w < P; ++w) {
+                int j = (h >> MH) * PWd + (w >> MW);
+                dst[((size_t)h * g.Wt + w) * Cd] = pack_bf16x2(c0[j] * scale, c1[j] * scale);
+            }
+        }
+    } else {
+        const float *src = in + (size_t)q * r * Cd + cd;
+        float c0[NC];
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            float t = 0.f;
+            if ((sel.mask >> j) & 1ull) t = src[(size_t)sel.pos[j] * Cd];
+            c0[j] = t;
+        }
+        fwht_inplace<NC>(c0);
+#pragma unroll
+        for (int h = 0; h < P; ++h) {
+#pragma unroll
+            for (int w = 0; w < P; ++w) {
+                int j = (h >> MH) * PWd + (w >> MW);
+                dst[((size_t)h * g.Wt + w) * Cd] = __float_as_uint(c0[j] * scale);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// generic kernels (matrix form)
+// ------------------------------------------------------------------------------------------
+
+template <bool BF16>
+struct Vec16;   // one 16-byte vector of channels as fp32 lanes
+template <>
+struct Vec16<false> {
+    static constexpr int N = 4;
+    __device__ static void load(const uint4 &u, float (&f)[4])
+    {
+        f[0] = __uint_as_float(u.x); f[1] = __uint_as_float(u.y);
+        f[2] = __uint_as_float(u.z); f[3] = __uint_as_float(u.w);
+    }
+};
+template <>
+struct Vec16<true> {
+    static constexpr int N = 8;
+    __device__ static void load(const uint4 &u, float (&f)[8])
+    {
+        f[0] = bf16_lo_to_f32(u.x); f[1] = bf16_hi_to_f32(u.x);
+        f[2] = bf16_lo_to_f32(u.y); f[3] = bf16_hi_to_f32(u.y);
+        f[4] = bf16_lo_to_f32(u.z); f[5] = bf16_hi_to_f32(u.z);
+        f[6] = bf16_lo_to_f32(u.w); f[7] = bf16_hi_to_f32(u.w);
+    }
+};
+
+__device__ __forceinline__ uint4 store_vec(const float (&f)[4])
+{
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]),
+                      __float_as_uint(f[3]));
+}
+__device__ __forceinline__ uint4 store_vec(const float (&f)[8])
+{
+    return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                      pack_bf16x2(f[6], f[7]));
+}
+
+// grid.x = patch, grid.y * blockDim.x covers the 16-byte channel vectors of a token.
+template <bool BF16>
+__global__ __launch_bounds__(128) void wht_project_generic_kernel(const uint4 *__restrict__ in,
+                                                                  uint4 *__restrict__ out, int Cv,
+                                                                  GridGeom g, NatTable nat, int r)
+{
+    constexpr int VN = Vec16<BF16>::N;
+    constexpr int KC = 4;
+    int cv = blockIdx.y * blockDim.x + threadIdx.x;
+    if (cv >= Cv) return;
+    long q = blockIdx.x;
+    int p = g.patch, pp = p * p;
+    const uint4 *src = in + (size_t)g.first_token(q) * Cv + cv;
+    for (int k0 = 0; k0 < r; k0 += KC) {
+        float acc[KC][VN];
+#pragma unroll
+        for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+            for (int e = 0; e < VN; ++e) acc[kk][e] = 0.f;
+        for (int t = 0; t < pp; ++t) {
+            int h = t / p, w = t - h * p;
+            float f[VN];
+            Vec16<BF16>::load(src[((size_t)h * g.Wt + w) * Cv], f);
+#pragma unroll
+            for (int kk = 0; kk < KC; ++kk) {
+                int k = k0 + kk < r ? k0 + kk : r - 1;
+                bool neg = __popc((unsigned)nat.v[k] & (unsigned)t) & 1;
+#pragma unroll
+                for (int e = 0; e < VN; ++e) acc[kk][e] += neg ? -f[e] : f[e];
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < KC; ++kk)
+            if (k0 + kk < r) out[((size_t)q * r + k0 + kk) * Cv + cv] = store_vec(acc[kk]);
+    }
+}
+
+// Reverse, matrix form.  Input is fp32 [P*r][C]; thread = (patch, 16-byte OUTPUT vector).
+template <bool BF16>
+__global__ __launch_bounds__(128) void wht_unproject_generic_kernel(const float *__restrict__ in,
+                                                                    uint4 *__restrict__ out, int Cv,
+                                                                    GridGeom g, NatTable nat, int r)
+{
+    constexpr int VN = Vec16<BF16>::N;
+    constexpr int TC = 4;
+    int cv = blockIdx.y * blockDim.x + threadIdx.x;
+    if (cv >= Cv) return;
+    long q = blockIdx.x;
+    int p = g.patch, pp = p * p;
+    const int C = Cv * VN;
+    const float scale = 1.0f / (float)pp;
+    const float *src = in + (size_t)q * r * C + (size_t)cv * VN;
+    uint4 *dst = out + (size_t)g.first_token(q) * Cv + cv;
+    for (int t0 = 0; t0 < pp; t0 += TC) {     // pp is a multiple of 4 for every legal patch
+        float acc[TC][VN];
+#pragma unroll
+        for (int tt = 0; tt < TC; ++tt)
+#pragma unroll
+            for (int e = 0; e < VN; ++e) acc[tt][e] = 0.f;
+        for (int k = 0; k < r; ++k) {
+            float f[VN];
+#pragma unroll
+            for (int e = 0; e < VN; e += 4) {
+                float4 t4 = *reinterpret_cast<const float4 *>(src + (size_t)k * C + e);
+                f[e] = t4.x; f[e + 1] = t4.y; f[e + 2] = t4.z; f[e + 3] = t4.w;
+            }
+#pragma unroll
+            for (int tt = 0; tt < TC; ++tt) {
+                bool neg = __popc((unsigned)nat.v[k] & (unsigned)(t0 + tt)) & 1;
+#pragma unroll
+                for (int e = 0; e < VN; ++e) acc[tt][e] += neg ? -f[e] : f[e];
+            }
+        }
+#pragma unroll
+        for (int tt = 0; tt < TC; ++tt) {
+            int t = t0 + tt;
+            int h = t / p, w = t - h * p;
+#pragma unroll
+            for (int e = 0; e < VN; ++e) acc[tt][e] *= scale;
+            dst[((size_t)h * g.Wt + w) * Cv] = store_vec(acc[tt]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// dispatch
+// ------------------------------------------------------------------------------------------
+
+GridGeom make_geom(int H, int W, int patch)
+{
+    GridGeom g;
+    g.Wt = W;
+    g.HWt = H * W;
+    g.PW = W / patch;
+    g.PHW = (H / patch) * (W / patch);
+    g.patch = patch;
+    return g;
+}
+
+template <bool UNPROJECT, int LP, int MH, int MW, bool BF16>
+void launch_reg_one(const void *in, void *out, long items, int Cd, const GridGeom &g,
+                    const PooledSel &sel, int r, hipStream_t stream)
+{
+    unsigned blocks = (unsigned)((items + 255) / 256);
+    if (UNPROJECT)
+        hipLaunchKernelGGL((wht_unproject_reg_kernel<LP, MH, MW, BF16>), dim3(blocks), dim3(256), 0,
+                           stream, (const float *)in, (uint32_t *)out, items, Cd, g, sel, r);
+    else
+        hipLaunchKernelGGL((wht_project_reg_kernel<LP, MH, MW, BF16>), dim3(blocks), dim3(256), 0,
+                           stream, (const uint32_t *)in, (uint32_t *)out, items, Cd, g, sel, r);
+}
+
+template <bool UNPROJECT, int LP, int MH, bool BF16>
+void launch_reg_mw(int mw, const void *in, void *out, long items, int Cd, const GridGeom &g,
+                   const PooledSel &sel, int r, hipStream_t s)
+{
+    switch (mw) {
+        case 0: launch_reg_one<UNPROJECT, LP, MH, 0, BF16>(in, out, items, Cd, g, sel, r, s); break;
+        case 1: launch_reg_one<UNPROJECT, LP, MH, (LP >= 1 ? 1 : 0), BF16>(in, out, items, Cd, g, sel, r, s); break;
+        case 2: launch_reg_one<UNPROJECT, LP, MH, (LP >= 2 ? 2 : 0), BF16>(in, out, items, Cd, g, sel, r, s); break;
+        default: launch_reg_one<UNPROJECT, LP, MH, (LP >= 3 ? 3 : 0), BF16>(in, out, items, Cd, g, sel, r, s); break;
+    }
+}
+
+template <bool UNPROJECT, int LP, bool BF16>
+void launch_reg_mh(int mh, int mw, const void *in, void *out, long items, int Cd, const GridGeom &g,
+                   const PooledSel &sel, int r, hipStream_t s)
+{
+    switch (mh) {
+        case 0: launch_reg_mw<UNPROJECT, LP, 0, BF16>(mw, in, out, items, Cd, g, sel, r, s); break;
+        case 1: launch_reg_mw<UNPROJECT, LP, (LP >= 1 ? 1 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, s); break;
+        case 2: launch_reg_mw<UNPROJECT, LP, (LP >= 2 ? 2 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, s); break;
+        default: launch_reg_mw<UNPROJECT, LP, (LP >= 3 ? 3 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, s); break;
+    }
+}
+
+template <bool UNPROJECT>
+hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int dtype,
+                      const BasisPlan &plan, hipStream_t s)
+{
+    const bool bf16 = dtype == LBP_BF16;
+    const int Cd = bf16 ? C / 2 : C;
+    const long Q = (long)N * (H / plan.patch) * (W / plan.patch);
+    const long items = Q * Cd;
+    GridGeom g = make_geom(H, W, plan.patch);
+    PooledSel sel;
+    sel.mask = plan.pooled_mask;
+    for (int j = 0; j < 64; ++j) sel.pos[j] = plan.pooled_pos[j];
+    // mh <= log2p and mw <= log2p always hold for a plan made by make_basis_plan
+    const int mh = plan.mh, mw = plan.mw, r = plan.r;
+    switch (plan.log2p) {
+        case 1:
+            if (bf16) launch_reg_mh<UNPROJECT, 1, true>(mh, mw, in, out, items, Cd, g, sel, r, s);
+            else launch_reg_mh<UNPROJECT, 1, false>(mh, mw, in, out, items, Cd, g, sel, r, s);
+            break;
+        case 2:
+            if (bf16) launch_reg_mh<UNPROJECT, 2, true>(mh, mw, in, out, items, Cd, g, sel, r, s);
+            else launch_reg_mh<UNPROJECT, 2, false>(mh, mw, in, out, items, Cd, g, sel, r, s);
+            break;
+        case 3:
+            if (bf16) launch_reg_mh<UNPROJECT, 3, true>(mh, mw, in, out, items, Cd, g, sel, r, s);
+            else launch_reg_mh<UNPROJECT, 3, false>(mh, mw, in, out, items, Cd, g, sel, r, s);
+            break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <bool UNPROJECT>
+hipError_t launch_generic(const void *in, void *out, int N, int H, int W, int C, int dtype,
+                          const BasisPlan &plan, hipStream_t s)
+{
+    const bool bf16 = dtype == LBP_BF16;
+    const int Cv = bf16 ? C / 8 : C / 4;
+    const long Q = (long)N * (H / plan.patch) * (W / plan.patch);
+    GridGeom g = make_geom(H, W, plan.patch);
+    NatTable nat;
+    for (int k = 0; k < kMaxBases; ++k) nat.v[k] = plan.nat[k];
+    dim3 grid((unsigned)Q, (unsigned)((Cv + 127) / 128));
+    if (UNPROJECT) {
+        if (bf16)
+            hipLaunchKernelGGL(wht_unproject_generic_kernel<true>, grid, dim3(128), 0, s,
+                               (const float *)in, (uint4 *)out, Cv, g, nat, plan.r);
+        else
+            hipLaunchKernelGGL(wht_unproject_generic_kernel<false>, grid, dim3(128), 0, s,
+                               (const float *)in, (uint4 *)out, Cv, g, nat, plan.r);
+    } else {
+        if (bf16)
+            hipLaunchKernelGGL(wht_project_generic_kernel<true>, grid, dim3(128), 0, s,
+                               (const uint4 *)in, (uint4 *)out, Cv, g, nat, plan.r);
+        else
+            hipLaunchKernelGGL(wht_project_generic_kernel<false>, grid, dim3(128), 0, s,
+                               (const uint4 *)in, (uint4 *)out, Cv, g, nat, plan.r);
+    }
+    return hipGetLastError();
+}
+
+bool use_register_path(const BasisPlan &plan, WhtPath path)
+{
+    if (plan.patch > 8) return false;
+    return path != WhtPath::kGeneric;
+}
+
+}  // namespace
+
+hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
+                          const BasisPlan &plan, WhtPath path, hipStream_t stream)
+{
+    if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
+    if (use_register_path(plan, path))
+        return launch_reg<false>(in, out, N, H, W, C, dtype, plan, stream);
+    return launch_generic<false>(in, out, N, H, W, C, dtype, plan, stream);
+}
+
+hipError_t launch_unproject(const float *in, void *out, int N, int H, int W, int C, int dtype,
+                            const BasisPlan &plan, WhtPath path, hipStream_t stream)
+{
+    if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
+    if (use_register_path(plan, path))
+        return launch_reg<true>(in, out, N, H, W, C, dtype, plan, stream);
+    return launch_generic<true>(in, out, N, H, W, C, dtype, plan, stream);
+}
+
+}  // namespace lbp

@@ -1,0 +1,121 @@
+"""CPU-only tests of the library's host side: it loads without a GPU, exports every symbol the
+header declares, selects bases bit-exactly like the oracle, and reports every argument error
+before touching the device (so garbage device pointers are safe to pass here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2309_15275_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2309_15275_amd import build
+        build.build(verbose=False)
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "lbp_wht.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b((?:lbp_|full_bp_)\w+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_selection_is_bit_exact_against_the_oracle(lib):
+    for p in (2, 4, 8, 16):
+        for order in ("l1", "linf"):
+            for r in range(1, p * p + 1):
+                assert binding.select_bases(p, r, order) == oracle.select_bases(p, r, order).tolist()
+
+
+def test_selection_errors(lib):
+    buf = (ctypes.c_int32 * 4)()
+    assert lib.lbp_wht_select_bases(3, 1, 0, buf) == -3
+    assert lib.lbp_wht_select_bases(32, 1, 0, buf) == -3
+    assert lib.lbp_wht_select_bases(8, 0, 0, buf) == -4
+    assert lib.lbp_wht_select_bases(8, 65, 0, buf) == -4
+    assert lib.lbp_wht_select_bases(8, 4, 2, buf) == -9
+    assert lib.lbp_wht_select_bases(8, 4, 0, None) == -1
+
+
+P = ctypes.c_void_p
+X, GY, W_, GX, GW = 0x10000000, 0x20000000, 0x30000000, 0x40000000, 0x50000000   # never dereferenced
+
+
+def call_backward(lib, shape=None, patch=8, idx=(0, 1, 8, 9), r=None, x=X, gy=GY, w=W_, gx=GX, gw=GW):
+    shape = shape or binding.LbpShape(2, 16, 16, 64, 128, 1, 0)
+    arr = (ctypes.c_int32 * max(len(idx), 1))(*idx)
+    return lib.lbp_wht_backward(P(x) if x else None, P(gy) if gy else None, P(w) if w else None,
+                                ctypes.byref(shape), patch, arr, len(idx) if r is None else r,
+                                P(gx) if gx else None, P(gw) if gw else None, None)
+
+
+def test_backward_argument_errors_are_reported_before_any_device_work(lib):
+    S = binding.LbpShape
+    assert call_backward(lib, x=0) == -1
+    assert call_backward(lib, gx=0, gw=0) == -1
+    assert call_backward(lib, shape=S(0, 16, 16, 64, 128, 1, 0)) == -2
+    assert call_backward(lib, shape=S(2, 12, 16, 64, 128, 1, 0)) == -2           # H % patch
+    assert call_backward(lib, shape=S(2, 16, 20, 64, 128, 1, 0)) == -2           # W % patch
+    assert call_backward(lib, shape=S(1 << 15, 1 << 8, 1 << 8, 8, 8, 1, 0)) == -2  # 2^31 tokens
+    assert call_backward(lib, patch=3) == -3
+    assert call_backward(lib, patch=32) == -3
+    assert call_backward(lib, r=0) == -4
+    assert call_backward(lib, idx=tuple(range(65)), r=65) == -4
+    assert call_backward(lib, idx=(0, 1, 1, 9)) == -5
+    assert call_backward(lib, idx=(0, 1, 64, 9)) == -5
+    assert call_backward(lib, idx=(0, -1, 8, 9)) == -5
+    assert call_backward(lib, shape=S(2, 16, 16, 64, 128, 7, 0)) == -6
+    assert call_backward(lib, shape=S(2, 16, 16, 64, 128, 0, 1)) == -6           # bf16 gW of fp32 tensors
+    assert call_backward(lib, gx=X) == -7
+    assert call_backward(lib, gw=GY + 64) == -7
+    assert call_backward(lib, gx=GW) == -7
+    assert call_backward(lib, x=X + 2) == -8
+    assert call_backward(lib, shape=S(2, 16, 16, 60, 128, 1, 0)) == -8           # Cin % 8 (bf16)
+    assert call_backward(lib, shape=S(2, 16, 16, 64, 126, 0, 0)) == -8           # Cout % 4 (fp32)
+
+
+def test_full_bp_and_projection_argument_errors(lib):
+    S = binding.LbpShape
+    sh = S(2, 16, 16, 64, 128, 1, 0)
+    assert lib.full_bp_backward(None, P(GY), P(W_), ctypes.byref(sh), P(GX), P(GW), None) == -1
+    assert lib.full_bp_backward(P(X), P(GY), P(W_), None, P(GX), P(GW), None) == -1
+    assert lib.full_bp_backward(P(X), P(GY), P(W_), ctypes.byref(sh), P(X), P(GW), None) == -7
+    idx = (ctypes.c_int32 * 2)(0, 1)
+    assert lib.lbp_wht_project(None, 2, 16, 16, 64, 1, 8, idx, 2, P(GX), None) == -1
+    assert lib.lbp_wht_project(P(X), 2, 16, 16, 64, 1, 8, idx, 2, P(X), None) == -7
+    assert lib.lbp_wht_project(P(X), 2, 16, 16, 64, 1, 5, idx, 2, P(GX), None) == -3
+    assert lib.lbp_wht_project(P(X), 2, 16, 12, 64, 1, 8, idx, 2, P(GX), None) == -2
+    assert lib.lbp_wht_unproject(P(X), 2, 16, 16, 64, 9, 8, idx, 2, P(GX), None) == -6
+    assert lib.lbp_wht_unproject(P(X), 2, 16, 16, 64, 1, 8, idx, 3, P(GX), None) in (-5, -4)
+
+
+def test_no_cpu_fallback_without_a_device(lib):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    assert call_backward(lib) == -11           # valid arguments, no device: HIP error, not a result
+    assert lib.lbp_last_hip_error() != 0
+
+
+def test_workspace_bytes_and_strerror(lib):
+    sh = binding.LbpShape(64, 16, 16, 768, 3072, 1, 0)
+    need = binding.workspace_bytes(sh, 8, 8)
+    Mr = 64 * 256 // 64 * 8
+    assert need >= Mr * (3072 + 768) * 2 + Mr * 768 * 4 + 3072 * 768 * 4
+    assert binding.workspace_bytes(binding.LbpShape(64, 16, 16, 768, 3072, 5, 0), 8, 8) == 0
+    assert binding.workspace_bytes(sh, 8, 0) == 0
+    assert binding.workspace_bytes(sh, 0, 0) > 0
+    for code in range(0, -12, -1):
+        assert binding.strerror(code) and "unknown status" not in binding.strerror(code)
+    assert "unknown status" in binding.strerror(-99)
