@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liblbpwht.so")
 
-SOURCES = ["lbp_host.cpp", "wht_kernels.hip", "gemm_kernels.hip", "lbp_api.hip"]
+SOURCES = ["lbp_host.cpp", "wht_kernels.hip", "gemm_kernels.hip", "gemm_mfma.hip", "lbp_api.hip"]
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions on this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

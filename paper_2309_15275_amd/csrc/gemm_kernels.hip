@@ -1,16 +1,16 @@
-// Matrix products of the backward pass on gfx950:
+// Matrix products of the backward pass on gfx950, the plain kernels:
 //   gx_r = gy_r * W      (Algorithm 1, fourth statement)    A stored [M][K], B stored [K][N]
 //   gW   = gy_r^T * x_r  (Algorithm 1, third statement)     A stored [K][M], B stored [K][N]
 // and the same two shapes at full rank for Eq. 2.  B is always stored with the reduction index
 // as its slow axis (W is [Cout][Cin], x_r is [rows][Cin]), A either way.
 //
-// bf16 operands: 128x128x32 workgroup tiles, four wavefronts in a 2x2 arrangement, each owning a
-// 64x64 block as 2x2 v_mfma_f32_32x32x16_bf16 tiles with fp32 accumulators.  Global loads are
-// 16-byte vectors prefetched into registers one tile ahead of the matrix-core work; operands
-// whose reduction index is the slow axis are transposed on their way out of LDS.
-// fp32 operands: a plain 64x64x16 FMA kernel (used by the fp32 exactness configuration only).
+// fp32 operands: a 64x64x16 FMA kernel (the fp32 path exists for exactness checks, not speed).
+// bf16 operands, "simple" path: 128x128x32 tiles with v_mfma_f32_32x32x16_bf16 and element-wise
+// LDS transposition.  It is the slow, easy-to-read cross-check of the tuned kernel in
+// gemm_mfma.hip and is only used when asked for.
 // Split-K: slice z of the reduction writes its own fp32 partial result; a second kernel sums the
-// slices in a fixed order, so results do not depend on scheduling.
+// slices in a fixed order, so results do not depend on scheduling.  This file also holds the
+// dispatcher between the implementations.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -32,6 +32,7 @@ struct GemmDev {
     int M, N, K;
     long lda, ldb;
     int k_per_split;     // multiple of BK
+    float scale;
 };
 
 __device__ __forceinline__ uint4 load16_or_zero(const unsigned short *p, bool ok)
@@ -40,7 +41,7 @@ __device__ __forceinline__ uint4 load16_or_zero(const unsigned short *p, bool ok
 }
 
 template <bool A_KFAST>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDev g)
+__global__ __launch_bounds__(256) void gemm_bf16_simple_kernel(GemmDev g)
 {
     __shared__ __attribute__((aligned(16))) unsigned short As[A_KFAST ? BM * LDA_KFAST : BK * LD_KSLOW];
     __shared__ __attribute__((aligned(16))) unsigned short Bs[BK * LD_KSLOW];
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDev g)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     int row = m0 + wm * 64 + mi * 32 + grp * 8 + kg * 4 + e;
-                    if (row < g.M && col < g.N) Cz[(size_t)row * g.N + col] = acc[mi][ni][grp * 4 + e];
+                    if (row < g.M && col < g.N) Cz[(size_t)row * g.N + col] = acc[mi][ni][grp * 4 + e] * g.scale;
                 }
         }
 }
@@ -164,6 +165,7 @@ struct GemmDevF32 {
     int M, N, K;
     long lda, ldb;
     int k_per_split;
+    float scale;
 };
 
 template <bool A_KFAST>
@@ -217,7 +219,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDevF32 g)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             int col = n0 + tx * 4 + j;
-            if (row < g.M && col < g.N) Cz[(size_t)row * g.N + col] = acc[i][j];
+            if (row < g.M && col < g.N) Cz[(size_t)row * g.N + col] = acc[i][j] * g.scale;
         }
     }
 }
@@ -246,27 +248,36 @@ int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 }  // namespace
 
-hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream)
+hipError_t launch_gemm(const GemmArgs &a, GemmPath path, hipStream_t stream)
 {
-    if (a.M < 1 || a.N < 1 || a.K < 1 || a.splits < 1) return hipErrorInvalidValue;
+    if (a.M < 1 || a.N < 1 || a.K < 1 || a.splits < 1 || !a.A || !a.B || !a.C) return hipErrorInvalidValue;
+    if (a.dtype == LBP_BF16 && path != GemmPath::kSimple) return launch_gemm_mfma(a, stream);
+    return launch_gemm_simple(a, stream);
+}
+
+hipError_t launch_gemm_simple(const GemmArgs &a, hipStream_t stream)
+{
+    if (a.out != GemmOut::kF32) return hipErrorInvalidValue;   // the plain kernels only store fp32
     if (a.dtype == LBP_BF16) {
         // 16-byte vector loads: the fast axis of every operand must be a multiple of 8 elements
         if (a.N % 8 || a.ldb % 8 || a.lda % 8 || (a.a_kfast ? a.K % 8 : a.M % 8)) return hipErrorInvalidValue;
         GemmDev g;
         g.A = (const unsigned short *)a.A;
         g.B = (const unsigned short *)a.B;
-        g.C = a.C;
+        g.C = (float *)a.C;
+        g.scale = a.scale;
         g.M = a.M; g.N = a.N; g.K = a.K;
         g.lda = a.lda; g.ldb = a.ldb;
         g.k_per_split = round_up((a.K + a.splits - 1) / a.splits, BK);
         dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM, a.splits);
-        if (a.a_kfast) hipLaunchKernelGGL(gemm_bf16_kernel<true>, grid, dim3(256), 0, stream, g);
-        else hipLaunchKernelGGL(gemm_bf16_kernel<false>, grid, dim3(256), 0, stream, g);
+        if (a.a_kfast) hipLaunchKernelGGL(gemm_bf16_simple_kernel<true>, grid, dim3(256), 0, stream, g);
+        else hipLaunchKernelGGL(gemm_bf16_simple_kernel<false>, grid, dim3(256), 0, stream, g);
     } else if (a.dtype == LBP_F32) {
         GemmDevF32 g;
         g.A = (const float *)a.A;
         g.B = (const float *)a.B;
-        g.C = a.C;
+        g.C = (float *)a.C;
+        g.scale = a.scale;
         g.M = a.M; g.N = a.N; g.K = a.K;
         g.lda = a.lda; g.ldb = a.ldb;
         g.k_per_split = round_up((a.K + a.splits - 1) / a.splits, FK);

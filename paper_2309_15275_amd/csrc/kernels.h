@@ -9,6 +9,7 @@ namespace lbp {
 // Which implementation of a step to use.  kAuto picks the fastest one that supports the shape;
 // the others exist so that tests can run every kernel on every shape it supports.
 enum class WhtPath { kAuto = 0, kGeneric = 1, kRegister = 2 };
+enum class GemmPath { kAuto = 0, kSimple = 1 };
 
 // p(.) of Eq. 6 per patch: in [N][H][W][C] -> out [P*r][C], both of `dtype`.
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
@@ -18,26 +19,45 @@ hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C,
 hipError_t launch_unproject(const float *in, void *out, int N, int H, int W, int C, int dtype,
                             const BasisPlan &plan, WhtPath path, hipStream_t stream);
 
+// What a matrix product does with its accumulators.
+enum class GemmOut {
+    kF32 = 0,        // C[z][M][N] fp32 = scale * partial product of split-K slice z
+    kBF16 = 1,       // C[M][N] bf16 = scale * product            (splits must be 1)
+    kUnproject = 2   // rows of the product are (patch, basis) pairs: apply p^-1(.) of Eq. 7 per
+                     // patch in the epilogue and write bf16 tokens [N][H][W][Ncols]   (splits 1)
+};
+
 // Operand descriptions for the matrix products.  All matrices are row-major and dense along
 // their fast axis; `ld` is the row pitch in elements.
 //   a_kfast  true : A is stored [M][K] (K contiguous)      false: A is stored [K][M]
 //   B is always stored [K][N] (N contiguous).
 struct GemmArgs {
-    const void *A;
-    const void *B;
-    int M, N, K;
-    long lda, ldb;
-    bool a_kfast;
-    int dtype;          // LBP_F32 or LBP_BF16 operands; accumulation is fp32 in both cases
-    int splits;         // split-K slices; slice z writes C + z*M*N (fp32), unscaled
-    float *C;           // fp32 output [splits][M][N]
+    const void *A = nullptr;
+    const void *B = nullptr;
+    int M = 0, N = 0, K = 0;
+    long lda = 0, ldb = 0;
+    bool a_kfast = true;
+    int dtype = LBP_BF16;      // operand type; accumulation is fp32
+    int splits = 1;            // split-K slices
+    GemmOut out = GemmOut::kF32;
+    void *C = nullptr;
+    float scale = 1.0f;
+    // kUnproject only: token grid of one image and the selected bases
+    int grid_h = 0, grid_w = 0;
+    const BasisPlan *plan = nullptr;
 };
 
-// C[z] = A[:, Kz] * B[Kz, :] for every split-K slice z.
-hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream);
+// True if launch_gemm supports GemmOut::kUnproject for this selection and dtype.
+bool gemm_can_fuse_unproject(const BasisPlan &plan, int dtype, GemmPath path);
+
+hipError_t launch_gemm(const GemmArgs &g, GemmPath path, hipStream_t stream);
 
 // out[i] = scale * sum_z part[z][i], i < count (count % 4 == 0), written as `out_dtype`.
 hipError_t launch_splitk_reduce(const float *part, int splits, long count, float scale, void *out,
                                 int out_dtype, hipStream_t stream);
+
+// Implementation hooks between the two GEMM source files.
+hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t stream);
+hipError_t launch_gemm_simple(const GemmArgs &g, hipStream_t stream);
 
 }  // namespace lbp

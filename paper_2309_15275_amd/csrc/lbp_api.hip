@@ -85,6 +85,25 @@ int get_workspace(DeviceState *st, size_t bytes, char **out)
     return LBP_OK;
 }
 
+lbp::GemmPath gemm_path_from_env()
+{
+    const char *s = std::getenv("LBP_GEMM_PATH");
+    if (s && !std::strcmp(s, "simple")) return lbp::GemmPath::kSimple;
+    return lbp::GemmPath::kAuto;
+}
+
+// LBP_FUSE_UNPROJECT=0 keeps the reverse projection a kernel of its own (for testing).
+bool fuse_unproject_from_env()
+{
+    const char *s = std::getenv("LBP_FUSE_UNPROJECT");
+    return !(s && !std::strcmp(s, "0"));
+}
+
+// gW = scale * A^T-style product with split-K: direct store when one slice suffices and the
+// kernel can write the output type, otherwise fp32 partial sums and a fixed-order reduction.
+int weight_gradient(const void *A, const void *B, int Cout, int Cin, long K, int dtype, int gw_dtype,
+                    int splits, float scale, float *part, void *gW, lbp::GemmPath gpath, hipStream_t s);
+
 lbp::WhtPath wht_path_from_env()
 {
     const char *s = std::getenv("LBP_WHT_PATH");
@@ -122,6 +141,33 @@ int validate_buffers(const void *x, const void *gy, const void *W, const lbp_sha
         hipError_t e_ = (expr);                        \
         if (e_ != hipSuccess) return hip_fail(e_);     \
     } while (0)
+
+int weight_gradient(const void *A, const void *B, int Cout, int Cin, long K, int dtype, int gw_dtype,
+                    int splits, float scale, float *part, void *gW, lbp::GemmPath gpath, hipStream_t s)
+{
+    lbp::GemmArgs g;
+    g.A = A; g.B = B;
+    g.M = Cout; g.N = Cin; g.K = (int)K;
+    g.lda = Cout; g.ldb = Cin;
+    g.a_kfast = false;
+    g.dtype = dtype;
+    const bool mfma = dtype == LBP_BF16 && gpath != lbp::GemmPath::kSimple;
+    if (splits == 1 && (gw_dtype == LBP_F32 || mfma)) {
+        g.splits = 1;
+        g.out = gw_dtype == LBP_F32 ? lbp::GemmOut::kF32 : lbp::GemmOut::kBF16;
+        g.C = gW;
+        g.scale = scale;
+        LBP_HIP(lbp::launch_gemm(g, gpath, s));
+        return LBP_OK;
+    }
+    g.splits = splits;
+    g.out = lbp::GemmOut::kF32;
+    g.C = part;
+    g.scale = 1.0f;
+    LBP_HIP(lbp::launch_gemm(g, gpath, s));
+    LBP_HIP(lbp::launch_splitk_reduce(part, splits, (long)Cout * Cin, scale, gW, gw_dtype, s));
+    return LBP_OK;
+}
 
 }  // namespace
 
@@ -268,23 +314,17 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
 
     // g^y = WHT(gy; I)   (second statement of Algorithm 1; needed by both products)
     LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s));
+    const lbp::GemmPath gpath = gemm_path_from_env();
     if (gW) {
         // x^ = WHT(x; I), then g~w = g^w = g^y^T x^  (with the 1/p^2 of the normalisation)
         LBP_HIP(lbp::launch_project(x, x_r, N, H, Wd, Cin, dt, plan, path, s));
-        lbp::GemmArgs g;
-        g.A = gy_r; g.B = x_r;
-        g.M = Cout; g.N = Cin; g.K = (int)Mr;
-        g.lda = Cout; g.ldb = Cin;
-        g.a_kfast = false;
-        g.dtype = dt;
-        g.splits = ws.splits_gw;
-        g.C = part;
-        LBP_HIP(lbp::launch_gemm(g, s));
-        LBP_HIP(lbp::launch_splitk_reduce(part, ws.splits_gw, (long)Cout * Cin, inv_pp, gW,
-                                          shape->gw_dtype, s));
+        rc = weight_gradient(gy_r, x_r, Cout, Cin, Mr, dt, shape->gw_dtype, ws.splits_gw, inv_pp, part,
+                             gW, gpath, s);
+        if (rc) return rc;
     }
     if (gx) {
-        // g^x = g^y w, then g~x = WHT^-1(g^x; I)
+        // g^x = g^y w, then g~x = WHT^-1(g^x; I): fused into the product's epilogue when the
+        // kernel supports the selection, else through an fp32 buffer and a kernel of its own
         lbp::GemmArgs g;
         g.A = gy_r; g.B = W;
         g.M = (int)Mr; g.N = Cin; g.K = Cout;
@@ -292,9 +332,18 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
         g.a_kfast = true;
         g.dtype = dt;
         g.splits = 1;
-        g.C = gx_r;
-        LBP_HIP(lbp::launch_gemm(g, s));
-        LBP_HIP(lbp::launch_unproject(gx_r, gx, N, H, Wd, Cin, dt, plan, path, s));
+        if (fuse_unproject_from_env() && lbp::gemm_can_fuse_unproject(plan, dt, gpath)) {
+            g.out = lbp::GemmOut::kUnproject;
+            g.C = gx;
+            g.grid_h = H; g.grid_w = Wd;
+            g.plan = &plan;
+            LBP_HIP(lbp::launch_gemm(g, gpath, s));
+        } else {
+            g.out = lbp::GemmOut::kF32;
+            g.C = gx_r;
+            LBP_HIP(lbp::launch_gemm(g, gpath, s));
+            LBP_HIP(lbp::launch_unproject(gx_r, gx, N, H, Wd, Cin, dt, plan, path, s));
+        }
     }
     return LBP_OK;
 }
@@ -316,26 +365,20 @@ int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_sha
     lbp::WorkspacePlan ws;
     rc = lbp::plan_workspace(shape, 0, 0, st->num_cus, &ws);
     if (rc) return rc;
-    // gx needs an fp32 staging buffer of M x Cin when the tensors are bf16
-    size_t gx_stage = gx && dt == LBP_BF16 ? ((size_t)M * Cin * 4 + 255) / 256 * 256 : 0;
+    // the plain bf16 kernel needs an fp32 staging buffer of M x Cin for gx
+    size_t gx_stage = gx && dt == LBP_BF16 && gemm_path_from_env() == lbp::GemmPath::kSimple
+                          ? ((size_t)M * Cin * 4 + 255) / 256 * 256 : 0;
     char *base = nullptr;
     rc = get_workspace(st, ws.total + gx_stage, &base);
     if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     float *part = (float *)(base + ws.splitk);
 
+    const lbp::GemmPath gpath = gemm_path_from_env();
     if (gW) {   // gW = gy^T x  (Eq. 2)
-        lbp::GemmArgs g;
-        g.A = gy; g.B = x;
-        g.M = Cout; g.N = Cin; g.K = (int)M;
-        g.lda = Cout; g.ldb = Cin;
-        g.a_kfast = false;
-        g.dtype = dt;
-        g.splits = ws.splits_gw;
-        g.C = part;
-        LBP_HIP(lbp::launch_gemm(g, s));
-        LBP_HIP(lbp::launch_splitk_reduce(part, ws.splits_gw, (long)Cout * Cin, 1.0f, gW,
-                                          shape->gw_dtype, s));
+        rc = weight_gradient(gy, x, Cout, Cin, M, dt, shape->gw_dtype, ws.splits_gw, 1.0f, part, gW,
+                             gpath, s);
+        if (rc) return rc;
     }
     if (gx) {   // gx = gy W  (Eq. 2)
         lbp::GemmArgs g;
@@ -346,12 +389,19 @@ int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_sha
         g.dtype = dt;
         g.splits = 1;
         if (dt == LBP_F32) {
-            g.C = (float *)gx;
-            LBP_HIP(lbp::launch_gemm(g, s));
+            g.out = lbp::GemmOut::kF32;
+            g.C = gx;
+            LBP_HIP(lbp::launch_gemm(g, gpath, s));
+        } else if (gpath != lbp::GemmPath::kSimple) {
+            g.out = lbp::GemmOut::kBF16;
+            g.C = gx;
+            LBP_HIP(lbp::launch_gemm(g, gpath, s));
         } else {
+            // the plain bf16 kernel only stores fp32: stage and convert
             float *stage = (float *)(base + ws.total);
+            g.out = lbp::GemmOut::kF32;
             g.C = stage;
-            LBP_HIP(lbp::launch_gemm(g, s));
+            LBP_HIP(lbp::launch_gemm(g, gpath, s));
             LBP_HIP(lbp::launch_splitk_reduce(stage, 1, M * Cin, 1.0f, gx, LBP_BF16, s));
         }
     }

@@ -1,0 +1,57 @@
+// Device-side pieces of the Walsh-Hadamard projections that more than one kernel file uses:
+// the per-launch tables passed by value and the pooled in-register transform.
+#pragma once
+#include "device_utils.h"
+#include "lbp_host.h"
+
+namespace lbp {
+
+struct NatTable {
+    uint8_t v[kMaxBases];
+};
+
+struct PooledSel {
+    uint64_t mask;
+    uint8_t pos[64];
+};
+
+// Decomposition of a patch number into the first token of the patch.
+struct GridGeom {
+    int Wt;        // tokens per grid row (W)
+    int HWt;       // tokens per image (H*W)
+    int PW;        // patches per grid row
+    int PHW;       // patches per image
+    int patch;
+    __device__ __forceinline__ long first_token(long q) const
+    {
+        long n = q / PHW;
+        int rem = (int)(q - n * PHW);
+        int a = rem / PW, b = rem - a * PW;
+        return n * HWt + (long)a * patch * Wt + (long)b * patch;
+    }
+};
+
+// Sum-pool a P x P patch over 2^MH x 2^MW token groups, then transform the pooled patch.
+template <int P, int MH, int MW>
+__device__ __forceinline__ void pooled_transform(const float (&v)[P * P],
+                                                 float (&c)[(P >> MH) * (P >> MW)])
+{
+    constexpr int PH = P >> MH, PWd = P >> MW;
+#pragma unroll
+    for (int hh = 0; hh < PH; ++hh) {
+#pragma unroll
+        for (int ww = 0; ww < PWd; ++ww) {
+            float s = 0.f;
+#pragma unroll
+            for (int dh = 0; dh < (1 << MH); ++dh) {
+#pragma unroll
+                for (int dw = 0; dw < (1 << MW); ++dw)
+                    s += v[((hh << MH) + dh) * P + (ww << MW) + dw];
+            }
+            c[hh * PWd + ww] = s;
+        }
+    }
+    fwht_inplace<PH * PWd>(c);
+}
+
+}  // namespace lbp

@@ -21,7 +21,8 @@ def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     yield
-    os.environ.pop("LBP_WHT_PATH", None)
+    for var in ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT"):
+        os.environ.pop(var, None)
     torch.cuda.synchronize()
 
 
@@ -120,12 +121,24 @@ RAGGED = [
     (2, 8, 12, 40, 24, 4, 10, "l1"),
     (3, 4, 6, 16, 32, 2, 3, "l1"),
     (1, 32, 16, 24, 40, 16, 10, "l1"),      # patch 16: generic projection kernels
+    (8, 16, 16, 72, 136, 8, 10, "l1"),      # r does not divide the GEMM tile: 3 row tiles of 120
+    (2, 16, 16, 72, 136, 8, 3, "l1"),
+    (2, 16, 16, 72, 136, 8, 21, "l1"),      # no pooling possible: reverse projection not fused
+    (6, 16, 32, 264, 520, 8, 8, "l1"),      # several tiles along every GEMM dimension
 ]
 
+# (LBP_GEMM_PATH, LBP_FUSE_UNPROJECT): tuned kernels, tuned kernels with the reverse projection as
+# a kernel of its own, and the plain cross-check kernels
+VARIANTS = [("auto", "1"), ("auto", "0"), ("simple", "1")]
 
+
+@pytest.mark.parametrize("variant", range(len(VARIANTS)))
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("case", range(len(RAGGED)))
-def test_backward_matches_oracle_on_ragged_shapes(dtype, case):
+def test_backward_matches_oracle_on_ragged_shapes(dtype, case, variant):
+    if dtype == "f32" and variant > 0:
+        pytest.skip("the fp32 path has one implementation")
+    os.environ["LBP_GEMM_PATH"], os.environ["LBP_FUSE_UNPROJECT"] = VARIANTS[variant]
     N, H, W, Cin, Cout, patch, r, order = RAGGED[case]
     wl = small("ragged", N, H, W, Cin, Cout, patch, dtype, 200 + case)
     idx = oracle.select_bases(patch, r, order)
@@ -133,8 +146,17 @@ def test_backward_matches_oracle_on_ragged_shapes(dtype, case):
     assert egx <= TOL[dtype] and egw <= TOL[dtype], (egx, egw)
 
 
+def test_arbitrary_unordered_selection_backward():
+    wl = small("lhe", 3, 16, 16, 72, 136, 8, "bf16", 260)
+    for idx in ([9, 0, 18, 2, 16], [63, 1, 8], [0, 4, 32, 36]):
+        egx, egw = run_backward_case(wl, np.asarray(idx))
+        assert egx <= TOL["bf16"] and egw <= TOL["bf16"], (idx, egx, egw)
+
+
+@pytest.mark.parametrize("gemm", ["auto", "simple"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_full_rank_backward_matches_oracle(dtype):
+def test_full_rank_backward_matches_oracle(dtype, gemm):
+    os.environ["LBP_GEMM_PATH"] = gemm
     wl = small("full", 3, 16, 24, 72, 200, 8, dtype, 300)
     host, dev = device_inputs(wl)
     gx, gW = binding.full_bp_backward(dev["x"], dev["gy"], dev["w"])
