@@ -12,7 +12,9 @@ CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liblbpwht.so")
 
-SOURCES = ["lbp_host.cpp", "wht_kernels.hip", "gemm_kernels.hip", "gemm_mfma.hip", "lbp_api.hip"]
+SOURCES = ["lbp_host.cpp", "wht_kernels.hip", "gemm_kernels.hip", "gemm_mfma.hip",
+           "gemm_mfma_128x128.hip", "gemm_mfma_64x128.hip", "gemm_mfma_256x128.hip",
+           "gemm_mfma_256x256.hip", "lbp_api.hip"]
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions on this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -35,7 +37,7 @@ def _compile(src):
 def build(verbose=True):
     """Compiles every source (always) and links the shared library.  Returns its path."""
     os.makedirs(BUILD, exist_ok=True)
-    with concurrent.futures.ThreadPoolExecutor(max_workers=4) as pool:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=8) as pool:
         objs = list(pool.map(_compile, SOURCES))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     res = subprocess.run(cmd, capture_output=True, text=True)

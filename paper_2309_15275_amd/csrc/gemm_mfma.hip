@@ -1,327 +1,80 @@
-// bf16 matrix-core products of the backward pass on gfx950 (fp32 accumulation):
-//   gx_r = gy_r * W      (Algorithm 1, fourth statement)    A stored [M][K], B stored [K][N]
-//   gW   = gy_r^T * x_r  (Algorithm 1, third statement)     A stored [K][M], B stored [K][N]
-// and the same two shapes at full rank for Eq. 2.
-//
-// One workgroup owns a BM x BN tile of the output and walks the reduction in steps of 64.
-//   * Global -> registers (16-byte loads, issued one step ahead) -> LDS (two stages, one barrier
-//     per step).
-//   * Operands whose reduction index is contiguous in memory are stored [row][k] in LDS and read
-//     back with 16-byte reads.  Operands whose reduction index is the slow axis (W, and both
-//     operands of gW) are stored as they arrive, [k][row], and transposed on the way to the
-//     matrix cores with ds_read_b64_tr_b16: within each group of 16 lanes, lane i supplies the
-//     address of 4 consecutive elements of row k = i/4 starting at column 4*(i%4), and lane j
-//     receives the 4 k-values of column j.  Two such reads give the 8 consecutive k-values per
-//     lane that v_mfma_f32_32x32x16_bf16 takes.  Row pitches are padded so that both access
-//     patterns spread over all LDS banks.
-//   * Each wavefront owns a (BM/WGM) x (BN/WGN) block of 32x32 accumulator tiles.
-//   * Epilogues: scaled fp32 store (per split-K slice), scaled bf16 store, or the reverse
-//     projection of Eq. 7 fused in: the tile's rows are (patch, basis) pairs, the accumulators go
-//     through LDS, and every lane expands the r coefficients of one (patch, channel pair) into
-//     the p x p tokens of that patch with the same pooled butterfly the stand-alone kernel uses.
-//   * Workgroups are numbered so that each of the 8 XCDs (private L2 each) works on a contiguous
-//     run of tiles that share the same rows of A.
-#include "device_utils.h"
-#include "kernels.h"
-#include "wht_device.h"
+// Host side of the bf16 matrix-core GEMM: parameter set-up and the choice of tile shape.
+#include <cstdlib>
+
+#include "gemm_mfma_impl.h"
 
 namespace lbp {
 namespace {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef short i16x4_t __attribute__((ext_vector_type(4)));
-typedef short i16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
+int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-#define LBP_LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
-
-constexpr int BK = 64;
-
-enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_UNPROJECT = 2 };
-
-struct MfmaParams {
-    const unsigned short *A;
-    const unsigned short *B;
-    int M, N, K;
-    long lda, ldb;
-    int k_per_split;      // multiple of BK
-    int bm_step;          // rows of the output one tile advances by (BM, or a multiple of r below BM)
-    int tiles_m, tiles_n;
-    void *C;
-    float scale;
-    // fused reverse projection
-    GridGeom geom;
-    PooledSel sel;
-    int r, mh, mw;
-    long Q;               // number of patches
+struct TileShape {
+    int bm, bn;
+    bool fused;   // has the fused reverse-projection epilogue
+    hipError_t (*launch)(const mfma::Params &, bool, GemmOut, int, int, hipStream_t);
 };
 
-__device__ __forceinline__ uint4 ld16(const unsigned short *p, bool ok)
+const TileShape kTiles[] = {
+    {128, 128, true, mfma_tile_128x128},
+    {64, 128, true, mfma_tile_64x128},
+    {256, 128, false, mfma_tile_256x128},
+    {256, 256, false, mfma_tile_256x256},
+};
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+
+int tile_from_env()
 {
-    return ok ? *reinterpret_cast<const uint4 *>(p) : make_uint4(0u, 0u, 0u, 0u);
+    const char *s = std::getenv("LBP_GEMM_TILE");
+    if (!s || !*s) return -1;
+    int v = std::atoi(s);
+    return v >= 0 && v < kNumTiles ? v : -1;
 }
 
-// Reverse projection of one tile held in LDS as fp32 ct[row][cts]; rows are (patch, basis).
-template <int LP, int MH, int MW, int BN, int NT>
-__device__ __forceinline__ void unproject_tile(const float *ct, int cts, const MfmaParams &p, int m0,
-                                               int n0, int tid)
+// Workgroups needed by a tile shape.
+long workgroups(const TileShape &t, long M, long N, int splits)
 {
-    constexpr int P = 1 << LP;
-    constexpr int PWd = P >> MW;
-    constexpr int NC = (P >> MH) * PWd;
-    constexpr float scale = 1.0f / (float)(P * P);
-    constexpr int HALF = BN / 2;
-    const int patches = p.bm_step / p.r;
-    const int Cd = p.N >> 1;
-    for (int it = tid; it < patches * HALF; it += NT) {
-        int pt = it / HALF, cp = it - pt * HALF;
-        long q = (long)(m0 / p.r) + pt;
-        if (q >= p.Q || n0 + 2 * cp >= p.N) continue;
-        const float *src = ct + (size_t)(pt * p.r) * cts + 2 * cp;
-        float c0[NC], c1[NC];
-#pragma unroll
-        for (int j = 0; j < NC; ++j) {
-            float2 t = make_float2(0.f, 0.f);
-            if ((p.sel.mask >> j) & 1ull) t = *reinterpret_cast<const float2 *>(src + (size_t)p.sel.pos[j] * cts);
-            c0[j] = t.x;
-            c1[j] = t.y;
-        }
-        fwht_inplace<NC>(c0);
-        fwht_inplace<NC>(c1);
-        uint32_t *dst = reinterpret_cast<uint32_t *>(p.C) + (size_t)p.geom.first_token(q) * Cd + (n0 >> 1) + cp;
-#pragma unroll
-        for (int h = 0; h < P; ++h) {
-#pragma unroll
-            for (int w = 0; w < P; ++w) {
-                int j = (h >> MH) * PWd + (w >> MW);
-                dst[((size_t)h * p.geom.Wt + w) * Cd] = pack_bf16x2(c0[j] * scale, c1[j] * scale);
-            }
-        }
-    }
+    return ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * splits;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool A_KFAST, int EPI, int LP>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(MfmaParams p)
+// Picks the tile shape: large tiles need fewer bytes per FLOP from L2 (a compute unit's L1 takes
+// in 64 bytes a clock, which a 128x128 tile just balances against the matrix cores), small tiles
+// give more workgroups when the output is small.  The cost is the number of rounds the
+// workgroups take over the compute units times the time of one workgroup.
+int choose_tile(const GemmArgs &a, int num_cus)
 {
-    constexpr int NT = 64 * WGM * WGN;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int SA = A_KFAST ? (BK + 8) * 2 : BM * 2 + 64;   // LDS row pitch of A in bytes
-    constexpr int SB = BN * 2 + 64;
-    constexpr int A_BYTES = (A_KFAST ? BM : BK) * SA;
-    constexpr int B_BYTES = BK * SB;
-    constexpr int STAGE = A_BYTES + B_BYTES;
-    constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;       // 16-byte chunks per thread per step
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile does not divide over the threads");
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave - wm * WGN;
-
-    // XCD-aware tile numbering: workgroup ids go round-robin over the 8 XCDs
-    const int T = p.tiles_m * p.tiles_n;
-    int t = blockIdx.x;
-    if ((T & 7) == 0) t = (t & 7) * (T >> 3) + (t >> 3);
-    const int tm = t / p.tiles_n, tn = t - tm * p.tiles_n;
-    const int m0 = tm * p.bm_step, n0 = tn * BN;
-    const int kbeg = blockIdx.y * p.k_per_split;
-    const int kend = min(p.K, kbeg + p.k_per_split);
-
-    // ---- per-thread load descriptors
-    const unsigned short *ga[A_CH];
-    const unsigned short *gb[B_CH];
-    int lda_off[A_CH], ldb_off[B_CH];   // LDS byte offsets inside a stage
-    int ka[A_CH], kb[B_CH];             // k offset of the chunk inside a step
-    bool oka[A_CH], okb[B_CH];
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-        int c = tid + i * NT;
-        if (A_KFAST) {
-            int row = c >> 3, kc = c & 7;
-            lda_off[i] = row * SA + kc * 16;
-            ka[i] = kc * 8;
-            oka[i] = row < p.bm_step && m0 + row < p.M;
-            ga[i] = p.A + (size_t)(m0 + row) * p.lda + kc * 8;
-        } else {
-            int krow = c / (BM / 8), cc = c - krow * (BM / 8);
-            lda_off[i] = krow * SA + cc * 16;
-            ka[i] = krow;
-            oka[i] = m0 + cc * 8 < p.M;
-            ga[i] = p.A + (size_t)krow * p.lda + m0 + cc * 8;
+    int best = 0;
+    double best_cost = 1e300;
+    for (int i = 0; i < kNumTiles; ++i) {
+        const TileShape &t = kTiles[i];
+        if (a.out == GemmOut::kUnproject && !t.fused) continue;
+        long wgs = workgroups(t, a.M, a.N, a.splits);
+        double rounds = (double)((wgs + num_cus - 1) / num_cus);
+        double mfma_clk = 2.0 * t.bm * t.bn * mfma::BK / 4096.0;
+        double fill_clk = (double)(t.bm + t.bn) * mfma::BK * 2 / 64.0;
+        double step = mfma_clk > fill_clk ? mfma_clk : fill_clk;
+        double steps = (double)((a.K + a.splits - 1) / a.splits + mfma::BK - 1) / mfma::BK;
+        double cost = rounds * (steps * step + 4000.0);
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = i;
         }
     }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-        int c = tid + i * NT;
-        int krow = c / (BN / 8), cc = c - krow * (BN / 8);
-        ldb_off[i] = A_BYTES + krow * SB + cc * 16;
-        kb[i] = krow;
-        okb[i] = n0 + cc * 8 < p.N;
-        gb[i] = p.B + (size_t)krow * p.ldb + n0 + cc * 8;
-    }
+    return best;
+}
 
-    uint4 ra[A_CH], rb[B_CH];
-    auto fetch = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) {
-            size_t off = A_KFAST ? (size_t)k0 : (size_t)k0 * p.lda;
-            ra[i] = ld16(ga[i] + off, oka[i] && k0 + ka[i] < kend);
-        }
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i)
-            rb[i] = ld16(gb[i] + (size_t)k0 * p.ldb, okb[i] && k0 + kb[i] < kend);
-    };
-    auto stage = [&](unsigned char *s) {
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4 *>(s + lda_off[i]) = ra[i];
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4 *>(s + ldb_off[i]) = rb[i];
-    };
-
-    // ---- per-lane fragment offsets inside a stage
-    const int li = lane & 31, kg = lane >> 5, grp = lane >> 4, i16 = lane & 15;
-    int a_off[TM], b_off[TN];
-#pragma unroll
-    for (int mi = 0; mi < TM; ++mi) {
-        if (A_KFAST)
-            a_off[mi] = (wm * WM + mi * 32 + li) * SA + kg * 16;
+int device_cus()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cus = v;
         else
-            a_off[mi] = (8 * (grp >> 1) + (i16 >> 2)) * SA + (wm * WM + mi * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2;
+            cus = 256;
     }
-#pragma unroll
-    for (int ni = 0; ni < TN; ++ni)
-        b_off[ni] = A_BYTES + (8 * (grp >> 1) + (i16 >> 2)) * SB + (wn * WN + ni * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2;
-
-    f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    if (kbeg < kend) {
-        fetch(kbeg);
-        stage(smem);
-        __syncthreads();
-        int buf = 0;
-        for (int k0 = kbeg; k0 < kend; k0 += BK) {
-            const bool more = k0 + BK < kend;
-            if (more) fetch(k0 + BK);
-            const unsigned char *s = smem + buf * STAGE;
-#pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
-                bf16x8_t a[TM], b[TN];
-#pragma unroll
-                for (int mi = 0; mi < TM; ++mi) {
-                    if (A_KFAST) {
-                        a[mi] = *reinterpret_cast<const bf16x8_t *>(s + a_off[mi] + ks * 32);
-                    } else {
-                        const unsigned char *q = s + a_off[mi] + ks * 16 * SA;
-                        i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q));
-                        i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q + 4 * SA));
-                        a[mi] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                    }
-                }
-#pragma unroll
-                for (int ni = 0; ni < TN; ++ni) {
-                    const unsigned char *q = s + b_off[ni] + ks * 16 * SB;
-                    i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q));
-                    i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q + 4 * SB));
-                    b[ni] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                }
-#pragma unroll
-                for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-                    for (int ni = 0; ni < TN; ++ni)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
-            }
-            if (more) stage(smem + (buf ^ 1) * STAGE);
-            __syncthreads();
-            buf ^= 1;
-        }
-    }
-
-    // accumulator element 4*g4 + e of a 32x32 tile: row 8*g4 + 4*(lane/32) + e, column lane%32
-    if (EPI == EPI_UNPROJECT) {
-        constexpr int CTS = BN + 8;
-        static_assert(EPI != EPI_UNPROJECT || BM * CTS * 4 <= 2 * STAGE, "tile does not fit in LDS");
-        float *ct = reinterpret_cast<float *>(smem);
-        // the loop above ended with a barrier: nobody reads operands any more
-#pragma unroll
-        for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        int row = wm * WM + mi * 32 + g4 * 8 + kg * 4 + e;
-                        int col = wn * WN + ni * 32 + li;
-                        ct[row * CTS + col] = acc[mi][ni][g4 * 4 + e];
-                    }
-        __syncthreads();
-        switch (p.mh * 4 + p.mw) {
-#define LBP_CASE(MH, MW)                                                                         \
-    case MH * 4 + MW:                                                                            \
-        if constexpr (MH <= LP && MW <= LP && ((1 << LP) >> MH) * ((1 << LP) >> MW) <= 16)      \
-            unproject_tile<LP, MH, MW, BN, NT>(ct, CTS, p, m0, n0, tid);                         \
-        break;
-            LBP_CASE(0, 0) LBP_CASE(0, 1) LBP_CASE(0, 2) LBP_CASE(0, 3)
-            LBP_CASE(1, 0) LBP_CASE(1, 1) LBP_CASE(1, 2) LBP_CASE(1, 3)
-            LBP_CASE(2, 0) LBP_CASE(2, 1) LBP_CASE(2, 2) LBP_CASE(2, 3)
-            LBP_CASE(3, 0) LBP_CASE(3, 1) LBP_CASE(3, 2) LBP_CASE(3, 3)
-#undef LBP_CASE
-            default: break;
-        }
-    } else {
-#pragma unroll
-        for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni) {
-                int col = n0 + wn * WN + ni * 32 + li;
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        int row = m0 + wm * WM + mi * 32 + g4 * 8 + kg * 4 + e;
-                        if (row < p.M && col < p.N) {
-                            float v = acc[mi][ni][g4 * 4 + e] * p.scale;
-                            if (EPI == EPI_F32) {
-                                float *Cz = reinterpret_cast<float *>(p.C) + (size_t)blockIdx.y * p.M * p.N;
-                                Cz[(size_t)row * p.N + col] = v;
-                            } else {
-                                reinterpret_cast<unsigned short *>(p.C)[(size_t)row * p.N + col] =
-                                    (unsigned short)f32_to_bf16_bits(v);
-                            }
-                        }
-                    }
-            }
-    }
+    return cus;
 }
-
-template <int BM, int BN, int WGM, int WGN, bool A_KFAST, int EPI, int LP>
-hipError_t launch_one(const MfmaParams &p, int splits, hipStream_t stream)
-{
-    constexpr int SA = A_KFAST ? (BK + 8) * 2 : BM * 2 + 64;
-    constexpr int SB = BN * 2 + 64;
-    constexpr int STAGE = (A_KFAST ? BM : BK) * SA + BK * SB;
-    constexpr int LDS = 2 * STAGE;
-    auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, A_KFAST, EPI, LP>;
-    static bool configured = false;     // per instantiation; racing threads set the same value
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
-    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)splits);
-    hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), LDS, stream, p);
-    return hipGetLastError();
-}
-
-int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 }  // namespace
 
@@ -329,33 +82,39 @@ bool gemm_can_fuse_unproject(const BasisPlan &plan, int dtype, GemmPath path)
 {
     if (path == GemmPath::kSimple || dtype != LBP_BF16) return false;
     if (plan.patch != 4 && plan.patch != 8) return false;
-    if (plan.r > 128) return false;
     int nc = (plan.patch >> plan.mh) * (plan.patch >> plan.mw);
-    return nc <= 16;
+    return nc <= 16;     // r <= patch^2 <= 64 always fits the smallest tile
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
 {
-    constexpr int BM = 128, BN = 128;
     if (a.dtype != LBP_BF16) return hipErrorInvalidValue;
+    if (a.M < 8 || a.N < 8 || a.K < 1) return hipErrorInvalidValue;
     if (a.N % 8 || a.ldb % 8 || a.lda % 8 || (a.a_kfast ? a.K % 8 : a.M % 8)) return hipErrorInvalidValue;
     if (a.out != GemmOut::kF32 && a.splits != 1) return hipErrorInvalidValue;
-    MfmaParams p{};
+    int tile = tile_from_env();
+    if (tile >= 0 && a.out == GemmOut::kUnproject && !kTiles[tile].fused) tile = -1;
+    if (tile < 0) tile = a.tile >= 0 && a.tile < kNumTiles ? a.tile : choose_tile(a, device_cus());
+    const TileShape &t = kTiles[tile];
+
+    mfma::Params p{};
     p.A = (const unsigned short *)a.A;
     p.B = (const unsigned short *)a.B;
     p.M = a.M; p.N = a.N; p.K = a.K;
     p.lda = a.lda; p.ldb = a.ldb;
-    p.k_per_split = round_up((a.K + a.splits - 1) / a.splits, BK);
-    p.bm_step = BM;
-    p.tiles_n = (a.N + BN - 1) / BN;
+    p.k_per_split = round_up((a.K + a.splits - 1) / a.splits, mfma::BK);
+    p.bm_step = t.bm;
+    p.tiles_n = (a.N + t.bn - 1) / t.bn;
     p.C = a.C;
     p.scale = a.scale;
+    int lp = 0;
     if (a.out == GemmOut::kUnproject) {
-        if (!a.plan || !a.a_kfast || !gemm_can_fuse_unproject(*a.plan, a.dtype, GemmPath::kAuto))
+        if (!a.plan || !a.a_kfast || !t.fused || !gemm_can_fuse_unproject(*a.plan, a.dtype, GemmPath::kAuto))
             return hipErrorInvalidValue;
         const BasisPlan &bp = *a.plan;
+        lp = bp.log2p;
         p.r = bp.r; p.mh = bp.mh; p.mw = bp.mw;
-        p.bm_step = BM / bp.r * bp.r;
+        p.bm_step = t.bm / bp.r * bp.r;
         p.sel.mask = bp.pooled_mask;
         for (int j = 0; j < 64; ++j) p.sel.pos[j] = bp.pooled_pos[j];
         p.geom.Wt = a.grid_w;
@@ -364,17 +123,9 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
         p.geom.PHW = (a.grid_h / bp.patch) * (a.grid_w / bp.patch);
         p.geom.patch = bp.patch;
         p.Q = a.M / bp.r;
-        p.tiles_m = (a.M + p.bm_step - 1) / p.bm_step;
-        if (bp.patch == 8) return launch_one<BM, BN, 2, 2, true, EPI_UNPROJECT, 3>(p, 1, stream);
-        return launch_one<BM, BN, 2, 2, true, EPI_UNPROJECT, 2>(p, 1, stream);
     }
-    p.tiles_m = (a.M + BM - 1) / BM;
-    if (a.out == GemmOut::kF32) {
-        if (a.a_kfast) return launch_one<BM, BN, 2, 2, true, EPI_F32, 0>(p, a.splits, stream);
-        return launch_one<BM, BN, 2, 2, false, EPI_F32, 0>(p, a.splits, stream);
-    }
-    if (a.a_kfast) return launch_one<BM, BN, 2, 2, true, EPI_BF16, 0>(p, 1, stream);
-    return launch_one<BM, BN, 2, 2, false, EPI_BF16, 0>(p, 1, stream);
+    p.tiles_m = (a.M + p.bm_step - 1) / p.bm_step;
+    return t.launch(p, a.a_kfast, a.out, lp, a.splits, stream);
 }
 
 }  // namespace lbp

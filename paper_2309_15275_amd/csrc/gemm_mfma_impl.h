@@ -1,0 +1,394 @@
+// bf16 matrix-core GEMM kernel template for gfx950 (fp32 accumulation); instantiated per tile
+// shape by the gemm_mfma_*.hip files.
+//
+// One workgroup owns a BM x BN tile of the output and walks the reduction in steps of BK = 64.
+//   * Global -> registers (16-byte loads, issued one step ahead) -> LDS (two stages, one barrier
+//     per step).  Loads are never predicated in the steady state: rows and columns past the edge
+//     of a matrix are clamped to the last valid ones (they only feed outputs that are never
+//     stored); only a final partial step of the reduction zero-fills.
+//   * Operands whose reduction index is contiguous in memory are stored [row][k] in LDS and read
+//     back with 16-byte reads.  Operands whose reduction index is the slow axis (W, and both
+//     operands of gW) are stored as they arrive, [k][row], and transposed on the way to the
+//     matrix cores with ds_read_b64_tr_b16: within each group of 16 lanes, lane i supplies the
+//     address of 4 consecutive elements of row k = i/4 starting at column 4*(i%4), and lane j
+//     receives the 4 k-values of column j.  Two such reads give the 8 consecutive k-values per
+//     lane that v_mfma_f32_32x32x16_bf16 takes.  Row pitches are padded so that both access
+//     patterns spread over all LDS banks.
+//   * Each wavefront owns a (BM/WGM) x (BN/WGN) block of 32x32 accumulator tiles.
+//   * Epilogues: scaled fp32 store (per split-K slice), scaled bf16 store, or the reverse
+//     projection of Eq. 7 fused in: the tile's rows are (patch, basis) pairs, the accumulators go
+//     through LDS, and every lane expands the r coefficients of one (patch, channel pair) into
+//     the p x p tokens of that patch with the same pooled butterfly the stand-alone kernel uses.
+//   * Workgroups are numbered so that each of the 8 XCDs (private L2 each) works on a contiguous
+//     run of tiles that share the same rows of A.
+#pragma once
+#include "device_utils.h"
+#include "kernels.h"
+#include "wht_device.h"
+
+namespace lbp {
+namespace mfma {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef short i16x4_t __attribute__((ext_vector_type(4)));
+typedef short i16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+#define LBP_LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
+
+constexpr int BK = 64;
+
+enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_UNPROJECT = 2 };
+
+struct Params {
+    const unsigned short *A;
+    const unsigned short *B;
+    int M, N, K;
+    long lda, ldb;
+    int k_per_split;      // multiple of BK
+    int bm_step;          // rows of the output one tile advances by (BM, or a multiple of r below BM)
+    int tiles_m, tiles_n;
+    void *C;
+    float scale;
+    // fused reverse projection
+    GridGeom geom;
+    PooledSel sel;
+    int r, mh, mw;
+    long Q;               // number of patches
+};
+
+// Reverse projection of one tile held in LDS as fp32 ct[row][cts]; rows are (patch, basis).
+template <int LP, int MH, int MW, int BN, int NT>
+__device__ __forceinline__ void unproject_tile(const float *ct, int cts, const Params &p, int m0,
+                                               int n0, int tid)
+{
+    constexpr int P = 1 << LP;
+    constexpr int PWd = P >> MW;
+    constexpr int NC = (P >> MH) * PWd;
+    constexpr float scale = 1.0f / (float)(P * P);
+    constexpr int HALF = BN / 2;
+    const int patches = p.bm_step / p.r;
+    const int Cd = p.N >> 1;
+    for (int it = tid; it < patches * HALF; it += NT) {
+        int pt = it / HALF, cp = it - pt * HALF;
+        long q = (long)(m0 / p.r) + pt;
+        if (q >= p.Q || n0 + 2 * cp >= p.N) continue;
+        const float *src = ct + (size_t)(pt * p.r) * cts + 2 * cp;
+        float c0[NC], c1[NC];
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            float2 t = make_float2(0.f, 0.f);
+            if ((p.sel.mask >> j) & 1ull) t = *reinterpret_cast<const float2 *>(src + (size_t)p.sel.pos[j] * cts);
+            c0[j] = t.x;
+            c1[j] = t.y;
+        }
+        fwht_inplace<NC>(c0);
+        fwht_inplace<NC>(c1);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(p.C) + (size_t)p.geom.first_token(q) * Cd + (n0 >> 1) + cp;
+#pragma unroll
+        for (int h = 0; h < P; ++h) {
+#pragma unroll
+            for (int w = 0; w < P; ++w) {
+                int j = (h >> MH) * PWd + (w >> MW);
+                dst[((size_t)h * p.geom.Wt + w) * Cd] = pack_bf16x2(c0[j] * scale, c1[j] * scale);
+            }
+        }
+    }
+}
+
+template <int BM, int BN, bool A_KFAST>
+struct Smem {
+    static constexpr int SA = A_KFAST ? (BK + 8) * 2 : BM * 2 + 64;   // LDS row pitch of A in bytes
+    static constexpr int SB = BN * 2 + 64;
+    static constexpr int A_BYTES = (A_KFAST ? BM : BK) * SA;
+    static constexpr int B_BYTES = BK * SB;
+    static constexpr int STAGE = A_BYTES + B_BYTES;
+    static constexpr int TOTAL = 2 * STAGE;
+};
+
+template <int BM, int BN, int WGM, int WGN, bool A_KFAST, int EPI, int LP>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
+{
+    using S = Smem<BM, BN, A_KFAST>;
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int SA = S::SA, SB = S::SB, A_BYTES = S::A_BYTES, STAGE = S::STAGE;
+    constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;       // 16-byte chunks per thread per step
+    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile does not divide over the threads");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 tiles");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave - wm * WGN;
+
+    // XCD-aware tile numbering: workgroup ids go round-robin over the 8 XCDs
+    const int T = p.tiles_m * p.tiles_n;
+    int t = blockIdx.x;
+    if ((T & 7) == 0) t = (t & 7) * (T >> 3) + (t >> 3);
+    const int tm = t / p.tiles_n, tn = t - tm * p.tiles_n;
+    const int m0 = tm * p.bm_step, n0 = tn * BN;
+    const int kbeg = blockIdx.y * p.k_per_split;
+    const int kend = min(p.K, kbeg + p.k_per_split);
+
+    // ---- per-thread load descriptors (rows / columns clamped into the matrix)
+    const unsigned short *ga[A_CH];
+    const unsigned short *gb[B_CH];
+    int sa_off[A_CH], sb_off[B_CH];     // LDS byte offsets inside a stage
+    int ka[A_CH], kb[B_CH];             // k offset of the chunk inside a step
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+        int c = tid + i * NT;
+        if (A_KFAST) {
+            int row = c >> 3, kc = c & 7;
+            sa_off[i] = row * SA + kc * 16;
+            ka[i] = kc * 8;
+            ga[i] = p.A + (size_t)min(m0 + row, p.M - 1) * p.lda + kc * 8;
+        } else {
+            int krow = c / (BM / 8), cc = c - krow * (BM / 8);
+            sa_off[i] = krow * SA + cc * 16;
+            ka[i] = krow;
+            ga[i] = p.A + (size_t)krow * p.lda + min(m0 + cc * 8, p.M - 8);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) {
+        int c = tid + i * NT;
+        int krow = c / (BN / 8), cc = c - krow * (BN / 8);
+        sb_off[i] = A_BYTES + krow * SB + cc * 16;
+        kb[i] = krow;
+        gb[i] = p.B + (size_t)krow * p.ldb + min(n0 + cc * 8, p.N - 8);
+    }
+
+    // Two register sets: while step s is multiplied out of LDS, the loads of steps s+1 and s+2
+    // are in flight (one step of a tile is far shorter than a trip to L2 or HBM).  The steady
+    // state has no predication and no branches around loads, so the compiler's wait counters only
+    // wait for the older of the two sets.
+    uint4 ra[2][A_CH], rb[2][B_CH];
+    auto fetch_full = [&](int set, int k0) {        // needs k0 + BK <= kend
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i)
+            ra[set][i] = *reinterpret_cast<const uint4 *>(ga[i] + (A_KFAST ? (size_t)k0 : (size_t)k0 * p.lda));
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i)
+            rb[set][i] = *reinterpret_cast<const uint4 *>(gb[i] + (size_t)k0 * p.ldb);
+    };
+    auto fetch_tail = [&](int set, int k0) {        // a partial step: zero-fill k >= kend
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            ra[set][i] = make_uint4(0u, 0u, 0u, 0u);
+            if (k0 + ka[i] < kend)
+                ra[set][i] = *reinterpret_cast<const uint4 *>(ga[i] + (A_KFAST ? (size_t)k0 : (size_t)k0 * p.lda));
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) {
+            rb[set][i] = make_uint4(0u, 0u, 0u, 0u);
+            if (k0 + kb[i] < kend) rb[set][i] = *reinterpret_cast<const uint4 *>(gb[i] + (size_t)k0 * p.ldb);
+        }
+    };
+    auto stage = [&](int set, unsigned char *s) {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4 *>(s + sa_off[i]) = ra[set][i];
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4 *>(s + sb_off[i]) = rb[set][i];
+    };
+
+    // ---- per-lane fragment offsets inside a stage
+    const int li = lane & 31, kg = lane >> 5, grp = lane >> 4, i16 = lane & 15;
+    int a_off[TM], b_off[TN];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi) {
+        if (A_KFAST)
+            a_off[mi] = (wm * WM + mi * 32 + li) * SA + kg * 16;
+        else
+            a_off[mi] = (8 * (grp >> 1) + (i16 >> 2)) * SA + (wm * WM + mi * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2;
+    }
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni)
+        b_off[ni] = A_BYTES + (8 * (grp >> 1) + (i16 >> 2)) * SB + (wn * WN + ni * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2;
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    auto multiply = [&](const unsigned char *s) {
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8_t a[TM], b[TN];
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi) {
+                if (A_KFAST) {
+                    a[mi] = *reinterpret_cast<const bf16x8_t *>(s + a_off[mi] + ks * 32);
+                } else {
+                    const unsigned char *q = s + a_off[mi] + ks * 16 * SA;
+                    i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q));
+                    i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q + 4 * SA));
+                    a[mi] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
+            }
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) {
+                const unsigned char *q = s + b_off[ni] + ks * 16 * SB;
+                i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q));
+                i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q + 4 * SB));
+                b[ni] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < TN; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+        }
+    };
+
+    unsigned char *buf0 = smem, *buf1 = smem + STAGE;
+    const int nfull = (kend - kbeg) / BK;           // whole steps; a partial one may follow
+    if (nfull > 0) {
+        fetch_full(0, kbeg);
+        if (nfull > 1) fetch_full(1, kbeg + BK);
+        stage(0, buf0);
+        __syncthreads();
+        // invariant at the top: buf0 holds step s, set 1 is in flight for step s+1
+        int s = 0;
+        for (; s + 3 < nfull; s += 2) {
+            fetch_full(0, kbeg + (s + 2) * BK);
+            multiply(buf0);
+            stage(1, buf1);
+            __syncthreads();
+            fetch_full(1, kbeg + (s + 3) * BK);
+            multiply(buf1);
+            stage(0, buf0);
+            __syncthreads();
+        }
+        const int rem = nfull - s;                  // 1, 2 or 3 steps left, buf0 holds the first
+        if (rem == 3) fetch_full(0, kbeg + (s + 2) * BK);
+        multiply(buf0);
+        if (rem >= 2) {
+            stage(1, buf1);
+            __syncthreads();
+            multiply(buf1);
+            if (rem == 3) {
+                stage(0, buf0);
+                __syncthreads();
+                multiply(buf0);
+            }
+        }
+        __syncthreads();
+    }
+    if (kbeg + nfull * BK < kend) {                 // the partial step, not pipelined
+        fetch_tail(0, kbeg + nfull * BK);
+        stage(0, buf0);
+        __syncthreads();
+        multiply(buf0);
+        __syncthreads();
+    }
+
+    // accumulator element 4*g4 + e of a 32x32 tile: row 8*g4 + 4*(lane/32) + e, column lane%32
+    if constexpr (EPI == EPI_UNPROJECT) {
+        constexpr int CTS = BN + 8;
+        static_assert(BM * CTS * 4 <= S::TOTAL, "tile does not fit in LDS");
+        float *ct = reinterpret_cast<float *>(smem);
+        // the loop above ended with a barrier: nobody reads operands any more
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        int row = wm * WM + mi * 32 + g4 * 8 + kg * 4 + e;
+                        int col = wn * WN + ni * 32 + li;
+                        ct[row * CTS + col] = acc[mi][ni][g4 * 4 + e];
+                    }
+        __syncthreads();
+        switch (p.mh * 4 + p.mw) {
+#define LBP_CASE(MH, MW)                                                                         \
+    case MH * 4 + MW:                                                                            \
+        if constexpr (MH <= LP && MW <= LP && ((1 << LP) >> MH) * ((1 << LP) >> MW) <= 16)      \
+            unproject_tile<LP, MH, MW, BN, NT>(ct, CTS, p, m0, n0, tid);                         \
+        break;
+            LBP_CASE(0, 0) LBP_CASE(0, 1) LBP_CASE(0, 2) LBP_CASE(0, 3)
+            LBP_CASE(1, 0) LBP_CASE(1, 1) LBP_CASE(1, 2) LBP_CASE(1, 3)
+            LBP_CASE(2, 0) LBP_CASE(2, 1) LBP_CASE(2, 2) LBP_CASE(2, 3)
+            LBP_CASE(3, 0) LBP_CASE(3, 1) LBP_CASE(3, 2) LBP_CASE(3, 3)
+#undef LBP_CASE
+            default: break;
+        }
+    } else {
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) {
+                int col = n0 + wn * WN + ni * 32 + li;
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        int row = m0 + wm * WM + mi * 32 + g4 * 8 + kg * 4 + e;
+                        if (row < p.M && col < p.N) {
+                            float v = acc[mi][ni][g4 * 4 + e] * p.scale;
+                            if (EPI == EPI_F32) {
+                                float *Cz = reinterpret_cast<float *>(p.C) + (size_t)blockIdx.y * p.M * p.N;
+                                Cz[(size_t)row * p.N + col] = v;
+                            } else {
+                                reinterpret_cast<unsigned short *>(p.C)[(size_t)row * p.N + col] =
+                                    (unsigned short)f32_to_bf16_bits(v);
+                            }
+                        }
+                    }
+            }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, bool A_KFAST, int EPI, int LP>
+hipError_t launch_one(const Params &p, int splits, hipStream_t stream)
+{
+    constexpr int LDS = Smem<BM, BN, A_KFAST>::TOTAL;
+    auto kern = gemm_kernel<BM, BN, WGM, WGN, A_KFAST, EPI, LP>;
+    static bool configured = false;     // per instantiation; racing threads set the same value
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)splits);
+    hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), LDS, stream, p);
+    return hipGetLastError();
+}
+
+// All instantiations of one tile shape: op = out kind x operand layout, lp = log2(patch) for the
+// fused reverse projection.
+template <int BM, int BN, int WGM, int WGN, bool FUSED>
+hipError_t launch_tile(const Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s)
+{
+    if (out == GemmOut::kUnproject) {
+        if constexpr (FUSED) {
+            if (lp == 3) return launch_one<BM, BN, WGM, WGN, true, EPI_UNPROJECT, 3>(p, 1, s);
+            if (lp == 2) return launch_one<BM, BN, WGM, WGN, true, EPI_UNPROJECT, 2>(p, 1, s);
+        }
+        return hipErrorInvalidValue;
+    }
+    if (out == GemmOut::kF32) {
+        if (a_kfast) return launch_one<BM, BN, WGM, WGN, true, EPI_F32, 0>(p, splits, s);
+        return launch_one<BM, BN, WGM, WGN, false, EPI_F32, 0>(p, splits, s);
+    }
+    if (a_kfast) return launch_one<BM, BN, WGM, WGN, true, EPI_BF16, 0>(p, 1, s);
+    return launch_one<BM, BN, WGM, WGN, false, EPI_BF16, 0>(p, 1, s);
+}
+
+}  // namespace mfma
+
+// One entry per tile shape, defined in gemm_mfma_<shape>.hip.
+hipError_t mfma_tile_128x128(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
+hipError_t mfma_tile_64x128(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
+hipError_t mfma_tile_256x128(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
+hipError_t mfma_tile_256x256(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
+
+}  // namespace lbp

@@ -39,6 +39,7 @@ struct GemmArgs {
     bool a_kfast = true;
     int dtype = LBP_BF16;      // operand type; accumulation is fp32
     int splits = 1;            // split-K slices
+    int tile = -1;             // tile shape of the bf16 matrix-core kernel, -1 = choose
     GemmOut out = GemmOut::kF32;
     void *C = nullptr;
     float scale = 1.0f;
