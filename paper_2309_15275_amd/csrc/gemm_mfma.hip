@@ -8,58 +8,18 @@ namespace {
 
 int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-struct TileShape {
-    int bm, bn;
-    bool fused;   // has the fused reverse-projection epilogue
-    hipError_t (*launch)(const mfma::Params &, bool, GemmOut, int, int, hipStream_t);
-};
+typedef hipError_t (*TileLaunch)(const mfma::Params &, bool, GemmOut, int, int, hipStream_t);
 
-const TileShape kTiles[] = {
-    {128, 128, true, mfma_tile_128x128},
-    {64, 128, true, mfma_tile_64x128},
-    {256, 128, false, mfma_tile_256x128},
-    {256, 256, false, mfma_tile_256x256},
-};
-constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+// same order as kGemmTiles
+const TileLaunch kLaunch[kNumGemmTiles] = {mfma_tile_128x128, mfma_tile_64x128, mfma_tile_256x128,
+                                           mfma_tile_256x256};
 
 int tile_from_env()
 {
     const char *s = std::getenv("LBP_GEMM_TILE");
     if (!s || !*s) return -1;
     int v = std::atoi(s);
-    return v >= 0 && v < kNumTiles ? v : -1;
-}
-
-// Workgroups needed by a tile shape.
-long workgroups(const TileShape &t, long M, long N, int splits)
-{
-    return ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * splits;
-}
-
-// Picks the tile shape: large tiles need fewer bytes per FLOP from L2 (a compute unit's L1 takes
-// in 64 bytes a clock, which a 128x128 tile just balances against the matrix cores), small tiles
-// give more workgroups when the output is small.  The cost is the number of rounds the
-// workgroups take over the compute units times the time of one workgroup.
-int choose_tile(const GemmArgs &a, int num_cus)
-{
-    int best = 0;
-    double best_cost = 1e300;
-    for (int i = 0; i < kNumTiles; ++i) {
-        const TileShape &t = kTiles[i];
-        if (a.out == GemmOut::kUnproject && !t.fused) continue;
-        long wgs = workgroups(t, a.M, a.N, a.splits);
-        double rounds = (double)((wgs + num_cus - 1) / num_cus);
-        double mfma_clk = 2.0 * t.bm * t.bn * mfma::BK / 4096.0;
-        double fill_clk = (double)(t.bm + t.bn) * mfma::BK * 2 / 64.0;
-        double step = mfma_clk > fill_clk ? mfma_clk : fill_clk;
-        double steps = (double)((a.K + a.splits - 1) / a.splits + mfma::BK - 1) / mfma::BK;
-        double cost = rounds * (steps * step + 4000.0);
-        if (cost < best_cost) {
-            best_cost = cost;
-            best = i;
-        }
-    }
-    return best;
+    return v >= 0 && v < kNumGemmTiles ? v : -1;
 }
 
 int device_cus()
@@ -92,10 +52,15 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
     if (a.M < 8 || a.N < 8 || a.K < 1) return hipErrorInvalidValue;
     if (a.N % 8 || a.ldb % 8 || a.lda % 8 || (a.a_kfast ? a.K % 8 : a.M % 8)) return hipErrorInvalidValue;
     if (a.out != GemmOut::kF32 && a.splits != 1) return hipErrorInvalidValue;
-    int tile = tile_from_env();
-    if (tile >= 0 && a.out == GemmOut::kUnproject && !kTiles[tile].fused) tile = -1;
-    if (tile < 0) tile = a.tile >= 0 && a.tile < kNumTiles ? a.tile : choose_tile(a, device_cus());
-    const TileShape &t = kTiles[tile];
+    int tile = tile_from_env();     // testing: force one tile shape for every product
+    if (tile >= 0 && a.out == GemmOut::kUnproject && !kGemmTiles[tile].fused) tile = -1;
+    if (tile < 0) tile = a.tile;
+    if (tile < 0 || tile >= kNumGemmTiles) {
+        const bool fused = a.out == GemmOut::kUnproject;
+        tile = plan_gemm(a.M, a.N, a.K / a.splits, a.out == GemmOut::kF32 ? 4 : 2, false,
+                         fused && a.plan ? a.plan->r : 0, fused && a.plan ? a.plan->patch : 0, device_cus()).tile;
+    }
+    const GemmTileInfo &t = kGemmTiles[tile];
 
     mfma::Params p{};
     p.A = (const unsigned short *)a.A;
@@ -109,7 +74,7 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
     p.scale = a.scale;
     int lp = 0;
     if (a.out == GemmOut::kUnproject) {
-        if (!a.plan || !a.a_kfast || !t.fused || !gemm_can_fuse_unproject(*a.plan, a.dtype, GemmPath::kAuto))
+        if (!a.plan || !a.a_kfast || !t.fused || a.plan->r > t.bm || !gemm_can_fuse_unproject(*a.plan, a.dtype, GemmPath::kAuto))
             return hipErrorInvalidValue;
         const BasisPlan &bp = *a.plan;
         lp = bp.log2p;
@@ -125,7 +90,7 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
         p.Q = a.M / bp.r;
     }
     p.tiles_m = (a.M + p.bm_step - 1) / p.bm_step;
-    return t.launch(p, a.a_kfast, a.out, lp, a.splits, stream);
+    return kLaunch[tile](p, a.a_kfast, a.out, lp, a.splits, stream);
 }
 
 }  // namespace lbp

@@ -106,9 +106,10 @@ struct Smem {
     static constexpr int TOTAL = 2 * STAGE;
 };
 
-template <int BM, int BN, int WGM, int WGN, bool A_KFAST, int EPI, int LP>
+template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
 {
+    static_assert(PF == 2 || PF == 4, "prefetch depth must be even");
     using S = Smem<BM, BN, A_KFAST>;
     constexpr int NT = 64 * WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -161,11 +162,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
         gb[i] = p.B + (size_t)krow * p.ldb + min(n0 + cc * 8, p.N - 8);
     }
 
-    // Two register sets: while step s is multiplied out of LDS, the loads of steps s+1 and s+2
-    // are in flight (one step of a tile is far shorter than a trip to L2 or HBM).  The steady
-    // state has no predication and no branches around loads, so the compiler's wait counters only
-    // wait for the older of the two sets.
-    uint4 ra[2][A_CH], rb[2][B_CH];
+    // PF register sets: while step s is multiplied out of LDS, the loads of steps s+1 .. s+PF are
+    // in flight (one step of a tile is far shorter than a trip to L2 or HBM, so a small problem
+    // with one workgroup per compute unit needs several steps in flight).  The steady state has no
+    // predication and no branches around loads, so the compiler's wait counters only wait for
+    // the oldest set.
+    uint4 ra[PF][A_CH], rb[PF][B_CH];
     auto fetch_full = [&](int set, int k0) {        // needs k0 + BK <= kend
 #pragma unroll
         for (int i = 0; i < A_CH; ++i)
@@ -246,45 +248,42 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
         }
     };
 
-    unsigned char *buf0 = smem, *buf1 = smem + STAGE;
+    unsigned char *const bufs[2] = {smem, smem + STAGE};
     const int nfull = (kend - kbeg) / BK;           // whole steps; a partial one may follow
     if (nfull > 0) {
-        fetch_full(0, kbeg);
-        if (nfull > 1) fetch_full(1, kbeg + BK);
-        stage(0, buf0);
+#pragma unroll
+        for (int j = 0; j < PF; ++j)
+            if (j < nfull) fetch_full(j, kbeg + j * BK);
+        stage(0, bufs[0]);
         __syncthreads();
-        // invariant at the top: buf0 holds step s, set 1 is in flight for step s+1
+        // invariant at the top of step s (j = s mod PF): LDS stage s&1 holds step s, register
+        // sets j+1 .. j+PF-1 are in flight for steps s+1 .. s+PF-1, set j is free
         int s = 0;
-        for (; s + 3 < nfull; s += 2) {
-            fetch_full(0, kbeg + (s + 2) * BK);
-            multiply(buf0);
-            stage(1, buf1);
-            __syncthreads();
-            fetch_full(1, kbeg + (s + 3) * BK);
-            multiply(buf1);
-            stage(0, buf0);
-            __syncthreads();
-        }
-        const int rem = nfull - s;                  // 1, 2 or 3 steps left, buf0 holds the first
-        if (rem == 3) fetch_full(0, kbeg + (s + 2) * BK);
-        multiply(buf0);
-        if (rem >= 2) {
-            stage(1, buf1);
-            __syncthreads();
-            multiply(buf1);
-            if (rem == 3) {
-                stage(0, buf0);
+        for (; s + 2 * PF - 1 < nfull; s += PF) {
+#pragma unroll
+            for (int j = 0; j < PF; ++j) {
+                fetch_full(j, kbeg + (s + j + PF) * BK);
+                multiply(bufs[j & 1]);
+                stage((j + 1) % PF, bufs[(j + 1) & 1]);
                 __syncthreads();
-                multiply(buf0);
             }
         }
-        __syncthreads();
+        const int rem = nfull - s;                  // 1 .. 2*PF-1 steps left
+#pragma unroll
+        for (int j = 0; j < 2 * PF - 1; ++j) {
+            if (j < rem) {
+                if (s + j + PF < nfull) fetch_full(j % PF, kbeg + (s + j + PF) * BK);
+                multiply(bufs[j & 1]);
+                if (j + 1 < rem) stage((j + 1) % PF, bufs[(j + 1) & 1]);
+                __syncthreads();
+            }
+        }
     }
     if (kbeg + nfull * BK < kend) {                 // the partial step, not pipelined
         fetch_tail(0, kbeg + nfull * BK);
-        stage(0, buf0);
+        stage(0, bufs[0]);
         __syncthreads();
-        multiply(buf0);
+        multiply(bufs[0]);
         __syncthreads();
     }
 
@@ -346,11 +345,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool A_KFAST, int EPI, int LP>
+template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
 hipError_t launch_one(const Params &p, int splits, hipStream_t stream)
 {
     constexpr int LDS = Smem<BM, BN, A_KFAST>::TOTAL;
-    auto kern = gemm_kernel<BM, BN, WGM, WGN, A_KFAST, EPI, LP>;
+    auto kern = gemm_kernel<BM, BN, WGM, WGN, PF, A_KFAST, EPI, LP>;
     static bool configured = false;     // per instantiation; racing threads set the same value
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -363,24 +362,24 @@ hipError_t launch_one(const Params &p, int splits, hipStream_t stream)
     return hipGetLastError();
 }
 
-// All instantiations of one tile shape: op = out kind x operand layout, lp = log2(patch) for the
-// fused reverse projection.
-template <int BM, int BN, int WGM, int WGN, bool FUSED>
+// All instantiations of one tile shape and prefetch depth: output kind x operand layout; lp is
+// log2(patch) for the fused reverse projection.
+template <int BM, int BN, int WGM, int WGN, int PF, bool FUSED>
 hipError_t launch_tile(const Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s)
 {
     if (out == GemmOut::kUnproject) {
         if constexpr (FUSED) {
-            if (lp == 3) return launch_one<BM, BN, WGM, WGN, true, EPI_UNPROJECT, 3>(p, 1, s);
-            if (lp == 2) return launch_one<BM, BN, WGM, WGN, true, EPI_UNPROJECT, 2>(p, 1, s);
+            if (lp == 3) return launch_one<BM, BN, WGM, WGN, PF, true, EPI_UNPROJECT, 3>(p, 1, s);
+            if (lp == 2) return launch_one<BM, BN, WGM, WGN, PF, true, EPI_UNPROJECT, 2>(p, 1, s);
         }
         return hipErrorInvalidValue;
     }
     if (out == GemmOut::kF32) {
-        if (a_kfast) return launch_one<BM, BN, WGM, WGN, true, EPI_F32, 0>(p, splits, s);
-        return launch_one<BM, BN, WGM, WGN, false, EPI_F32, 0>(p, splits, s);
+        if (a_kfast) return launch_one<BM, BN, WGM, WGN, PF, true, EPI_F32, 0>(p, splits, s);
+        return launch_one<BM, BN, WGM, WGN, PF, false, EPI_F32, 0>(p, splits, s);
     }
-    if (a_kfast) return launch_one<BM, BN, WGM, WGN, true, EPI_BF16, 0>(p, 1, s);
-    return launch_one<BM, BN, WGM, WGN, false, EPI_BF16, 0>(p, 1, s);
+    if (a_kfast) return launch_one<BM, BN, WGM, WGN, PF, true, EPI_BF16, 0>(p, 1, s);
+    return launch_one<BM, BN, WGM, WGN, PF, false, EPI_BF16, 0>(p, 1, s);
 }
 
 }  // namespace mfma

@@ -15,9 +15,10 @@ enum class GemmPath { kAuto = 0, kSimple = 1 };
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
                           const BasisPlan &plan, WhtPath path, hipStream_t stream);
 
-// p^-1(.) of Eq. 7 per patch with the 1/p^2 factor: in fp32 [P*r][C] -> out [N][H][W][C] of `dtype`.
-hipError_t launch_unproject(const float *in, void *out, int N, int H, int W, int C, int dtype,
-                            const BasisPlan &plan, WhtPath path, hipStream_t stream);
+// p^-1(.) of Eq. 7 per patch with the 1/p^2 factor: in fp32 [slices][P*r][C] (the slices are
+// summed first: split-K partial results) -> out [N][H][W][C] of `dtype`.
+hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H, int W, int C,
+                            int dtype, const BasisPlan &plan, WhtPath path, hipStream_t stream);
 
 // What a matrix product does with its accumulators.
 enum class GemmOut {

@@ -102,7 +102,8 @@ bool fuse_unproject_from_env()
 // gW = scale * A^T-style product with split-K: direct store when one slice suffices and the
 // kernel can write the output type, otherwise fp32 partial sums and a fixed-order reduction.
 int weight_gradient(const void *A, const void *B, int Cout, int Cin, long K, int dtype, int gw_dtype,
-                    int splits, float scale, float *part, void *gW, lbp::GemmPath gpath, hipStream_t s);
+                    const lbp::GemmPlan &plan, float scale, float *part, void *gW, lbp::GemmPath gpath,
+                    hipStream_t s);
 
 lbp::WhtPath wht_path_from_env()
 {
@@ -143,9 +144,12 @@ int validate_buffers(const void *x, const void *gy, const void *W, const lbp_sha
     } while (0)
 
 int weight_gradient(const void *A, const void *B, int Cout, int Cin, long K, int dtype, int gw_dtype,
-                    int splits, float scale, float *part, void *gW, lbp::GemmPath gpath, hipStream_t s)
+                    const lbp::GemmPlan &plan, float scale, float *part, void *gW, lbp::GemmPath gpath,
+                    hipStream_t s)
 {
+    const int splits = plan.splits;
     lbp::GemmArgs g;
+    g.tile = plan.tile;
     g.A = A; g.B = B;
     g.M = Cout; g.N = Cin; g.K = (int)K;
     g.lda = Cout; g.ldb = Cin;
@@ -188,10 +192,20 @@ size_t lbp_wht_workspace_bytes(const lbp_shape_t *shape, int patch, int r)
 {
     if (lbp::validate_shape(shape, patch) != LBP_OK) return 0;
     if (patch != 0 && (r < 1 || r > patch * patch)) return 0;
+    // the split-K factors, hence the size, depend on the device's compute-unit count: use the
+    // current device's if there is one, else that of an MI355X
+    int cus = 256, dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+        cus = v;
+    else
+        (void)hipGetLastError();
     lbp::WorkspacePlan ws;
-    // sized for the largest split-K factor any device could ask for at this shape
-    if (lbp::plan_workspace(shape, patch, r, 1024, &ws) != LBP_OK) return 0;
-    return ws.total;
+    if (lbp::plan_workspace(shape, patch, r, cus, false, &ws) != LBP_OK) return 0;
+    size_t total = ws.total;
+    if (patch == 0 && shape->dtype == LBP_BF16)   // staging of gx for the plain cross-check kernels
+        total += ((size_t)shape->N * shape->H * shape->W * shape->Cin * 4 + 255) / 256 * 256;
+    return total;
 }
 
 int lbp_set_workspace(void *dev_ptr, size_t bytes)
@@ -271,7 +285,7 @@ int lbp_wht_unproject(const void *in, int N, int H, int W, int C, int dtype, int
     DeviceState *st;
     rc = current_device(&dev, &st);
     if (rc) return rc;
-    LBP_HIP(lbp::launch_unproject((const float *)in, out, N, H, W, C, dtype, plan, wht_path_from_env(),
+    LBP_HIP(lbp::launch_unproject((const float *)in, 1, out, N, H, W, C, dtype, plan, wht_path_from_env(),
                                   (hipStream_t)stream));
     return LBP_OK;
 }
@@ -293,8 +307,10 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
     DeviceState *st;
     rc = current_device(&dev, &st);
     if (rc) return rc;
+    const lbp::GemmPath gpath = gemm_path_from_env();
+    const bool can_fuse = fuse_unproject_from_env() && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
     lbp::WorkspacePlan ws;
-    rc = lbp::plan_workspace(shape, patch, r, st->num_cus, &ws);
+    rc = lbp::plan_workspace(shape, patch, r, st->num_cus, can_fuse, &ws);
     if (rc) return rc;
     char *base = nullptr;
     rc = get_workspace(st, ws.total, &base);
@@ -314,12 +330,11 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
 
     // g^y = WHT(gy; I)   (second statement of Algorithm 1; needed by both products)
     LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s));
-    const lbp::GemmPath gpath = gemm_path_from_env();
     if (gW) {
         // x^ = WHT(x; I), then g~w = g^w = g^y^T x^  (with the 1/p^2 of the normalisation)
         LBP_HIP(lbp::launch_project(x, x_r, N, H, Wd, Cin, dt, plan, path, s));
-        rc = weight_gradient(gy_r, x_r, Cout, Cin, Mr, dt, shape->gw_dtype, ws.splits_gw, inv_pp, part,
-                             gW, gpath, s);
+        rc = weight_gradient(gy_r, x_r, Cout, Cin, Mr, dt, shape->gw_dtype, ws.gw, inv_pp, part, gW,
+                             gpath, s);
         if (rc) return rc;
     }
     if (gx) {
@@ -331,18 +346,20 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
         g.lda = Cout; g.ldb = Cin;
         g.a_kfast = true;
         g.dtype = dt;
-        g.splits = 1;
-        if (fuse_unproject_from_env() && lbp::gemm_can_fuse_unproject(plan, dt, gpath)) {
+        g.tile = ws.gx.tile;
+        if (ws.gx_fused) {
+            g.splits = 1;
             g.out = lbp::GemmOut::kUnproject;
             g.C = gx;
             g.grid_h = H; g.grid_w = Wd;
             g.plan = &plan;
             LBP_HIP(lbp::launch_gemm(g, gpath, s));
         } else {
+            g.splits = ws.gx.splits;
             g.out = lbp::GemmOut::kF32;
             g.C = gx_r;
             LBP_HIP(lbp::launch_gemm(g, gpath, s));
-            LBP_HIP(lbp::launch_unproject(gx_r, gx, N, H, Wd, Cin, dt, plan, path, s));
+            LBP_HIP(lbp::launch_unproject(gx_r, ws.gx.splits, gx, N, H, Wd, Cin, dt, plan, path, s));
         }
     }
     return LBP_OK;
@@ -363,7 +380,7 @@ int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_sha
     const int Cin = shape->Cin, Cout = shape->Cout, dt = shape->dtype;
     const long M = (long)shape->N * shape->H * shape->W;
     lbp::WorkspacePlan ws;
-    rc = lbp::plan_workspace(shape, 0, 0, st->num_cus, &ws);
+    rc = lbp::plan_workspace(shape, 0, 0, st->num_cus, false, &ws);
     if (rc) return rc;
     // the plain bf16 kernel needs an fp32 staging buffer of M x Cin for gx
     size_t gx_stage = gx && dt == LBP_BF16 && gemm_path_from_env() == lbp::GemmPath::kSimple
@@ -376,8 +393,7 @@ int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_sha
 
     const lbp::GemmPath gpath = gemm_path_from_env();
     if (gW) {   // gW = gy^T x  (Eq. 2)
-        rc = weight_gradient(gy, x, Cout, Cin, M, dt, shape->gw_dtype, ws.splits_gw, 1.0f, part, gW,
-                             gpath, s);
+        rc = weight_gradient(gy, x, Cout, Cin, M, dt, shape->gw_dtype, ws.gw, 1.0f, part, gW, gpath, s);
         if (rc) return rc;
     }
     if (gx) {   // gx = gy W  (Eq. 2)
@@ -393,6 +409,7 @@ int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_sha
             g.C = gx;
             LBP_HIP(lbp::launch_gemm(g, gpath, s));
         } else if (gpath != lbp::GemmPath::kSimple) {
+            g.tile = ws.gx.tile;
             g.out = lbp::GemmOut::kBF16;
             g.C = gx;
             LBP_HIP(lbp::launch_gemm(g, gpath, s));

@@ -141,47 +141,97 @@ bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb)
     return a0 < b0 + nb && b0 < a0 + na;
 }
 
-int choose_splits(long M, long N, long K, int tile_m, int tile_n, int num_cus, int min_k)
+const GemmTileInfo kGemmTiles[kNumGemmTiles] = {
+    {128, 128, true, 1.0},
+    {64, 128, true, 1.0},
+    {256, 128, false, 1.15},
+    {256, 256, false, 1.4},
+};
+
+GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split, int fused_r,
+                   int fused_patch, int num_cus)
 {
-    long tiles = ((M + tile_m - 1) / tile_m) * ((N + tile_n - 1) / tile_n);
-    if (tiles < 1) tiles = 1;
-    long by_fill = num_cus / tiles;
-    long by_k = K / min_k;
-    long s = std::min(by_fill, by_k);
-    if (s < 1) s = 1;
-    if (s > 256) s = 256;
-    return (int)s;
+    const double kFill = 20.0;            // bytes per clock a compute unit takes in from L2
+    const double kClkPerUs = 2400.0;
+    const double kWgFixed = 3000.0;       // clocks of prologue and drain per workgroup
+    const int kStep = 64;                 // reduction elements per step of the kernel
+    if (num_cus < 1) num_cus = 256;
+    GemmPlan best{0, 1, 1e300};
+    for (int t = 0; t < kNumGemmTiles; ++t) {
+        const GemmTileInfo &ti = kGemmTiles[t];
+        if (fused_r > 0 && (!ti.fused || fused_r > ti.bm)) continue;
+        const long bm_step = fused_r > 0 ? ti.bm / fused_r * fused_r : ti.bm;
+        const long tiles = ((M + bm_step - 1) / bm_step) * ((N + ti.bn - 1) / ti.bn);
+        const int max_splits = (allow_split && fused_r == 0) ? 64 : 1;
+        for (int sp = 1; sp <= max_splits; ++sp) {
+            const long k_slice = (K + sp - 1) / sp;
+            if (sp > 1 && k_slice < 4 * kStep) break;
+            const double steps = (double)((k_slice + kStep - 1) / kStep);
+            const double fill = steps * (ti.bm + ti.bn) * kStep * 2.0;
+            double out;
+            if (fused_r > 0)
+                out = (double)(bm_step / fused_r) * fused_patch * fused_patch * ti.bn * 2.0;
+            else
+                out = (double)ti.bm * ti.bn * (sp > 1 ? 4 : out_elem_bytes);
+            const double mfma = steps * 2.0 * ti.bm * ti.bn * kStep / 4096.0;
+            double wg = (fill + out) / kFill;
+            if (mfma > wg) wg = mfma;
+            wg = wg * ti.slowdown + kWgFixed;
+            const double rounds = (double)((tiles * sp + num_cus - 1) / num_cus);
+            double clk = rounds * wg;
+            if (sp > 1)   // the reduction kernel: launch gap plus (sp reads + 1 write) of M*N
+                clk += 8000.0 + (double)(sp * 4 + out_elem_bytes) * M * N / (num_cus * kFill);
+            if (clk < best.est_us) best = GemmPlan{t, sp, clk};
+        }
+    }
+    best.est_us /= kClkPerUs;
+    return best;
 }
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, WorkspacePlan *ws)
+int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
+                   WorkspacePlan *ws)
 {
     if (!s || !ws) return LBP_ERR_NULL;
     std::memset(ws, 0, sizeof *ws);
-    size_t esz = dtype_size(s->dtype);
-    long M = (long)s->N * s->H * s->W;
+    if (num_cus < 1) num_cus = 256;
+    const size_t esz = dtype_size(s->dtype);
+    const int gw_bytes = (int)dtype_size(s->gw_dtype);
+    const long M = (long)s->N * s->H * s->W;
     size_t off = 0;
     if (patch == 0) {
         // full-rank backward: only the split-K partial sums of gW
-        ws->splits_gx = 1;
-        ws->splits_gw = choose_splits(s->Cout, s->Cin, M, 128, 128, num_cus, 512);
+        ws->gw = plan_gemm(s->Cout, s->Cin, M, gw_bytes, true, 0, 0, num_cus);
+        ws->gx = plan_gemm(M, s->Cin, s->Cout, (int)esz, false, 0, 0, num_cus);
         ws->splitk = off;
-        off += align_up((size_t)ws->splits_gw * s->Cout * s->Cin * 4, 256);
+        off += align_up((size_t)ws->gw.splits * s->Cout * s->Cin * 4, 256);
         ws->total = off;
         return LBP_OK;
     }
-    long Mr = M / ((long)patch * patch) * r;
+    const long Mr = M / ((long)patch * patch) * r;
+    ws->gw = plan_gemm(s->Cout, s->Cin, Mr, gw_bytes, true, 0, 0, num_cus);
+    // gx: fused epilogue (no split, few workgroups when Mr is small) against split-K partial sums
+    // that the reverse-projection kernel adds up while it reads them
+    GemmPlan unfused = plan_gemm(Mr, s->Cin, s->Cout, 4, true, 0, 0, num_cus);
+    unfused.est_us += 3.0 + (double)M * s->Cin * esz / (num_cus * 20.0 * 2400.0);
+    ws->gx = unfused;
+    ws->gx_fused = false;
+    if (can_fuse && s->dtype == LBP_BF16) {
+        GemmPlan fused = plan_gemm(Mr, s->Cin, s->Cout, 2, false, r, patch, num_cus);
+        if (fused.est_us <= unfused.est_us) {
+            ws->gx = fused;
+            ws->gx_fused = true;
+        }
+    }
     ws->gy_r = off;
     off += align_up((size_t)Mr * s->Cout * esz, 256);
     ws->x_r = off;
     off += align_up((size_t)Mr * s->Cin * esz, 256);
     ws->gx_r = off;
-    off += align_up((size_t)Mr * s->Cin * 4, 256);
-    ws->splits_gw = choose_splits(s->Cout, s->Cin, Mr, 128, 128, num_cus, 256);
-    ws->splits_gx = 1;
+    if (!ws->gx_fused) off += align_up((size_t)ws->gx.splits * Mr * s->Cin * 4, 256);
     ws->splitk = off;
-    off += align_up((size_t)ws->splits_gw * s->Cout * s->Cin * 4, 256);
+    off += align_up((size_t)ws->gw.splits * s->Cout * s->Cin * 4, 256);
     ws->total = off;
     return LBP_OK;
 }

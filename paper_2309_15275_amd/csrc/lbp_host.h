@@ -58,21 +58,47 @@ int validate_alignment(const void *const *ptrs, int n);
 // [a, a+na) and [b, b+nb) overlap?
 bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb);
 
+// Tile shapes of the bf16 matrix-core GEMM (gemm_mfma_*.hip instantiates them in this order).
+struct GemmTileInfo {
+    int bm, bn;        // output tile of one workgroup
+    bool fused;        // has the fused reverse-projection epilogue
+    double slowdown;   // measured factor over the simple cost model below
+};
+constexpr int kNumGemmTiles = 4;
+extern const GemmTileInfo kGemmTiles[kNumGemmTiles];
+
+// How one matrix product is run.
+struct GemmPlan {
+    int tile;          // index into kGemmTiles
+    int splits;        // split-K slices (1 = the kernel writes the final output itself)
+    double est_us;     // cost-model estimate, for diagnostics
+};
+
+// Picks tile shape and split-K factor for C[M][N] = A * B with reduction length K.
+//   out_elem_bytes  size of one output element when the kernel stores the result itself
+//   allow_split     the caller can reduce fp32 partial results afterwards
+//   fused_r/patch   non-zero: the reverse projection is fused into the epilogue (rows are
+//                   (patch, basis) pairs, r bases kept); implies no split
+// The model: a compute unit takes in about 20 bytes a clock from L2 however many loads are in
+// flight, so a workgroup's time is its operand and output bytes over that rate (or its matrix-core
+// time if larger), and the workgroups run in ceil(count / compute units) rounds.
+GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split, int fused_r,
+                   int fused_patch, int num_cus);
+
 // Workspace layout of one backward call; offsets in bytes from the workspace base, each
 // 256-byte aligned.  Sizes of 0 mean "not used".
 struct WorkspacePlan {
     size_t gy_r, x_r, gx_r, splitk;   // offsets
     size_t total;                      // bytes
-    int splits_gw;                     // split-K factor of the weight-gradient product
-    int splits_gx;                     // split-K factor of the input-gradient product (full rank: 1)
+    GemmPlan gw;                       // the weight-gradient product
+    GemmPlan gx;                       // the input-gradient product
+    bool gx_fused;                     // reverse projection fused into that product's epilogue
 };
 
-// num_cus: compute units of the device (used to pick split-K factors); pass 256 when unknown.
-int plan_workspace(const lbp_shape_t *shape, int patch, int r, int num_cus, WorkspacePlan *ws);
-
-// Split-K factor for an M x N output with reduction length K: enough slices that the tiles fill
-// `num_cus` compute units once or twice, each slice at least `min_k` long.
-int choose_splits(long M, long N, long K, int tile_m, int tile_n, int num_cus, int min_k);
+// num_cus: compute units of the device (the GEMM plans depend on it); pass 256 when unknown.
+// can_fuse: the selection allows the fused reverse projection (false gives the larger workspace).
+int plan_workspace(const lbp_shape_t *shape, int patch, int r, int num_cus, bool can_fuse,
+                   WorkspacePlan *ws);
 
 const char *status_string(int code);
 

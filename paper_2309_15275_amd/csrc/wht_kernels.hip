@@ -74,7 +74,8 @@ template <int LP, int MH, int MW, bool BF16>
 __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__restrict__ in,
                                                                 uint32_t *__restrict__ out,
                                                                 long items, int Cd, GridGeom g,
-                                                                PooledSel sel, int r)
+                                                                PooledSel sel, int r, int slices,
+                                                                size_t slice_stride)
 {
     constexpr int P = 1 << LP;
     constexpr int PWd = P >> MW;
@@ -93,7 +94,15 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
 #pragma unroll
         for (int j = 0; j < NC; ++j) {
             float2 t = make_float2(0.f, 0.f);
-            if ((sel.mask >> j) & 1ull) t = src[(size_t)sel.pos[j] * Cd];
+            if ((sel.mask >> j) & 1ull) {
+                const float2 *sp = src + (size_t)sel.pos[j] * Cd;
+                t = *sp;
+                for (int z = 1; z < slices; ++z) {      // fixed order: deterministic sums
+                    float2 u = *reinterpret_cast<const float2 *>(reinterpret_cast<const float *>(sp) + z * slice_stride);
+                    t.x += u.x;
+                    t.y += u.y;
+                }
+            }
             c0[j] = t.x;
             c1[j] = t.y;
         }
@@ -113,7 +122,11 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
 #pragma unroll
         for (int j = 0; j < NC; ++j) {
             float t = 0.f;
-            if ((sel.mask >> j) & 1ull) t = src[(size_t)sel.pos[j] * Cd];
+            if ((sel.mask >> j) & 1ull) {
+                const float *sp = src + (size_t)sel.pos[j] * Cd;
+                t = *sp;
+                for (int z = 1; z < slices; ++z) t += sp[z * slice_stride];
+            }
             c0[j] = t;
         }
         fwht_inplace<NC>(c0);
@@ -207,7 +220,8 @@ __global__ __launch_bounds__(128) void wht_project_generic_kernel(const uint4 *_
 template <bool BF16>
 __global__ __launch_bounds__(128) void wht_unproject_generic_kernel(const float *__restrict__ in,
                                                                     uint4 *__restrict__ out, int Cv,
-                                                                    GridGeom g, NatTable nat, int r)
+                                                                    GridGeom g, NatTable nat, int r,
+                                                                    int slices, size_t slice_stride)
 {
     constexpr int VN = Vec16<BF16>::N;
     constexpr int TC = 4;
@@ -230,6 +244,10 @@ __global__ __launch_bounds__(128) void wht_unproject_generic_kernel(const float 
 #pragma unroll
             for (int e = 0; e < VN; e += 4) {
                 float4 t4 = *reinterpret_cast<const float4 *>(src + (size_t)k * C + e);
+                for (int z = 1; z < slices; ++z) {
+                    float4 u4 = *reinterpret_cast<const float4 *>(src + z * slice_stride + (size_t)k * C + e);
+                    t4.x += u4.x; t4.y += u4.y; t4.z += u4.z; t4.w += u4.w;
+                }
                 f[e] = t4.x; f[e + 1] = t4.y; f[e + 2] = t4.z; f[e + 3] = t4.w;
             }
 #pragma unroll
@@ -265,14 +283,21 @@ GridGeom make_geom(int H, int W, int patch)
     return g;
 }
 
+// Slices of the reverse direction's input (split-K partial sums) and their pitch in floats.
+struct Slices {
+    int count = 1;
+    size_t stride = 0;
+};
+
 template <bool UNPROJECT, int LP, int MH, int MW, bool BF16>
 void launch_reg_one(const void *in, void *out, long items, int Cd, const GridGeom &g,
-                    const PooledSel &sel, int r, hipStream_t stream)
+                    const PooledSel &sel, int r, Slices sl, hipStream_t stream)
 {
     unsigned blocks = (unsigned)((items + 255) / 256);
     if (UNPROJECT)
         hipLaunchKernelGGL((wht_unproject_reg_kernel<LP, MH, MW, BF16>), dim3(blocks), dim3(256), 0,
-                           stream, (const float *)in, (uint32_t *)out, items, Cd, g, sel, r);
+                           stream, (const float *)in, (uint32_t *)out, items, Cd, g, sel, r, sl.count,
+                           sl.stride);
     else
         hipLaunchKernelGGL((wht_project_reg_kernel<LP, MH, MW, BF16>), dim3(blocks), dim3(256), 0,
                            stream, (const uint32_t *)in, (uint32_t *)out, items, Cd, g, sel, r);
@@ -280,31 +305,31 @@ void launch_reg_one(const void *in, void *out, long items, int Cd, const GridGeo
 
 template <bool UNPROJECT, int LP, int MH, bool BF16>
 void launch_reg_mw(int mw, const void *in, void *out, long items, int Cd, const GridGeom &g,
-                   const PooledSel &sel, int r, hipStream_t s)
+                   const PooledSel &sel, int r, Slices sl, hipStream_t s)
 {
     switch (mw) {
-        case 0: launch_reg_one<UNPROJECT, LP, MH, 0, BF16>(in, out, items, Cd, g, sel, r, s); break;
-        case 1: launch_reg_one<UNPROJECT, LP, MH, (LP >= 1 ? 1 : 0), BF16>(in, out, items, Cd, g, sel, r, s); break;
-        case 2: launch_reg_one<UNPROJECT, LP, MH, (LP >= 2 ? 2 : 0), BF16>(in, out, items, Cd, g, sel, r, s); break;
-        default: launch_reg_one<UNPROJECT, LP, MH, (LP >= 3 ? 3 : 0), BF16>(in, out, items, Cd, g, sel, r, s); break;
+        case 0: launch_reg_one<UNPROJECT, LP, MH, 0, BF16>(in, out, items, Cd, g, sel, r, sl, s); break;
+        case 1: launch_reg_one<UNPROJECT, LP, MH, (LP >= 1 ? 1 : 0), BF16>(in, out, items, Cd, g, sel, r, sl, s); break;
+        case 2: launch_reg_one<UNPROJECT, LP, MH, (LP >= 2 ? 2 : 0), BF16>(in, out, items, Cd, g, sel, r, sl, s); break;
+        default: launch_reg_one<UNPROJECT, LP, MH, (LP >= 3 ? 3 : 0), BF16>(in, out, items, Cd, g, sel, r, sl, s); break;
     }
 }
 
 template <bool UNPROJECT, int LP, bool BF16>
 void launch_reg_mh(int mh, int mw, const void *in, void *out, long items, int Cd, const GridGeom &g,
-                   const PooledSel &sel, int r, hipStream_t s)
+                   const PooledSel &sel, int r, Slices sl, hipStream_t s)
 {
     switch (mh) {
-        case 0: launch_reg_mw<UNPROJECT, LP, 0, BF16>(mw, in, out, items, Cd, g, sel, r, s); break;
-        case 1: launch_reg_mw<UNPROJECT, LP, (LP >= 1 ? 1 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, s); break;
-        case 2: launch_reg_mw<UNPROJECT, LP, (LP >= 2 ? 2 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, s); break;
-        default: launch_reg_mw<UNPROJECT, LP, (LP >= 3 ? 3 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, s); break;
+        case 0: launch_reg_mw<UNPROJECT, LP, 0, BF16>(mw, in, out, items, Cd, g, sel, r, sl, s); break;
+        case 1: launch_reg_mw<UNPROJECT, LP, (LP >= 1 ? 1 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, sl, s); break;
+        case 2: launch_reg_mw<UNPROJECT, LP, (LP >= 2 ? 2 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, sl, s); break;
+        default: launch_reg_mw<UNPROJECT, LP, (LP >= 3 ? 3 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, sl, s); break;
     }
 }
 
 template <bool UNPROJECT>
 hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int dtype,
-                      const BasisPlan &plan, hipStream_t s)
+                      const BasisPlan &plan, Slices sl, hipStream_t s)
 {
     const bool bf16 = dtype == LBP_BF16;
     const int Cd = bf16 ? C / 2 : C;
@@ -318,16 +343,16 @@ hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int
     const int mh = plan.mh, mw = plan.mw, r = plan.r;
     switch (plan.log2p) {
         case 1:
-            if (bf16) launch_reg_mh<UNPROJECT, 1, true>(mh, mw, in, out, items, Cd, g, sel, r, s);
-            else launch_reg_mh<UNPROJECT, 1, false>(mh, mw, in, out, items, Cd, g, sel, r, s);
+            if (bf16) launch_reg_mh<UNPROJECT, 1, true>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
+            else launch_reg_mh<UNPROJECT, 1, false>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
             break;
         case 2:
-            if (bf16) launch_reg_mh<UNPROJECT, 2, true>(mh, mw, in, out, items, Cd, g, sel, r, s);
-            else launch_reg_mh<UNPROJECT, 2, false>(mh, mw, in, out, items, Cd, g, sel, r, s);
+            if (bf16) launch_reg_mh<UNPROJECT, 2, true>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
+            else launch_reg_mh<UNPROJECT, 2, false>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
             break;
         case 3:
-            if (bf16) launch_reg_mh<UNPROJECT, 3, true>(mh, mw, in, out, items, Cd, g, sel, r, s);
-            else launch_reg_mh<UNPROJECT, 3, false>(mh, mw, in, out, items, Cd, g, sel, r, s);
+            if (bf16) launch_reg_mh<UNPROJECT, 3, true>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
+            else launch_reg_mh<UNPROJECT, 3, false>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
             break;
         default: return hipErrorInvalidValue;
     }
@@ -336,7 +361,7 @@ hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int
 
 template <bool UNPROJECT>
 hipError_t launch_generic(const void *in, void *out, int N, int H, int W, int C, int dtype,
-                          const BasisPlan &plan, hipStream_t s)
+                          const BasisPlan &plan, Slices sl, hipStream_t s)
 {
     const bool bf16 = dtype == LBP_BF16;
     const int Cv = bf16 ? C / 8 : C / 4;
@@ -348,10 +373,10 @@ hipError_t launch_generic(const void *in, void *out, int N, int H, int W, int C,
     if (UNPROJECT) {
         if (bf16)
             hipLaunchKernelGGL(wht_unproject_generic_kernel<true>, grid, dim3(128), 0, s,
-                               (const float *)in, (uint4 *)out, Cv, g, nat, plan.r);
+                               (const float *)in, (uint4 *)out, Cv, g, nat, plan.r, sl.count, sl.stride);
         else
             hipLaunchKernelGGL(wht_unproject_generic_kernel<false>, grid, dim3(128), 0, s,
-                               (const float *)in, (uint4 *)out, Cv, g, nat, plan.r);
+                               (const float *)in, (uint4 *)out, Cv, g, nat, plan.r, sl.count, sl.stride);
     } else {
         if (bf16)
             hipLaunchKernelGGL(wht_project_generic_kernel<true>, grid, dim3(128), 0, s,
@@ -376,17 +401,21 @@ hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C,
 {
     if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
     if (use_register_path(plan, path))
-        return launch_reg<false>(in, out, N, H, W, C, dtype, plan, stream);
-    return launch_generic<false>(in, out, N, H, W, C, dtype, plan, stream);
+        return launch_reg<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
+    return launch_generic<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
 }
 
-hipError_t launch_unproject(const float *in, void *out, int N, int H, int W, int C, int dtype,
-                            const BasisPlan &plan, WhtPath path, hipStream_t stream)
+hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H, int W, int C,
+                            int dtype, const BasisPlan &plan, WhtPath path, hipStream_t stream)
 {
     if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
+    if (slices < 1) return hipErrorInvalidValue;
+    Slices sl;
+    sl.count = slices;
+    sl.stride = (size_t)N * (H / plan.patch) * (W / plan.patch) * plan.r * C;
     if (use_register_path(plan, path))
-        return launch_reg<true>(in, out, N, H, W, C, dtype, plan, stream);
-    return launch_generic<true>(in, out, N, H, W, C, dtype, plan, stream);
+        return launch_reg<true>(in, out, N, H, W, C, dtype, plan, sl, stream);
+    return launch_generic<true>(in, out, N, H, W, C, dtype, plan, sl, stream);
 }
 
 }  // namespace lbp

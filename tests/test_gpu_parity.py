@@ -21,7 +21,7 @@ def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     yield
-    for var in ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT"):
+    for var in ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT", "LBP_GEMM_TILE"):
         os.environ.pop(var, None)
     torch.cuda.synchronize()
 
@@ -144,6 +144,32 @@ def test_backward_matches_oracle_on_ragged_shapes(dtype, case, variant):
     idx = oracle.select_bases(patch, r, order)
     egx, egw = run_backward_case(wl, idx)
     assert egx <= TOL[dtype] and egw <= TOL[dtype], (egx, egw)
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("case", [0, 3, 10, 13])
+def test_every_gemm_tile_shape_matches_oracle(case, tile):
+    # LBP_GEMM_TILE forces one tile shape of the matrix-core kernel for every product of the call
+    os.environ["LBP_GEMM_TILE"] = str(tile)
+    N, H, W, Cin, Cout, patch, r, order = RAGGED[case]
+    wl = small("tiles", N, H, W, Cin, Cout, patch, "bf16", 400 + case)
+    idx = oracle.select_bases(patch, r, order)
+    egx, egw = run_backward_case(wl, idx)
+    assert egx <= TOL["bf16"] and egw <= TOL["bf16"], (egx, egw)
+    host, dev = device_inputs(wl)
+    gx, gW = binding.full_bp_backward(dev["x"], dev["gy"], dev["w"])
+    gx0, gW0 = oracle.full_bp_backward(host["x"], host["gy"], host["w"])
+    assert rel_fro(to_host(gx), gx0) <= 5e-3 and rel_fro(to_host(gW), gW0) <= 5e-3
+
+
+def test_split_k_partial_sums_feed_the_reverse_projection():
+    # few rows, long reduction: the planner splits the input-gradient product over K and the
+    # reverse-projection kernel adds the slices up
+    wl = small("splitgx", 1, 8, 16, 64, 4096, 8, "bf16", 450)
+    for r in (4, 21):
+        idx = oracle.select_bases(8, r, "l1")
+        egx, egw = run_backward_case(wl, idx)
+        assert egx <= TOL["bf16"] and egw <= TOL["bf16"], (r, egx, egw)
 
 
 def test_arbitrary_unordered_selection_backward():
