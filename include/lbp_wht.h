@@ -100,6 +100,17 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
                      int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream);
 
 /*
+ * For measurement, not part of the method: the same call as lbp_wht_backward, bracketed by HIP
+ * events on `stream`.  It WAITS for the work to finish and returns the elapsed milliseconds of the
+ * three stages in stage_ms (host, 3 floats): [0] projection of gy and x, [1] weight-gradient
+ * product, [2] input-gradient product with the reverse projection.  Callers: benchmarks that
+ * report where the time of a call goes.
+ */
+int lbp_wht_backward_profile(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
+                             int patch, const int32_t *basis_idx, int r, void *gx, void *gW,
+                             void *stream, float *stage_ms);
+
+/*
  * Exact backward of Eq. 2 (Section 2), the full-rank comparison point built from the same
  * kernels: gx = gy W (per token), gW = gy^T x (summed over all tokens).  Same argument rules.
  */

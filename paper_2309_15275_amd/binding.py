@@ -17,7 +17,7 @@ _ORDERS = {"l1": ORDER_L1, "linf": ORDER_LINF, ORDER_L1: ORDER_L1, ORDER_LINF: O
 _DTYPES = {torch.float32: LBP_F32, torch.bfloat16: LBP_BF16}
 
 # every symbol include/lbp_wht.h declares
-EXPORTS = ("lbp_wht_select_bases", "lbp_wht_backward", "full_bp_backward", "lbp_wht_project",
+EXPORTS = ("lbp_wht_select_bases", "lbp_wht_backward", "lbp_wht_backward_profile", "full_bp_backward", "lbp_wht_project",
            "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
            "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version")
 
@@ -51,6 +51,8 @@ def load():
     shp = ctypes.POINTER(LbpShape)
     lib.lbp_wht_select_bases.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p]
     lib.lbp_wht_backward.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.lbp_wht_backward_profile.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp,
+                                             ctypes.POINTER(ctypes.c_float)]
     lib.full_bp_backward.argtypes = [vp, vp, vp, shp, vp, vp, vp]
     lib.lbp_wht_project.argtypes = [vp] + [ctypes.c_int] * 6 + [i32p, ctypes.c_int, vp, vp]
     lib.lbp_wht_unproject.argtypes = [vp] + [ctypes.c_int] * 6 + [i32p, ctypes.c_int, vp, vp]
@@ -137,6 +139,20 @@ def lbp_wht_backward(x, gy, w, patch, basis_idx, gx=None, gW=None, want_gx=True,
             _dev_tensor(gx, "gx", x.dtype) if gx is not None else None,
             _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
     return gx, gW
+
+
+def lbp_wht_backward_profile(x, gy, w, patch, basis_idx, gx, gW, stream=None):
+    """lbp_wht_backward bracketed by HIP events; waits, returns the three stage times in ms:
+    (projection, weight-gradient product, input-gradient product + reverse projection)."""
+    shape = make_shape(x, gy, w, gW.dtype)
+    idx, r = _idx_array(basis_idx)
+    ms = (ctypes.c_float * 3)()
+    with torch.cuda.device(x.device):
+        _check(load().lbp_wht_backward_profile(
+            _dev_tensor(x, "x"), _dev_tensor(gy, "gy", x.dtype), _dev_tensor(w, "w", x.dtype),
+            ctypes.byref(shape), int(patch), idx, r, _dev_tensor(gx, "gx", x.dtype),
+            _dev_tensor(gW, "gW"), _stream_ptr(stream), ms))
+    return tuple(ms)
 
 
 def full_bp_backward(x, gy, w, gx=None, gW=None, want_gx=True, want_gw=True,

@@ -15,6 +15,12 @@ enum class GemmPath { kAuto = 0, kSimple = 1 };
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
                           const BasisPlan &plan, WhtPath path, hipStream_t stream);
 
+// The same for two tensors on one token grid (gy and x of a backward call) in ONE launch where
+// the kernels allow it, so that the second, smaller tensor fills the tail of the first.
+hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
+                               int N, int H, int W, int dtype, const BasisPlan &plan, WhtPath path,
+                               hipStream_t stream);
+
 // p^-1(.) of Eq. 7 per patch with the 1/p^2 factor: in fp32 [slices][P*r][C] (the slices are
 // summed first: split-K partial results) -> out [N][H][W][C] of `dtype`.
 hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H, int W, int C,

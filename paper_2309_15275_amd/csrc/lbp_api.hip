@@ -290,8 +290,14 @@ int lbp_wht_unproject(const void *in, int N, int H, int W, int C, int dtype, int
     return LBP_OK;
 }
 
-int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
-                     int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream)
+}  // extern "C"
+
+namespace {
+
+// Algorithm 1.  `ev`, when not NULL, holds 4 events recorded on the stream before the projection,
+// after it, after the weight-gradient product and after the input-gradient product.
+int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_t *shape, int patch,
+                  const int32_t *basis_idx, int r, void *gx, void *gW, void *stream, hipEvent_t *ev)
 {
     if (!shape || !basis_idx) return LBP_ERR_NULL;
     if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
@@ -328,15 +334,21 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
     float *gx_r = (float *)(base + ws.gx_r);
     float *part = (float *)(base + ws.splitk);
 
-    // g^y = WHT(gy; I)   (second statement of Algorithm 1; needed by both products)
-    LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s));
+    if (ev) LBP_HIP(hipEventRecord(ev[0], s));
+    // g^y = WHT(gy; I) is needed by both products; x^ = WHT(x; I) only by the weight gradient
+    // (first two statements of Algorithm 1).  One launch covers both tensors.
+    if (gW)
+        LBP_HIP(lbp::launch_project_pair(gy, gy_r, Cout, x, x_r, Cin, N, H, Wd, dt, plan, path, s));
+    else
+        LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s));
+    if (ev) LBP_HIP(hipEventRecord(ev[1], s));
     if (gW) {
-        // x^ = WHT(x; I), then g~w = g^w = g^y^T x^  (with the 1/p^2 of the normalisation)
-        LBP_HIP(lbp::launch_project(x, x_r, N, H, Wd, Cin, dt, plan, path, s));
+        // g~w = g^w = g^y^T x^  (with the 1/p^2 of the normalisation)
         rc = weight_gradient(gy_r, x_r, Cout, Cin, Mr, dt, shape->gw_dtype, ws.gw, inv_pp, part, gW,
                              gpath, s);
         if (rc) return rc;
     }
+    if (ev) LBP_HIP(hipEventRecord(ev[2], s));
     if (gx) {
         // g^x = g^y w, then g~x = WHT^-1(g^x; I): fused into the product's epilogue when the
         // kernel supports the selection, else through an fp32 buffer and a kernel of its own
@@ -362,7 +374,38 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
             LBP_HIP(lbp::launch_unproject(gx_r, ws.gx.splits, gx, N, H, Wd, Cin, dt, plan, path, s));
         }
     }
+    if (ev) LBP_HIP(hipEventRecord(ev[3], s));
     return LBP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
+                     int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream)
+{
+    return backward_impl(x, gy, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr);
+}
+
+int lbp_wht_backward_profile(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
+                             int patch, const int32_t *basis_idx, int r, void *gx, void *gW,
+                             void *stream, float *stage_ms)
+{
+    if (!stage_ms) return LBP_ERR_NULL;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    int rc = LBP_OK;
+    for (int i = 0; i < 4 && rc == LBP_OK; ++i)
+        if (hipEventCreate(&ev[i]) != hipSuccess) rc = hip_fail(hipGetLastError());
+    if (rc == LBP_OK) rc = backward_impl(x, gy, W, shape, patch, basis_idx, r, gx, gW, stream, ev);
+    if (rc == LBP_OK) {
+        hipError_t e = hipEventSynchronize(ev[3]);
+        for (int i = 0; i < 3 && e == hipSuccess; ++i) e = hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]);
+        if (e != hipSuccess) rc = hip_fail(e);
+    }
+    for (int i = 0; i < 4; ++i)
+        if (ev[i]) (void)hipEventDestroy(ev[i]);
+    return rc;
 }
 
 int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,

@@ -25,19 +25,30 @@ namespace {
 // register kernels
 // ------------------------------------------------------------------------------------------
 
+// One tensor of a projection launch.  A launch can carry two (gy and x of one backward call):
+// the first `blocks` workgroups belong to tensor 0, the rest to tensor 1.
+struct ProjTensor {
+    const uint32_t *in;
+    uint32_t *out;
+    long items;         // patches * 32-bit channel columns
+    int Cd;             // 32-bit channel columns per token
+    unsigned blocks;    // workgroups of this tensor
+};
+
 template <int LP, int MH, int MW, bool BF16>
-__global__ __launch_bounds__(256) void wht_project_reg_kernel(const uint32_t *__restrict__ in,
-                                                              uint32_t *__restrict__ out,
-                                                              long items, int Cd, GridGeom g,
+__global__ __launch_bounds__(256) void wht_project_reg_kernel(ProjTensor t0, ProjTensor t1, GridGeom g,
                                                               PooledSel sel, int r)
 {
     constexpr int P = 1 << LP;
     constexpr int NC = (P >> MH) * (P >> MW);
-    long item = (long)blockIdx.x * 256 + threadIdx.x;
-    if (item >= items) return;
+    const bool second = blockIdx.x >= t0.blocks;
+    const ProjTensor &t = second ? t1 : t0;
+    const int Cd = t.Cd;
+    long item = (long)(blockIdx.x - (second ? t0.blocks : 0u)) * 256 + threadIdx.x;
+    if (item >= t.items) return;
     long q = item / Cd;
     int cd = (int)(item - q * Cd);
-    const uint32_t *src = in + (size_t)g.first_token(q) * Cd + cd;
+    const uint32_t *src = t.in + (size_t)g.first_token(q) * Cd + cd;
 
     uint32_t raw[P * P];
 #pragma unroll
@@ -49,14 +60,14 @@ __global__ __launch_bounds__(256) void wht_project_reg_kernel(const uint32_t *__
     float v[P * P];
     float c0[NC];
 #pragma unroll
-    for (int t = 0; t < P * P; ++t) v[t] = BF16 ? bf16_lo_to_f32(raw[t]) : __uint_as_float(raw[t]);
+    for (int i = 0; i < P * P; ++i) v[i] = BF16 ? bf16_lo_to_f32(raw[i]) : __uint_as_float(raw[i]);
     pooled_transform<P, MH, MW>(v, c0);
 
-    uint32_t *dst = out + (size_t)q * r * Cd + cd;
+    uint32_t *dst = t.out + (size_t)q * r * Cd + cd;
     if (BF16) {
         float c1[NC];
 #pragma unroll
-        for (int t = 0; t < P * P; ++t) v[t] = bf16_hi_to_f32(raw[t]);
+        for (int i = 0; i < P * P; ++i) v[i] = bf16_hi_to_f32(raw[i]);
         pooled_transform<P, MH, MW>(v, c1);
 #pragma unroll
         for (int j = 0; j < NC; ++j)
@@ -289,52 +300,74 @@ struct Slices {
     size_t stride = 0;
 };
 
+// Second tensor of a projection launch (unused by the reverse direction).
+struct Second {
+    const void *in = nullptr;
+    void *out = nullptr;
+    long items = 0;
+    int Cd = 0;
+};
+
 template <bool UNPROJECT, int LP, int MH, int MW, bool BF16>
 void launch_reg_one(const void *in, void *out, long items, int Cd, const GridGeom &g,
-                    const PooledSel &sel, int r, Slices sl, hipStream_t stream)
+                    const PooledSel &sel, int r, Slices sl, Second sec, hipStream_t stream)
 {
     unsigned blocks = (unsigned)((items + 255) / 256);
+    if (!UNPROJECT) {
+        ProjTensor t0{(const uint32_t *)in, (uint32_t *)out, items, Cd, blocks};
+        ProjTensor t1{(const uint32_t *)sec.in, (uint32_t *)sec.out, sec.items, sec.Cd > 0 ? sec.Cd : 1,
+                      (unsigned)((sec.items + 255) / 256)};
+        hipLaunchKernelGGL((wht_project_reg_kernel<LP, MH, MW, BF16>), dim3(t0.blocks + t1.blocks),
+                           dim3(256), 0, stream, t0, t1, g, sel, r);
+        return;
+    }
     if (UNPROJECT)
         hipLaunchKernelGGL((wht_unproject_reg_kernel<LP, MH, MW, BF16>), dim3(blocks), dim3(256), 0,
                            stream, (const float *)in, (uint32_t *)out, items, Cd, g, sel, r, sl.count,
                            sl.stride);
-    else
-        hipLaunchKernelGGL((wht_project_reg_kernel<LP, MH, MW, BF16>), dim3(blocks), dim3(256), 0,
-                           stream, (const uint32_t *)in, (uint32_t *)out, items, Cd, g, sel, r);
 }
 
 template <bool UNPROJECT, int LP, int MH, bool BF16>
 void launch_reg_mw(int mw, const void *in, void *out, long items, int Cd, const GridGeom &g,
-                   const PooledSel &sel, int r, Slices sl, hipStream_t s)
+                   const PooledSel &sel, int r, Slices sl, Second sec, hipStream_t s)
 {
     switch (mw) {
-        case 0: launch_reg_one<UNPROJECT, LP, MH, 0, BF16>(in, out, items, Cd, g, sel, r, sl, s); break;
-        case 1: launch_reg_one<UNPROJECT, LP, MH, (LP >= 1 ? 1 : 0), BF16>(in, out, items, Cd, g, sel, r, sl, s); break;
-        case 2: launch_reg_one<UNPROJECT, LP, MH, (LP >= 2 ? 2 : 0), BF16>(in, out, items, Cd, g, sel, r, sl, s); break;
-        default: launch_reg_one<UNPROJECT, LP, MH, (LP >= 3 ? 3 : 0), BF16>(in, out, items, Cd, g, sel, r, sl, s); break;
+        case 0: launch_reg_one<UNPROJECT, LP, MH, 0, BF16>(in, out, items, Cd, g, sel, r, sl, sec, s); break;
+        case 1: launch_reg_one<UNPROJECT, LP, MH, (LP >= 1 ? 1 : 0), BF16>(in, out, items, Cd, g, sel, r, sl, sec, s); break;
+        case 2: launch_reg_one<UNPROJECT, LP, MH, (LP >= 2 ? 2 : 0), BF16>(in, out, items, Cd, g, sel, r, sl, sec, s); break;
+        default: launch_reg_one<UNPROJECT, LP, MH, (LP >= 3 ? 3 : 0), BF16>(in, out, items, Cd, g, sel, r, sl, sec, s); break;
     }
 }
 
 template <bool UNPROJECT, int LP, bool BF16>
 void launch_reg_mh(int mh, int mw, const void *in, void *out, long items, int Cd, const GridGeom &g,
-                   const PooledSel &sel, int r, Slices sl, hipStream_t s)
+                   const PooledSel &sel, int r, Slices sl, Second sec, hipStream_t s)
 {
     switch (mh) {
-        case 0: launch_reg_mw<UNPROJECT, LP, 0, BF16>(mw, in, out, items, Cd, g, sel, r, sl, s); break;
-        case 1: launch_reg_mw<UNPROJECT, LP, (LP >= 1 ? 1 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, sl, s); break;
-        case 2: launch_reg_mw<UNPROJECT, LP, (LP >= 2 ? 2 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, sl, s); break;
-        default: launch_reg_mw<UNPROJECT, LP, (LP >= 3 ? 3 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, sl, s); break;
+        case 0: launch_reg_mw<UNPROJECT, LP, 0, BF16>(mw, in, out, items, Cd, g, sel, r, sl, sec, s); break;
+        case 1: launch_reg_mw<UNPROJECT, LP, (LP >= 1 ? 1 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, sl, sec, s); break;
+        case 2: launch_reg_mw<UNPROJECT, LP, (LP >= 2 ? 2 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, sl, sec, s); break;
+        default: launch_reg_mw<UNPROJECT, LP, (LP >= 3 ? 3 : 0), BF16>(mw, in, out, items, Cd, g, sel, r, sl, sec, s); break;
     }
 }
 
+// in2/out2/C2: optional second tensor on the same token grid (projection only).
 template <bool UNPROJECT>
 hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int dtype,
-                      const BasisPlan &plan, Slices sl, hipStream_t s)
+                      const BasisPlan &plan, Slices sl, hipStream_t s, const void *in2 = nullptr,
+                      void *out2 = nullptr, int C2 = 0)
 {
     const bool bf16 = dtype == LBP_BF16;
     const int Cd = bf16 ? C / 2 : C;
     const long Q = (long)N * (H / plan.patch) * (W / plan.patch);
     const long items = Q * Cd;
+    Second sec;
+    if (in2) {
+        sec.in = in2;
+        sec.out = out2;
+        sec.Cd = bf16 ? C2 / 2 : C2;
+        sec.items = Q * sec.Cd;
+    }
     GridGeom g = make_geom(H, W, plan.patch);
     PooledSel sel;
     sel.mask = plan.pooled_mask;
@@ -343,16 +376,16 @@ hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int
     const int mh = plan.mh, mw = plan.mw, r = plan.r;
     switch (plan.log2p) {
         case 1:
-            if (bf16) launch_reg_mh<UNPROJECT, 1, true>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
-            else launch_reg_mh<UNPROJECT, 1, false>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
+            if (bf16) launch_reg_mh<UNPROJECT, 1, true>(mh, mw, in, out, items, Cd, g, sel, r, sl, sec, s);
+            else launch_reg_mh<UNPROJECT, 1, false>(mh, mw, in, out, items, Cd, g, sel, r, sl, sec, s);
             break;
         case 2:
-            if (bf16) launch_reg_mh<UNPROJECT, 2, true>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
-            else launch_reg_mh<UNPROJECT, 2, false>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
+            if (bf16) launch_reg_mh<UNPROJECT, 2, true>(mh, mw, in, out, items, Cd, g, sel, r, sl, sec, s);
+            else launch_reg_mh<UNPROJECT, 2, false>(mh, mw, in, out, items, Cd, g, sel, r, sl, sec, s);
             break;
         case 3:
-            if (bf16) launch_reg_mh<UNPROJECT, 3, true>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
-            else launch_reg_mh<UNPROJECT, 3, false>(mh, mw, in, out, items, Cd, g, sel, r, sl, s);
+            if (bf16) launch_reg_mh<UNPROJECT, 3, true>(mh, mw, in, out, items, Cd, g, sel, r, sl, sec, s);
+            else launch_reg_mh<UNPROJECT, 3, false>(mh, mw, in, out, items, Cd, g, sel, r, sl, sec, s);
             break;
         default: return hipErrorInvalidValue;
     }
@@ -403,6 +436,18 @@ hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C,
     if (use_register_path(plan, path))
         return launch_reg<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
     return launch_generic<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
+}
+
+hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
+                               int N, int H, int W, int dtype, const BasisPlan &plan, WhtPath path,
+                               hipStream_t stream)
+{
+    if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
+    if (use_register_path(plan, path))
+        return launch_reg<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream, in1, out1, C1);
+    hipError_t e = launch_generic<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream);
+    if (e != hipSuccess) return e;
+    return launch_generic<false>(in1, out1, N, H, W, C1, dtype, plan, Slices{}, stream);
 }
 
 hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H, int W, int C,
