@@ -2,7 +2,7 @@
 // shape by the gemm_mfma_*.hip files.
 //
 // One workgroup owns a BM x BN tile of the output and walks the reduction in steps of BK = 64.
-//   * Global -> registers (16-byte loads, issued one step ahead) -> LDS (two stages, one barrier
+//   * Global -> registers (16-byte loads, issued PF steps ahead) -> LDS (two stages, one barrier
 //     per step).  Loads are never predicated in the steady state: rows and columns past the edge
 //     of a matrix are clamped to the last valid ones (they only feed outputs that are never
 //     stored); only a final partial step of the reduction zero-fills.
@@ -90,7 +90,7 @@ __device__ __forceinline__ void unproject_tile(const float *ct, int cts, const P
 #pragma unroll
             for (int w = 0; w < P; ++w) {
                 int j = (h >> MH) * PWd + (w >> MW);
-                dst[((size_t)h * p.geom.Wt + w) * Cd] = pack_bf16x2(c0[j] * scale, c1[j] * scale);
+                __builtin_nontemporal_store(pack_bf16x2(c0[j] * scale, c1[j] * scale), dst + ((size_t)h * p.geom.Wt + w) * Cd);
             }
         }
     }

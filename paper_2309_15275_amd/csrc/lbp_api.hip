@@ -92,11 +92,14 @@ lbp::GemmPath gemm_path_from_env()
     return lbp::GemmPath::kAuto;
 }
 
-// LBP_FUSE_UNPROJECT=0 keeps the reverse projection a kernel of its own (for testing).
-bool fuse_unproject_from_env()
+// LBP_FUSE_UNPROJECT: "0" keeps the reverse projection a kernel of its own, "1" fuses it into the
+// input-gradient product whenever the kernel supports the selection, unset lets the planner choose
+// (for testing and measurement).  Returns -1 when unset.
+int fuse_unproject_from_env()
 {
     const char *s = std::getenv("LBP_FUSE_UNPROJECT");
-    return !(s && !std::strcmp(s, "0"));
+    if (!s || !*s) return -1;
+    return std::strcmp(s, "0") ? 1 : 0;
 }
 
 // gW = scale * A^T-style product with split-K: direct store when one slice suffices and the
@@ -201,7 +204,7 @@ size_t lbp_wht_workspace_bytes(const lbp_shape_t *shape, int patch, int r)
     else
         (void)hipGetLastError();
     lbp::WorkspacePlan ws;
-    if (lbp::plan_workspace(shape, patch, r, cus, false, &ws) != LBP_OK) return 0;
+    if (lbp::plan_workspace(shape, patch, r, cus, false, false, &ws) != LBP_OK) return 0;
     size_t total = ws.total;
     if (patch == 0 && shape->dtype == LBP_BF16)   // staging of gx for the plain cross-check kernels
         total += ((size_t)shape->N * shape->H * shape->W * shape->Cin * 4 + 255) / 256 * 256;
@@ -314,9 +317,10 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     rc = current_device(&dev, &st);
     if (rc) return rc;
     const lbp::GemmPath gpath = gemm_path_from_env();
-    const bool can_fuse = fuse_unproject_from_env() && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
+    const int fuse_env = fuse_unproject_from_env();
+    const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
     lbp::WorkspacePlan ws;
-    rc = lbp::plan_workspace(shape, patch, r, st->num_cus, can_fuse, &ws);
+    rc = lbp::plan_workspace(shape, patch, r, st->num_cus, can_fuse, fuse_env == 1, &ws);
     if (rc) return rc;
     char *base = nullptr;
     rc = get_workspace(st, ws.total, &base);
@@ -423,7 +427,7 @@ int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_sha
     const int Cin = shape->Cin, Cout = shape->Cout, dt = shape->dtype;
     const long M = (long)shape->N * shape->H * shape->W;
     lbp::WorkspacePlan ws;
-    rc = lbp::plan_workspace(shape, 0, 0, st->num_cus, false, &ws);
+    rc = lbp::plan_workspace(shape, 0, 0, st->num_cus, false, false, &ws);
     if (rc) return rc;
     // the plain bf16 kernel needs an fp32 staging buffer of M x Cin for gx
     size_t gx_stage = gx && dt == LBP_BF16 && gemm_path_from_env() == lbp::GemmPath::kSimple

@@ -179,8 +179,8 @@ GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split,
             wg = wg * ti.slowdown + kWgFixed;
             const double rounds = (double)((tiles * sp + num_cus - 1) / num_cus);
             double clk = rounds * wg;
-            if (sp > 1)   // the reduction kernel: launch gap plus (sp reads + 1 write) of M*N
-                clk += 8000.0 + (double)(sp * 4 + out_elem_bytes) * M * N / (num_cus * kFill);
+            if (sp > 1)   // the reduction kernel: about 3 us of launch and ramp, then ~7 TB/s
+                clk += kClkPerUs * (3.0 + (double)(sp * 4 + out_elem_bytes) * M * N / 7.0e6);
             if (clk < best.est_us) best = GemmPlan{t, sp, clk};
         }
     }
@@ -191,7 +191,7 @@ GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split,
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
-                   WorkspacePlan *ws)
+                   bool force_fuse, WorkspacePlan *ws)
 {
     if (!s || !ws) return LBP_ERR_NULL;
     std::memset(ws, 0, sizeof *ws);
@@ -213,13 +213,24 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
     ws->gw = plan_gemm(s->Cout, s->Cin, Mr, gw_bytes, true, 0, 0, num_cus);
     // gx: fused epilogue (no split, few workgroups when Mr is small) against split-K partial sums
     // that the reverse-projection kernel adds up while it reads them
-    GemmPlan unfused = plan_gemm(Mr, s->Cin, s->Cout, 4, true, 0, 0, num_cus);
-    unfused.est_us += 3.0 + (double)M * s->Cin * esz / (num_cus * 20.0 * 2400.0);
+    GemmPlan unfused = plan_gemm(Mr, s->Cin, s->Cout, 4, false, 0, 0, num_cus);
+    for (int sp = 2; sp <= 16; ++sp) {      // slices are summed by the reverse-projection kernel
+        if (s->Cout / sp < 256) break;
+        GemmPlan g = plan_gemm(Mr, s->Cin, (s->Cout + sp - 1) / sp, 4, false, 0, 0, num_cus);
+        // the planner sees one slice: scale its rounds to sp times the workgroups
+        GemmPlan whole = plan_gemm(Mr * sp, s->Cin, (s->Cout + sp - 1) / sp, 4, false, 0, 0, num_cus);
+        g.est_us = whole.est_us;
+        g.splits = sp;
+        if (g.est_us + 1.0 * sp < unfused.est_us) unfused = g;
+    }
+    // the reverse-projection kernel: about 8 us of launch, ramp and tail at these sizes, then
+    // (slices read + tokens written) at ~4 TB/s
+    unfused.est_us += 8.0 + ((double)unfused.splits * Mr * s->Cin * 4 + (double)M * s->Cin * esz) / 4.0e6;
     ws->gx = unfused;
     ws->gx_fused = false;
     if (can_fuse && s->dtype == LBP_BF16) {
         GemmPlan fused = plan_gemm(Mr, s->Cin, s->Cout, 2, false, r, patch, num_cus);
-        if (fused.est_us <= unfused.est_us) {
+        if (force_fuse || fused.est_us <= unfused.est_us) {
             ws->gx = fused;
             ws->gx_fused = true;
         }

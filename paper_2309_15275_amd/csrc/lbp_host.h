@@ -96,9 +96,10 @@ struct WorkspacePlan {
 };
 
 // num_cus: compute units of the device (the GEMM plans depend on it); pass 256 when unknown.
-// can_fuse: the selection allows the fused reverse projection (false gives the larger workspace).
+// can_fuse: the selection allows the fused reverse projection (false gives the larger workspace);
+// force_fuse: take it whenever allowed instead of comparing estimates.
 int plan_workspace(const lbp_shape_t *shape, int patch, int r, int num_cus, bool can_fuse,
-                   WorkspacePlan *ws);
+                   bool force_fuse, WorkspacePlan *ws);
 
 const char *status_string(int code);
 

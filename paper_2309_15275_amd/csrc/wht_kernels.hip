@@ -54,7 +54,8 @@ __global__ __launch_bounds__(256) void wht_project_reg_kernel(ProjTensor t0, Pro
 #pragma unroll
     for (int h = 0; h < P; ++h) {
 #pragma unroll
-        for (int w = 0; w < P; ++w) raw[h * P + w] = src[((size_t)h * g.Wt + w) * Cd];
+        for (int w = 0; w < P; ++w)
+            raw[h * P + w] = __builtin_nontemporal_load(src + ((size_t)h * g.Wt + w) * Cd);   // read once
     }
 
     float v[P * P];
@@ -103,19 +104,19 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
         const float2 *src = reinterpret_cast<const float2 *>(in + (size_t)q * r * C) + cd;
         float c0[NC], c1[NC];
 #pragma unroll
-        for (int j = 0; j < NC; ++j) {
-            float2 t = make_float2(0.f, 0.f);
-            if ((sel.mask >> j) & 1ull) {
-                const float2 *sp = src + (size_t)sel.pos[j] * Cd;
-                t = *sp;
-                for (int z = 1; z < slices; ++z) {      // fixed order: deterministic sums
-                    float2 u = *reinterpret_cast<const float2 *>(reinterpret_cast<const float *>(sp) + z * slice_stride);
-                    t.x += u.x;
-                    t.y += u.y;
+        for (int j = 0; j < NC; ++j) c0[j] = c1[j] = 0.f;
+        // slice by slice (fixed order: deterministic sums), all coefficients of a slice in flight
+        // together
+        for (int z = 0; z < slices; ++z) {
+            const float2 *sz = reinterpret_cast<const float2 *>(reinterpret_cast<const float *>(src) + z * slice_stride);
+#pragma unroll
+            for (int j = 0; j < NC; ++j) {
+                if ((sel.mask >> j) & 1ull) {
+                    float2 t = sz[(size_t)sel.pos[j] * Cd];
+                    c0[j] += t.x;
+                    c1[j] += t.y;
                 }
             }
-            c0[j] = t.x;
-            c1[j] = t.y;
         }
         fwht_inplace<NC>(c0);
         fwht_inplace<NC>(c1);
@@ -124,21 +125,19 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
 #pragma unroll
             for (int w = 0; w < P; ++w) {
                 int j = (h >> MH) * PWd + (w >> MW);
-                dst[((size_t)h * g.Wt + w) * Cd] = pack_bf16x2(c0[j] * scale, c1[j] * scale);
+                __builtin_nontemporal_store(pack_bf16x2(c0[j] * scale, c1[j] * scale), dst + ((size_t)h * g.Wt + w) * Cd);
             }
         }
     } else {
         const float *src = in + (size_t)q * r * Cd + cd;
         float c0[NC];
 #pragma unroll
-        for (int j = 0; j < NC; ++j) {
-            float t = 0.f;
-            if ((sel.mask >> j) & 1ull) {
-                const float *sp = src + (size_t)sel.pos[j] * Cd;
-                t = *sp;
-                for (int z = 1; z < slices; ++z) t += sp[z * slice_stride];
-            }
-            c0[j] = t;
+        for (int j = 0; j < NC; ++j) c0[j] = 0.f;
+        for (int z = 0; z < slices; ++z) {
+            const float *sz = src + z * slice_stride;
+#pragma unroll
+            for (int j = 0; j < NC; ++j)
+                if ((sel.mask >> j) & 1ull) c0[j] += sz[(size_t)sel.pos[j] * Cd];
         }
         fwht_inplace<NC>(c0);
 #pragma unroll
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
 #pragma unroll
             for (int w = 0; w < P; ++w) {
                 int j = (h >> MH) * PWd + (w >> MW);
-                dst[((size_t)h * g.Wt + w) * Cd] = __float_as_uint(c0[j] * scale);
+                __builtin_nontemporal_store(__float_as_uint(c0[j] * scale), dst + ((size_t)h * g.Wt + w) * Cd);
             }
         }
     }
