@@ -23,7 +23,7 @@
  *            aligned; `shape` and `basis_idx` are HOST pointers read only during the call.
  *            Outputs are overwritten (never accumulated into) and must not overlap any input.
  *   Stream   `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
- *            enqueued on it; no entry point synchronises the device.
+ *            enqueued on it; no entry point synchronises the device unless it says so.
  *   Errors   every function returning int gives LBP_OK (0) or a negative lbp_status_t.  Argument
  *            errors are detected on the host before any HIP call is made, so they can be provoked
  *            and tested on a machine without a GPU.  There is no CPU fallback: without a usable
@@ -126,6 +126,16 @@ int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_sha
  */
 int lbp_wht_project(const void *in, int N, int H, int W, int C, int dtype, int patch,
                     const int32_t *basis_idx, int r, void *out, void *stream);
+
+/*
+ * The first two statements of Algorithm 1 exactly as lbp_wht_backward runs them: x^ = WHT(x; I) and
+ * g^y = WHT(gy; I) in ONE kernel launch (gy's workgroups first, x's filling the tail).
+ *   x [N][H][W][Cin], gy [N][H][W][Cout]  ->  x_r [P*r][Cin], gy_r [P*r][Cout], all of shape->dtype
+ * (shape->gw_dtype is ignored).  Exported so that the dominant kernel of the backward can be timed
+ * by itself, and for callers that keep x^ from the forward pass.
+ */
+int lbp_wht_project_pair(const void *x, const void *gy, const lbp_shape_t *shape, int patch,
+                         const int32_t *basis_idx, int r, void *x_r, void *gy_r, void *stream);
 
 /*
  * The reverse projection p^-1(.) of Eq. 7 alone, with the 1/patch^2 factor:

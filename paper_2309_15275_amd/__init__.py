@@ -6,5 +6,6 @@ from .binding import (  # noqa: F401
     lbp_wht_backward,
     select_bases,
     wht_project,
+    wht_project_pair,
     wht_unproject,
 )

@@ -18,7 +18,7 @@ _DTYPES = {torch.float32: LBP_F32, torch.bfloat16: LBP_BF16}
 
 # every symbol include/lbp_wht.h declares
 EXPORTS = ("lbp_wht_select_bases", "lbp_wht_backward", "lbp_wht_backward_profile", "full_bp_backward", "lbp_wht_project",
-           "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
+           "lbp_wht_project_pair", "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
            "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version")
 
 
@@ -56,6 +56,7 @@ def load():
     lib.full_bp_backward.argtypes = [vp, vp, vp, shp, vp, vp, vp]
     lib.lbp_wht_project.argtypes = [vp] + [ctypes.c_int] * 6 + [i32p, ctypes.c_int, vp, vp]
     lib.lbp_wht_unproject.argtypes = [vp] + [ctypes.c_int] * 6 + [i32p, ctypes.c_int, vp, vp]
+    lib.lbp_wht_project_pair.argtypes = [vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
     lib.lbp_wht_workspace_bytes.argtypes = [shp, ctypes.c_int, ctypes.c_int]
     lib.lbp_wht_workspace_bytes.restype = ctypes.c_size_t
     lib.lbp_set_workspace.argtypes = [vp, ctypes.c_size_t]
@@ -182,6 +183,25 @@ def wht_project(t, patch, basis_idx, out=None, stream=None):
         _check(load().lbp_wht_project(_dev_tensor(t, "t"), N, H, W, C, _DTYPES[t.dtype], int(patch),
                                       idx, r, _dev_tensor(out, "out", t.dtype), _stream_ptr(stream)))
     return out
+
+
+def wht_project_pair(x, gy, patch, basis_idx, x_r=None, gy_r=None, stream=None):
+    """x^ = WHT(x; I) and g^y = WHT(gy; I) in one launch; returns (x_r, gy_r)."""
+    N, H, W, Cin = x.shape
+    Cout = gy.shape[-1]
+    idx, r = _idx_array(basis_idx)
+    rows = N * H * W // (patch * patch) * r
+    if x_r is None:
+        x_r = torch.empty((rows, Cin), dtype=x.dtype, device=x.device)
+    if gy_r is None:
+        gy_r = torch.empty((rows, Cout), dtype=x.dtype, device=x.device)
+    shape = LbpShape(N, H, W, Cin, Cout, _DTYPES[x.dtype], LBP_F32)
+    with torch.cuda.device(x.device):
+        _check(load().lbp_wht_project_pair(_dev_tensor(x, "x"), _dev_tensor(gy, "gy", x.dtype),
+                                           ctypes.byref(shape), int(patch), idx, r,
+                                           _dev_tensor(x_r, "x_r", x.dtype), _dev_tensor(gy_r, "gy_r", x.dtype),
+                                           _stream_ptr(stream)))
+    return x_r, gy_r
 
 
 def wht_unproject(coef, shape, dtype, patch, basis_idx, out=None, stream=None):

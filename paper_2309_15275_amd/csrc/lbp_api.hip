@@ -269,6 +269,36 @@ int lbp_wht_project(const void *in, int N, int H, int W, int C, int dtype, int p
     return LBP_OK;
 }
 
+int lbp_wht_project_pair(const void *x, const void *gy, const lbp_shape_t *shape, int patch,
+                         const int32_t *basis_idx, int r, void *x_r, void *gy_r, void *stream)
+{
+    if (!x || !gy || !x_r || !gy_r || !basis_idx || !shape) return LBP_ERR_NULL;
+    int rc = lbp::validate_shape(shape, patch);
+    if (rc) return rc;
+    if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
+    lbp::BasisPlan plan;
+    rc = lbp::make_basis_plan(patch, basis_idx, r, &plan);
+    if (rc) return rc;
+    const void *ptrs[4] = {x, gy, x_r, gy_r};
+    rc = lbp::validate_alignment(ptrs, 4);
+    if (rc) return rc;
+    const size_t esz = lbp::dtype_size(shape->dtype);
+    const size_t M = (size_t)shape->N * shape->H * shape->W, Mr = M / (patch * patch) * r;
+    const void *bufs[4] = {x, gy, x_r, gy_r};
+    const size_t bytes[4] = {M * shape->Cin * esz, M * shape->Cout * esz, Mr * shape->Cin * esz,
+                             Mr * shape->Cout * esz};
+    for (int i = 2; i < 4; ++i)
+        for (int j = 0; j < i; ++j)
+            if (lbp::ranges_overlap(bufs[i], bytes[i], bufs[j], bytes[j])) return LBP_ERR_ALIAS;
+    int dev;
+    DeviceState *st;
+    rc = current_device(&dev, &st);
+    if (rc) return rc;
+    LBP_HIP(lbp::launch_project_pair(gy, gy_r, shape->Cout, x, x_r, shape->Cin, shape->N, shape->H, shape->W,
+                                     shape->dtype, plan, wht_path_from_env(), (hipStream_t)stream));
+    return LBP_OK;
+}
+
 int lbp_wht_unproject(const void *in, int N, int H, int W, int C, int dtype, int patch,
                       const int32_t *basis_idx, int r, void *out, void *stream)
 {

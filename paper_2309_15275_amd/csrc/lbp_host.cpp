@@ -146,6 +146,8 @@ const GemmTileInfo kGemmTiles[kNumGemmTiles] = {
     {64, 128, true, 1.0},
     {256, 128, false, 1.15},
     {256, 256, false, 1.4},
+    {128, 128, true, 0.92},    // 8 wavefronts: hides more of the LDS -> matrix-core latency
+    {64, 128, true, 0.88},     // 8 wavefronts
 };
 
 GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split, int fused_r,

@@ -58,13 +58,14 @@ int validate_alignment(const void *const *ptrs, int n);
 // [a, a+na) and [b, b+nb) overlap?
 bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb);
 
-// Tile shapes of the bf16 matrix-core GEMM (gemm_mfma_*.hip instantiates them in this order).
+// Tile shapes of the bf16 matrix-core GEMM (gemm_mfma_*.hip instantiates them in this order):
+// 128x128, 64x128, 256x128, 256x256, then 128x128 and 64x128 with 8 instead of 4 wavefronts.
 struct GemmTileInfo {
     int bm, bn;        // output tile of one workgroup
     bool fused;        // has the fused reverse-projection epilogue
     double slowdown;   // measured factor over the simple cost model below
 };
-constexpr int kNumGemmTiles = 4;
+constexpr int kNumGemmTiles = 6;
 extern const GemmTileInfo kGemmTiles[kNumGemmTiles];
 
 // How one matrix product is run.

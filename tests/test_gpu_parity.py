@@ -146,7 +146,7 @@ def test_backward_matches_oracle_on_ragged_shapes(dtype, case, variant):
     assert egx <= TOL[dtype] and egw <= TOL[dtype], (egx, egw)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5])
 @pytest.mark.parametrize("case", [0, 3, 10, 13])
 def test_every_gemm_tile_shape_matches_oracle(case, tile):
     # LBP_GEMM_TILE forces one tile shape of the matrix-core kernel for every product of the call
