@@ -42,8 +42,7 @@ bool gemm_can_fuse_unproject(const BasisPlan &plan, int dtype, GemmPath path)
 {
     if (path == GemmPath::kSimple || dtype != LBP_BF16) return false;
     if (plan.patch != 4 && plan.patch != 8) return false;
-    int nc = (plan.patch >> plan.mh) * (plan.patch >> plan.mw);
-    return nc <= 16;     // r <= patch^2 <= 64 always fits the smallest tile
+    return true;     // r <= patch^2 <= 64 always fits the smallest tile
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)

@@ -54,4 +54,31 @@ __device__ __forceinline__ void pooled_transform(const float (&v)[P * P],
     fwht_inplace<PH * PWd>(c);
 }
 
+// The same from raw 32-bit words, converting on the fly: HALF 0 = low bf16 of each word, 1 = high
+// bf16, 2 = the word is an fp32 value.  No array of converted tokens is kept.
+template <int P, int MH, int MW, int HALF>
+__device__ __forceinline__ void pooled_transform_raw(const uint32_t (&raw)[P * P],
+                                                     float (&c)[(P >> MH) * (P >> MW)])
+{
+    constexpr int PH = P >> MH, PWd = P >> MW;
+#pragma unroll
+    for (int hh = 0; hh < PH; ++hh) {
+#pragma unroll
+        for (int ww = 0; ww < PWd; ++ww) {
+            float s = 0.f;
+#pragma unroll
+            for (int dh = 0; dh < (1 << MH); ++dh) {
+#pragma unroll
+                for (int dw = 0; dw < (1 << MW); ++dw) {
+                    uint32_t u = raw[((hh << MH) + dh) * P + (ww << MW) + dw];
+                    float f = HALF == 0 ? bf16_lo_to_f32(u) : HALF == 1 ? bf16_hi_to_f32(u) : __uint_as_float(u);
+                    s = (dh == 0 && dw == 0) ? f : s + f;
+                }
+            }
+            c[hh * PWd + ww] = s;
+        }
+    }
+    fwht_inplace<PH * PWd>(c);
+}
+
 }  // namespace lbp

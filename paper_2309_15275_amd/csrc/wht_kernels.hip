@@ -58,25 +58,28 @@ __global__ __launch_bounds__(256) void wht_project_reg_kernel(ProjTensor t0, Pro
             raw[h * P + w] = __builtin_nontemporal_load(src + ((size_t)h * g.Wt + w) * Cd);   // read once
     }
 
-    float v[P * P];
-    float c0[NC];
-#pragma unroll
-    for (int i = 0; i < P * P; ++i) v[i] = BF16 ? bf16_lo_to_f32(raw[i]) : __uint_as_float(raw[i]);
-    pooled_transform<P, MH, MW>(v, c0);
-
     uint32_t *dst = t.out + (size_t)q * r * Cd + cd;
     if (BF16) {
-        float c1[NC];
+        // low halves first; their coefficients wait as rounded bf16 pairs (half the registers)
+        // while the high halves go through the same transform
+        float c[NC];
+        pooled_transform_raw<P, MH, MW, 0>(raw, c);
+        uint32_t lo[(NC + 1) / 2];
 #pragma unroll
-        for (int i = 0; i < P * P; ++i) v[i] = bf16_hi_to_f32(raw[i]);
-        pooled_transform<P, MH, MW>(v, c1);
+        for (int j = 0; j < NC; j += 2) lo[j / 2] = f32_to_bf16_bits(c[j]) | (f32_to_bf16_bits(c[j + 1 < NC ? j + 1 : j]) << 16);
+        pooled_transform_raw<P, MH, MW, 1>(raw, c);
 #pragma unroll
         for (int j = 0; j < NC; ++j)
-            if ((sel.mask >> j) & 1ull) dst[(size_t)sel.pos[j] * Cd] = pack_bf16x2(c0[j], c1[j]);
+            if ((sel.mask >> j) & 1ull) {
+                uint32_t l = (j & 1) ? (lo[j / 2] >> 16) : (lo[j / 2] & 0xffffu);
+                dst[(size_t)sel.pos[j] * Cd] = l | (f32_to_bf16_bits(c[j]) << 16);
+            }
     } else {
+        float c[NC];
+        pooled_transform_raw<P, MH, MW, 2>(raw, c);
 #pragma unroll
         for (int j = 0; j < NC; ++j)
-            if ((sel.mask >> j) & 1ull) dst[(size_t)sel.pos[j] * Cd] = __float_as_uint(c0[j]);
+            if ((sel.mask >> j) & 1ull) dst[(size_t)sel.pos[j] * Cd] = __float_as_uint(c[j]);
     }
 }
 
