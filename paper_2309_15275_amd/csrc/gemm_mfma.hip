@@ -42,7 +42,10 @@ bool gemm_can_fuse_unproject(const BasisPlan &plan, int dtype, GemmPath path)
 {
     if (path == GemmPath::kSimple || dtype != LBP_BF16) return false;
     if (plan.patch != 4 && plan.patch != 8) return false;
-    return true;     // r <= patch^2 <= 64 always fits the smallest tile
+    // The fused epilogue expands coefficients with the pooled register butterfly; beyond 16 pooled
+    // coefficients per channel that is register bound and the stand-alone matrix-core kernel wins.
+    int nc = (plan.patch >> plan.mh) * (plan.patch >> plan.mw);
+    return nc <= 16;     // r <= patch^2 <= 64 always fits the smallest tile
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)

@@ -309,7 +309,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
         switch (p.mh * 4 + p.mw) {
 #define LBP_CASE(MH, MW)                                                                         \
     case MH * 4 + MW:                                                                            \
-        if constexpr (MH <= LP && MW <= LP)                                                      \
+        if constexpr (MH <= LP && MW <= LP && ((1 << LP) >> MH) * ((1 << LP) >> MW) <= 16)      \
             unproject_tile<LP, MH, MW, BN, NT>(ct, CTS, p, m0, n0, tid);                         \
         break;
             LBP_CASE(0, 0) LBP_CASE(0, 1) LBP_CASE(0, 2) LBP_CASE(0, 3)

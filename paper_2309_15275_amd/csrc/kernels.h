@@ -8,7 +8,7 @@ namespace lbp {
 
 // Which implementation of a step to use.  kAuto picks the fastest one that supports the shape;
 // the others exist so that tests can run every kernel on every shape it supports.
-enum class WhtPath { kAuto = 0, kGeneric = 1, kRegister = 2 };
+enum class WhtPath { kAuto = 0, kGeneric = 1, kRegister = 2, kMfma = 3 };
 enum class GemmPath { kAuto = 0, kSimple = 1 };
 
 // p(.) of Eq. 6 per patch: in [N][H][W][C] -> out [P*r][C], both of `dtype`.
@@ -25,6 +25,13 @@ hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *
 // summed first: split-K partial results) -> out [N][H][W][C] of `dtype`.
 hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H, int W, int C,
                             int dtype, const BasisPlan &plan, WhtPath path, hipStream_t stream);
+
+// Matrix-core form of the two projections (bf16 tensors, any selection, any patch up to 16).
+bool wht_mfma_supported(const BasisPlan &plan, int dtype, int C);
+hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
+                               int N, int H, int W, const BasisPlan &plan, hipStream_t stream);
+hipError_t launch_unproject_mfma(const float *in, int slices, void *out, int N, int H, int W, int C,
+                                 const BasisPlan &plan, hipStream_t stream);
 
 // What a matrix product does with its accumulators.
 enum class GemmOut {

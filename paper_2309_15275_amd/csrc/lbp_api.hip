@@ -114,6 +114,7 @@ lbp::WhtPath wht_path_from_env()
     if (!s) return lbp::WhtPath::kAuto;
     if (!std::strcmp(s, "generic")) return lbp::WhtPath::kGeneric;
     if (!std::strcmp(s, "register")) return lbp::WhtPath::kRegister;
+    if (!std::strcmp(s, "mfma")) return lbp::WhtPath::kMfma;
     return lbp::WhtPath::kAuto;
 }
 

@@ -429,12 +429,25 @@ bool use_register_path(const BasisPlan &plan, WhtPath path)
     return path != WhtPath::kGeneric;
 }
 
+// The matrix-core form takes over where the pooled butterfly cannot prune (more than 16 pooled
+// coefficients per channel) and for patch 16.
+bool use_mfma_path(const BasisPlan &plan, WhtPath path, int dtype, int C)
+{
+    if (!wht_mfma_supported(plan, dtype, C)) return false;
+    if (path == WhtPath::kMfma) return true;
+    if (path != WhtPath::kAuto) return false;
+    if (plan.patch > 8) return true;
+    return (plan.patch >> plan.mh) * (plan.patch >> plan.mw) > 16;
+}
+
 }  // namespace
 
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
                           const BasisPlan &plan, WhtPath path, hipStream_t stream)
 {
     if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
+    if (use_mfma_path(plan, path, dtype, C))
+        return launch_project_mfma(in, out, C, nullptr, nullptr, 0, N, H, W, plan, stream);
     if (use_register_path(plan, path))
         return launch_reg<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
     return launch_generic<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
@@ -445,6 +458,8 @@ hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *
                                hipStream_t stream)
 {
     if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
+    if (use_mfma_path(plan, path, dtype, C0) && use_mfma_path(plan, path, dtype, C1))
+        return launch_project_mfma(in0, out0, C0, in1, out1, C1, N, H, W, plan, stream);
     if (use_register_path(plan, path))
         return launch_reg<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream, in1, out1, C1);
     hipError_t e = launch_generic<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream);
@@ -457,6 +472,8 @@ hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H
 {
     if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
     if (slices < 1) return hipErrorInvalidValue;
+    if (use_mfma_path(plan, path, dtype, C))
+        return launch_unproject_mfma(in, slices, out, N, H, W, C, plan, stream);
     Slices sl;
     sl.count = slices;
     sl.stride = (size_t)N * (H / plan.patch) * (W / plan.patch) * plan.r * C;
