@@ -14,6 +14,7 @@ reverse projection, per patch, summed over the batch) per second.  The line also
   full_bp_ms / speedup_vs_full_bp   the same-style exact backward (Eq. 2) from this library,
   library_gemm_full_bp_ms           the two products through torch.matmul (the vendor GEMM library)
                                     as a second opinion on the comparison point,
+  preprojected_x_ms_per_step        lbp_wht_backward_preprojected: x^ kept from the forward pass,
   stages                            HIP-event time of each stage inside the call,
   roofline                          the dominant kernel (projection of gy and x, one launch, HBM
                                     bound): algorithmic bytes / its average duration,
@@ -136,7 +137,13 @@ def main():
         s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
         binding.wht_project_pair(s["x"], s["gy"], wl.patch, idx, x_r=xr, gy_r=gyr)
 
+    def pre_step(i):
+        s, (xr, _) = sets[i % n_sets], proj_bufs[i % n_sets]
+        binding.lbp_wht_backward_preprojected(xr, s["gy"], s["w"], wl.patch, idx, gx=s["gx"], gW=s["gW"])
+
     ms_lbp, wall_lbp = timed(lbp_step, args.steps, args.warmup)
+    # the variant that keeps x^ from the forward pass (never reads x)
+    ms_pre, _ = timed(pre_step, args.steps, args.warmup)
     # the dominant kernel by itself, back to back on the launch stream (same rotation of buffers)
     ms_proj, _ = timed(proj_step, args.steps, args.warmup)
     ms_full, _ = timed(full_step, max(10, args.steps // 4), max(3, args.warmup // 4))
@@ -220,6 +227,7 @@ def main():
         "speedup_vs_full_bp": round(ms_full / ms_lbp, 3),
         "library_gemm_full_bp_ms": None if ms_lib is None else round(ms_lib, 5),
         "speedup_vs_library_gemm_full_bp": None if ms_lib is None else round(ms_lib / ms_lbp, 3),
+        "preprojected_x_ms_per_step": round(ms_pre, 5),
         "host_wall_ms_per_step": round(wall_lbp, 5),
         "stages": stages,
         "roofline": roofline,

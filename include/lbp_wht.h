@@ -100,6 +100,17 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
                      int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream);
 
 /*
+ * Algorithm 1 with its first statement hoisted out: x^ = WHT(x; I) depends only on the layer's input
+ * and the index set, so the forward pass can compute it once (lbp_wht_project on x) and keep it
+ * instead of x, which is patch^2/r times larger.  x_r is that tensor, [P*r][Cin] of shape->dtype,
+ * projected with the SAME basis_idx; everything else as lbp_wht_backward.  The backward then never
+ * reads x.  Results are bit-identical to lbp_wht_backward on the same x.
+ */
+int lbp_wht_backward_preprojected(const void *x_r, const void *gy, const void *W,
+                                  const lbp_shape_t *shape, int patch, const int32_t *basis_idx, int r,
+                                  void *gx, void *gW, void *stream);
+
+/*
  * For measurement, not part of the method: the same call as lbp_wht_backward, bracketed by HIP
  * events on `stream`.  It WAITS for the work to finish and returns the elapsed milliseconds of the
  * three stages in stage_ms (host, 3 floats): [0] projection of gy and x, [1] weight-gradient

@@ -4,6 +4,7 @@ from .binding import (  # noqa: F401
     LbpError,
     full_bp_backward,
     lbp_wht_backward,
+    lbp_wht_backward_preprojected,
     select_bases,
     wht_project,
     wht_project_pair,

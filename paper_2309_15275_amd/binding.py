@@ -17,7 +17,7 @@ _ORDERS = {"l1": ORDER_L1, "linf": ORDER_LINF, ORDER_L1: ORDER_L1, ORDER_LINF: O
 _DTYPES = {torch.float32: LBP_F32, torch.bfloat16: LBP_BF16}
 
 # every symbol include/lbp_wht.h declares
-EXPORTS = ("lbp_wht_select_bases", "lbp_wht_backward", "lbp_wht_backward_profile", "full_bp_backward", "lbp_wht_project",
+EXPORTS = ("lbp_wht_select_bases", "lbp_wht_backward", "lbp_wht_backward_preprojected", "lbp_wht_backward_profile", "full_bp_backward", "lbp_wht_project",
            "lbp_wht_project_pair", "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
            "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version")
 
@@ -51,6 +51,7 @@ def load():
     shp = ctypes.POINTER(LbpShape)
     lib.lbp_wht_select_bases.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p]
     lib.lbp_wht_backward.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.lbp_wht_backward_preprojected.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
     lib.lbp_wht_backward_profile.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp,
                                              ctypes.POINTER(ctypes.c_float)]
     lib.full_bp_backward.argtypes = [vp, vp, vp, shp, vp, vp, vp]
@@ -138,6 +139,29 @@ def lbp_wht_backward(x, gy, w, patch, basis_idx, gx=None, gW=None, want_gx=True,
             _dev_tensor(x, "x"), _dev_tensor(gy, "gy", x.dtype), _dev_tensor(w, "w", x.dtype),
             ctypes.byref(shape), int(patch), idx, r,
             _dev_tensor(gx, "gx", x.dtype) if gx is not None else None,
+            _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
+    return gx, gW
+
+
+def lbp_wht_backward_preprojected(x_r, gy, w, patch, basis_idx, gx=None, gW=None, want_gx=True,
+                                  want_gw=True, gw_dtype=torch.float32, stream=None):
+    """Algorithm 1 with x^ = WHT(x; I) kept from the forward pass: x_r is [P*r, Cin] (wht_project of
+    x with the same basis_idx); gy [N,H,W,Cout], w [Cout,Cin].  Returns (gx, gW)."""
+    N, H, W, Cout = gy.shape
+    Cin = w.shape[1]
+    idx, r = _idx_array(basis_idx)
+    if tuple(x_r.shape) != (N * H * W // (patch * patch) * r, Cin) or tuple(w.shape) != (Cout, Cin):
+        raise ValueError("shapes must be x_r[P*r,Cin], gy[N,H,W,Cout], w[Cout,Cin]")
+    shape = LbpShape(N, H, W, Cin, Cout, _DTYPES[gy.dtype], _DTYPES[gw_dtype])
+    if want_gx and gx is None:
+        gx = torch.empty((N, H, W, Cin), dtype=gy.dtype, device=gy.device)
+    if want_gw and gW is None:
+        gW = torch.empty(w.shape, dtype=gw_dtype, device=w.device)
+    with torch.cuda.device(gy.device):
+        _check(load().lbp_wht_backward_preprojected(
+            _dev_tensor(x_r, "x_r", gy.dtype), _dev_tensor(gy, "gy"), _dev_tensor(w, "w", gy.dtype),
+            ctypes.byref(shape), int(patch), idx, r,
+            _dev_tensor(gx, "gx", gy.dtype) if gx is not None else None,
             _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
     return gx, gW
 

@@ -120,7 +120,7 @@ lbp::WhtPath wht_path_from_env()
 
 // Pointer, alias and alignment rules common to both backward entry points.
 int validate_buffers(const void *x, const void *gy, const void *W, const lbp_shape_t *s, void *gx,
-                     void *gW)
+                     void *gW, size_t x_rows = 0)
 {
     if (!x || !gy || !W) return LBP_ERR_NULL;
     if (!gx && !gW) return LBP_ERR_NULL;
@@ -129,8 +129,8 @@ int validate_buffers(const void *x, const void *gy, const void *W, const lbp_sha
     if (rc) return rc;
     size_t esz = lbp::dtype_size(s->dtype);
     size_t M = (size_t)s->N * s->H * s->W;
-    size_t nx = M * s->Cin * esz, ngy = M * s->Cout * esz, nw = (size_t)s->Cout * s->Cin * esz;
-    size_t ngx = nx, ngw = (size_t)s->Cout * s->Cin * lbp::dtype_size(s->gw_dtype);
+    size_t nx = (x_rows ? x_rows : M) * s->Cin * esz, ngy = M * s->Cout * esz, nw = (size_t)s->Cout * s->Cin * esz;
+    size_t ngx = M * s->Cin * esz, ngw = (size_t)s->Cout * s->Cin * lbp::dtype_size(s->gw_dtype);
     const void *ins[3] = {x, gy, W};
     size_t in_bytes[3] = {nx, ngy, nw};
     for (int i = 0; i < 3; ++i) {
@@ -330,8 +330,10 @@ namespace {
 
 // Algorithm 1.  `ev`, when not NULL, holds 4 events recorded on the stream before the projection,
 // after it, after the weight-gradient product and after the input-gradient product.
+// x_projected: `x` already is x^ = WHT(x; I), [P*r][Cin], kept from the forward pass.
 int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_t *shape, int patch,
-                  const int32_t *basis_idx, int r, void *gx, void *gW, void *stream, hipEvent_t *ev)
+                  const int32_t *basis_idx, int r, void *gx, void *gW, void *stream, hipEvent_t *ev,
+                  bool x_projected = false)
 {
     if (!shape || !basis_idx) return LBP_ERR_NULL;
     if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
@@ -340,7 +342,8 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     lbp::BasisPlan plan;
     rc = lbp::make_basis_plan(patch, basis_idx, r, &plan);
     if (rc) return rc;
-    rc = validate_buffers(x, gy, W, shape, gx, gW);
+    const size_t rows_r = (size_t)shape->N * shape->H * shape->W / ((size_t)patch * patch) * r;
+    rc = validate_buffers(x, gy, W, shape, gx, gW, x_projected ? rows_r : 0);
     if (rc) return rc;
 
     int dev;
@@ -365,15 +368,15 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     const long Mr = M / ((long)patch * patch) * r;
     const float inv_pp = 1.0f / (float)(patch * patch);
     void *gy_r = base + ws.gy_r;
-    void *x_r = base + ws.x_r;
+    const void *x_r = x_projected ? x : base + ws.x_r;
     float *gx_r = (float *)(base + ws.gx_r);
     float *part = (float *)(base + ws.splitk);
 
     if (ev) LBP_HIP(hipEventRecord(ev[0], s));
     // g^y = WHT(gy; I) is needed by both products; x^ = WHT(x; I) only by the weight gradient
     // (first two statements of Algorithm 1).  One launch covers both tensors.
-    if (gW)
-        LBP_HIP(lbp::launch_project_pair(gy, gy_r, Cout, x, x_r, Cin, N, H, Wd, dt, plan, path, s));
+    if (gW && !x_projected)
+        LBP_HIP(lbp::launch_project_pair(gy, gy_r, Cout, x, base + ws.x_r, Cin, N, H, Wd, dt, plan, path, s));
     else
         LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s));
     if (ev) LBP_HIP(hipEventRecord(ev[1], s));
@@ -421,6 +424,13 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
                      int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream)
 {
     return backward_impl(x, gy, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr);
+}
+
+int lbp_wht_backward_preprojected(const void *x_r, const void *gy, const void *W,
+                                  const lbp_shape_t *shape, int patch, const int32_t *basis_idx, int r,
+                                  void *gx, void *gW, void *stream)
+{
+    return backward_impl(x_r, gy, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr, true);
 }
 
 int lbp_wht_backward_profile(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,

@@ -211,6 +211,25 @@ def test_only_one_output_requested():
     assert none is None and rel_fro(to_host(gW), gW0) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_with_x_projected_in_the_forward_pass(dtype):
+    # x^ depends only on x and the index set (Alg. 1, first statement): computed once ahead of
+    # time it must give the very same bits, and match the oracle's whole Algorithm 1
+    wl = small("pre", 3, 16, 24, 72, 200, 8, dtype, 360)
+    host, dev = device_inputs(wl)
+    for r, order in [(8, "l1"), (21, "l1")]:
+        idx = oracle.select_bases(8, r, order)
+        x_r = binding.wht_project(dev["x"], 8, idx)
+        gx, gW = binding.lbp_wht_backward_preprojected(x_r, dev["gy"], dev["w"], 8, idx)
+        gx1, gW1 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx)
+        assert torch.equal(gx, gx1) and torch.equal(gW, gW1)
+        gx0, gW0 = oracle.lbp_wht_backward(host["x"], host["gy"], host["w"], 8, idx)
+        assert rel_fro(to_host(gx), gx0) <= TOL[dtype] and rel_fro(to_host(gW), gW0) <= TOL[dtype]
+    # only gW needs x^ at all
+    _, gW2 = binding.lbp_wht_backward_preprojected(x_r, dev["gy"], dev["w"], 8, idx, want_gx=False)
+    assert torch.equal(gW2, gW)
+
+
 def test_bf16_weight_gradient_output():
     wl = small("gwbf16", 2, 16, 16, 64, 128, 8, "bf16", 320)
     idx = oracle.select_bases(8, 8, "l1")

@@ -100,6 +100,19 @@ def test_full_bp_and_projection_argument_errors(lib):
     assert lib.lbp_wht_unproject(P(X), 2, 16, 16, 64, 1, 8, idx, 3, P(GX), None) in (-5, -4)
 
 
+def test_preprojected_backward_argument_errors(lib):
+    sh = binding.LbpShape(2, 16, 16, 64, 128, 1, 0)
+    idx = (ctypes.c_int32 * 4)(0, 1, 8, 9)
+    f = lib.lbp_wht_backward_preprojected
+    assert f(None, P(GY), P(W_), ctypes.byref(sh), 8, idx, 4, P(GX), P(GW), None) == -1
+    assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 8, idx, 0, P(GX), P(GW), None) == -4
+    assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 8, idx, 4, P(X), P(GW), None) == -7
+    # x_r is only P*r rows long: a buffer right behind it does not overlap it
+    rows_r = 2 * 16 * 16 // 64 * 4
+    behind = X + rows_r * 64 * 2
+    assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 8, idx, 4, P(behind), P(GW), None) in (0, -11)
+
+
 def test_no_cpu_fallback_without_a_device(lib):
     import torch
     if torch.cuda.is_available():
