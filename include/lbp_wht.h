@@ -89,6 +89,27 @@ typedef struct {
 int lbp_wht_select_bases(int patch, int r, int order, int32_t *basis_idx);
 
 /*
+ * Low-heuristic-error (LHE) selection, Section 3.2: the r bases with the largest profiled energy.
+ * `energy` is a HOST array of patch^2 doubles indexed u*patch + v (what lbp_wht_energy accumulates,
+ * copied back by the caller).  Writes the r indices by decreasing energy; bases of equal energy keep
+ * their LP_L1 order (the paper leaves ties open).  Pure host code.
+ */
+int lbp_wht_select_lhe(const double *energy, int patch, int r, int32_t *basis_idx);
+
+/*
+ * Profiling step of the LHE selection (Section 3.2; the spectrum shown in Section 4.4): adds to
+ * energy[u*patch + v] (DEVICE, patch^2 doubles, caller zeroes it before the first call) the sum over
+ * all patches and channels of the squared unnormalised WHT coefficient (Eq. 6) of basis (u, v) of
+ * `in` [N][H][W][C].  Call it on gy for a few training steps, copy `energy` back, then call
+ * lbp_wht_select_lhe.  Needs lbp_wht_energy_workspace_bytes of workspace (all coefficients are
+ * materialised once; this is a profiling call, not part of the per-step path).  bf16 tensors: the
+ * coefficients are rounded to bf16 before they are squared.  Sums run in a fixed order.
+ */
+int lbp_wht_energy(const void *in, int N, int H, int W, int C, int dtype, int patch, double *energy,
+                   void *stream);
+size_t lbp_wht_energy_workspace_bytes(int N, int H, int W, int C, int dtype, int patch);
+
+/*
  * Algorithm 1 (Section 3.1): x^ = WHT(x; I), g^y = WHT(gy; I), g^w = g^y^T x^, g^x = g^y w,
  * g~x = WHT^-1(g^x; I), g~w = g^w, with Eq. 6 / Eq. 7 per token patch.
  *   x, gy, W   inputs (device);  gx, gW outputs (device), either may be NULL to skip it.

@@ -19,6 +19,8 @@ from .lbp_oracle import (  # noqa: F401
     full_gx_tokens,
     full_gw_entries,
     flop_model,
+    wht_energy,
+    select_lhe,
     max_threads,
     set_threads,
 )

@@ -434,6 +434,56 @@ int oracle_full_gw_entries(const double *x, const double *gy, long M, int Cin, i
     return 0;
 }
 
+/* Energy of every basis (Section 3.2, low-heuristic-error selection; the spectrum of Section 4.4):
+ * E[u*p + v] = sum over patches and channels of (coefficient of basis (u,v))^2, unnormalised
+ * coefficients of Eq. 6.  By Parseval sum_j E[j] = p^2 * ||X||^2. */
+int oracle_wht_energy(const double *X, int N, int H, int W, int C, int p, double *E)
+{
+    if (!X || !E || check_grid(N, H, W, C, p)) return -1;
+    int pp = p * p;
+    int32_t *all = (int32_t *)malloc((size_t)pp * sizeof(int32_t));
+    if (!all) return -2;
+    for (int j = 0; j < pp; ++j) all[j] = j;
+    long Q = (long)N * (H / p) * (W / p);
+    double *coef = (double *)malloc((size_t)Q * pp * C * sizeof(double));
+    if (!coef) { free(all); return -2; }
+    int rc = oracle_project(X, N, H, W, C, p, pp, all, coef);
+    for (int j = 0; j < pp && !rc; ++j) {
+        double e = 0.0;
+        for (long q = 0; q < Q; ++q)
+            for (int c = 0; c < C; ++c) {
+                double v = coef[((size_t)q * pp + j) * C + c];
+                e += v * v;
+            }
+        E[j] = e;
+    }
+    free(coef);
+    free(all);
+    return rc;
+}
+
+/* Low-heuristic-error selection (Section 3.2): the r bases with the largest profiled energy, listed
+ * by decreasing energy.  The paper leaves ties open; here equal energies keep the LP_L1 order
+ * (reading of this build: parity unpinned for ties). */
+int oracle_select_lhe(const double *E, int p, int r, int32_t *idx)
+{
+    if (!E || !idx || !is_pow2(p) || r < 1 || r > p * p) return -1;
+    int pp = p * p;
+    int32_t *order = (int32_t *)malloc((size_t)pp * sizeof(int32_t));
+    if (!order) return -2;
+    int rc = oracle_select_bases(p, pp, 0, order);     /* LP_L1 order as the tie-break */
+    /* stable insertion sort by decreasing energy */
+    for (int i = 1; i < pp && !rc; ++i) {
+        int32_t cur = order[i];
+        int j = i - 1;
+        while (j >= 0 && E[order[j]] < E[cur]) { order[j + 1] = order[j]; --j; }
+        order[j + 1] = cur;
+    }
+    for (int k = 0; k < r && !rc; ++k) idx[k] = order[k];
+    free(order);
+    return rc;
+}
+
 /* Cost model of Table 1 (Section 3.3), FLOPs for one map of L tokens and rank r:
  * out[0] vanilla BP 4 Cx Cy L, out[1] projection (Cx+Cy) L r, out[2] low-rank matmuls
  * 4 Cx Cy r, out[3] reverse projection Cx L r. */

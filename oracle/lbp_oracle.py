@@ -202,6 +202,25 @@ def full_gw_entries(x, gy, co, ci):
     return out
 
 
+def wht_energy(X, p):
+    """Energy of every basis over all patches and channels: float64[p*p], index u*p + v."""
+    X = _f64(X)
+    N, H, W, C = X.shape
+    out = np.zeros(p * p, dtype=np.float64)
+    _check(_load().oracle_wht_energy(_p(X, _F64P), N, H, W, C, ctypes.c_int(p), _p(out, _F64P)),
+           "oracle_wht_energy")
+    return out
+
+
+def select_lhe(energy, p, r):
+    """Low-heuristic-error selection: the r bases of largest energy, by decreasing energy."""
+    energy = _f64(energy)
+    out = np.zeros(max(int(r), 1), dtype=np.int32)
+    _check(_load().oracle_select_lhe(_p(energy, _F64P), ctypes.c_int(p), ctypes.c_int(r), _p(out, _I32P)),
+           "oracle_select_lhe")
+    return out[:r]
+
+
 def flop_model(Cx, Cy, L, r):
     """Table 1: dict of FLOPs for vanilla BP, projection, low-rank matmuls, reverse projection."""
     out = (ctypes.c_double * 4)()

@@ -6,6 +6,8 @@ from .binding import (  # noqa: F401
     lbp_wht_backward,
     lbp_wht_backward_preprojected,
     select_bases,
+    select_lhe,
+    wht_energy,
     wht_project,
     wht_project_pair,
     wht_unproject,

@@ -17,7 +17,7 @@ _ORDERS = {"l1": ORDER_L1, "linf": ORDER_LINF, ORDER_L1: ORDER_L1, ORDER_LINF: O
 _DTYPES = {torch.float32: LBP_F32, torch.bfloat16: LBP_BF16}
 
 # every symbol include/lbp_wht.h declares
-EXPORTS = ("lbp_wht_select_bases", "lbp_wht_backward", "lbp_wht_backward_preprojected", "lbp_wht_backward_profile", "full_bp_backward", "lbp_wht_project",
+EXPORTS = ("lbp_wht_select_bases", "lbp_wht_select_lhe", "lbp_wht_energy", "lbp_wht_energy_workspace_bytes", "lbp_wht_backward", "lbp_wht_backward_preprojected", "lbp_wht_backward_profile", "full_bp_backward", "lbp_wht_project",
            "lbp_wht_project_pair", "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
            "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version")
 
@@ -51,6 +51,10 @@ def load():
     shp = ctypes.POINTER(LbpShape)
     lib.lbp_wht_select_bases.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p]
     lib.lbp_wht_backward.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.lbp_wht_select_lhe.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int, ctypes.c_int, i32p]
+    lib.lbp_wht_energy.argtypes = [vp] + [ctypes.c_int] * 6 + [vp, vp]
+    lib.lbp_wht_energy_workspace_bytes.argtypes = [ctypes.c_int] * 6
+    lib.lbp_wht_energy_workspace_bytes.restype = ctypes.c_size_t
     lib.lbp_wht_backward_preprojected.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
     lib.lbp_wht_backward_profile.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp,
                                              ctypes.POINTER(ctypes.c_float)]
@@ -98,6 +102,29 @@ def select_bases(patch, r, order="l1"):
     out = (ctypes.c_int32 * max(int(r), 1))()
     _check(load().lbp_wht_select_bases(int(patch), int(r), _ORDERS[order], out))
     return list(out[:r])
+
+
+def select_lhe(energy, patch, r):
+    """Low-heuristic-error selection of Section 3.2 from a host sequence of patch^2 energies."""
+    vals = [float(v) for v in energy]
+    arr = (ctypes.c_double * max(len(vals), 1))(*vals)
+    if len(vals) != patch * patch:
+        raise ValueError("energy must have patch^2 entries")
+    out = (ctypes.c_int32 * max(int(r), 1))()
+    _check(load().lbp_wht_select_lhe(arr, int(patch), int(r), out))
+    return list(out[:r])
+
+
+def wht_energy(t, patch, energy=None, stream=None):
+    """Adds the WHT energy spectrum of t [N,H,W,C] to `energy` (float64 device tensor of patch^2
+    entries, made and zeroed when not passed).  Returns it."""
+    N, H, W, C = t.shape
+    if energy is None:
+        energy = torch.zeros(patch * patch, dtype=torch.float64, device=t.device)
+    with torch.cuda.device(t.device):
+        _check(load().lbp_wht_energy(_dev_tensor(t, "t"), N, H, W, C, _DTYPES[t.dtype], int(patch),
+                                     _dev_tensor(energy, "energy", torch.float64), _stream_ptr(stream)))
+    return energy
 
 
 def _stream_ptr(stream):

@@ -33,6 +33,12 @@ hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *
 hipError_t launch_unproject_mfma(const float *in, int slices, void *out, int N, int H, int W, int C,
                                  const BasisPlan &plan, hipStream_t stream);
 
+// energy[j] += sum over patches q and channels of coef[q*pp + j][c]^2 for all pp = p^2 bases; `partial`
+// is scratch of pp * energy_chunks(Q) doubles.
+int energy_chunks(long Q);
+hipError_t launch_energy(const void *coef, long Q, int pp, int C, int dtype, double *partial, double *energy,
+                         hipStream_t stream);
+
 // What a matrix product does with its accumulators.
 enum class GemmOut {
     kF32 = 0,        // C[z][M][N] fp32 = scale * partial product of split-K slice z

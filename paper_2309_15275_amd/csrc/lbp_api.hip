@@ -300,6 +300,53 @@ int lbp_wht_project_pair(const void *x, const void *gy, const lbp_shape_t *shape
     return LBP_OK;
 }
 
+int lbp_wht_select_lhe(const double *energy, int patch, int r, int32_t *basis_idx)
+{
+    return lbp::select_lhe(energy, patch, r, basis_idx);
+}
+
+size_t lbp_wht_energy_workspace_bytes(int N, int H, int W, int C, int dtype, int patch)
+{
+    if (lbp::validate_grid(N, H, W, C, dtype, patch) != LBP_OK || patch == 0) return 0;
+    const size_t M = (size_t)N * H * W;
+    const long Q = (long)(M / ((size_t)patch * patch));
+    size_t coef = (M * C * lbp::dtype_size(dtype) + 255) / 256 * 256;
+    return coef + (size_t)patch * patch * lbp::energy_chunks(Q) * sizeof(double);
+}
+
+int lbp_wht_energy(const void *in, int N, int H, int W, int C, int dtype, int patch, double *energy,
+                   void *stream)
+{
+    if (!in || !energy) return LBP_ERR_NULL;
+    if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
+    int rc = lbp::validate_grid(N, H, W, C, dtype, patch);
+    if (rc) return rc;
+    const void *ptrs[2] = {in, energy};
+    rc = lbp::validate_alignment(ptrs, 2);
+    if (rc) return rc;
+    const int pp = patch * patch;
+    int32_t all[lbp::kMaxBases];
+    for (int j = 0; j < pp; ++j) all[j] = j;
+    lbp::BasisPlan plan;
+    rc = lbp::make_basis_plan(patch, all, pp, &plan);
+    if (rc) return rc;
+    int dev;
+    DeviceState *st;
+    rc = current_device(&dev, &st);
+    if (rc) return rc;
+    char *base = nullptr;
+    rc = get_workspace(st, lbp_wht_energy_workspace_bytes(N, H, W, C, dtype, patch), &base);
+    if (rc) return rc;
+    const size_t M = (size_t)N * H * W;
+    const long Q = (long)(M / (size_t)pp);
+    const size_t coef_bytes = (M * C * lbp::dtype_size(dtype) + 255) / 256 * 256;
+    hipStream_t s = (hipStream_t)stream;
+    // all p^2 coefficients of every patch (row q*p^2 + j = basis j in sequency order), then their squares
+    LBP_HIP(lbp::launch_project(in, base, N, H, W, C, dtype, plan, wht_path_from_env(), s));
+    LBP_HIP(lbp::launch_energy(base, Q, pp, C, dtype, (double *)(base + coef_bytes), energy, s));
+    return LBP_OK;
+}
+
 int lbp_wht_unproject(const void *in, int N, int H, int W, int C, int dtype, int patch,
                       const int32_t *basis_idx, int r, void *out, void *stream)
 {

@@ -52,6 +52,21 @@ int select_bases(int patch, int r, int order, int32_t *basis_idx)
     return LBP_OK;
 }
 
+int select_lhe(const double *energy, int patch, int r, int32_t *basis_idx)
+{
+    if (patch_log2(patch) < 0) return LBP_ERR_PATCH;
+    if (r < 1 || r > patch * patch) return LBP_ERR_RANK;
+    if (!energy || !basis_idx) return LBP_ERR_NULL;
+    const int pp = patch * patch;
+    std::vector<int32_t> order((size_t)pp);
+    int rc = select_bases(patch, pp, LBP_ORDER_L1, order.data());
+    if (rc) return rc;
+    // stable: bases of equal energy stay in LP_L1 order
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return energy[a] > energy[b]; });
+    for (int k = 0; k < r; ++k) basis_idx[k] = order[(size_t)k];
+    return LBP_OK;
+}
+
 static int trailing_zeros_capped(int v, int cap)
 {
     int n = 0;

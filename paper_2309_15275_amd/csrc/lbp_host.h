@@ -42,6 +42,10 @@ int make_basis_plan(int patch, const int32_t *basis_idx, int r, BasisPlan *plan)
 
 int select_bases(int patch, int r, int order, int32_t *basis_idx);
 
+// Low-heuristic-error selection (Section 3.2): the r bases of largest energy, by decreasing energy;
+// equal energies keep the LP_L1 order.  energy has patch^2 entries indexed u*patch + v.
+int select_lhe(const double *energy, int patch, int r, int32_t *basis_idx);
+
 // Element size in bytes of a dtype code, 0 if unknown.
 size_t dtype_size(int dtype);
 

@@ -230,6 +230,38 @@ def test_backward_with_x_projected_in_the_forward_pass(dtype):
     assert torch.equal(gW2, gW)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("patch", [4, 8, 16])
+def test_energy_spectrum_matches_oracle(dtype, patch):
+    wl = small("energy", 3, 2 * patch, 3 * patch, 40, 72, patch, dtype, 500 + patch)
+    host, dev = device_inputs(wl)
+    E = binding.wht_energy(dev["gy"], patch)
+    E0 = oracle.wht_energy(host["gy"], patch)
+    tol = 1e-5 if dtype == "f32" else 5e-3          # bf16: coefficients are rounded before squaring
+    assert np.max(np.abs(E.cpu().numpy() - E0)) <= tol * E0.max()
+    assert np.allclose(E.cpu().numpy(), E0, rtol=10 * tol, atol=tol * E0.max())
+    # a second call accumulates, and repeats the same bits
+    E2 = binding.wht_energy(dev["gy"], patch)
+    assert torch.equal(E2, E)
+    binding.wht_energy(dev["gy"], patch, energy=E)
+    assert torch.equal(E, 2 * E2)
+
+
+def test_lhe_selection_end_to_end():
+    # profile gy, pick the r strongest bases, run the backward with them (Section 3.2)
+    wl = small("lhe2e", 4, 16, 16, 64, 96, 8, "bf16", 520)
+    host, dev = device_inputs(wl)
+    E = binding.wht_energy(dev["gy"], 8).cpu().numpy()
+    E0 = oracle.wht_energy(host["gy"], 8)
+    idx = binding.select_lhe(E, 8, 10)
+    idx0 = oracle.select_lhe(E0, 8, 10)
+    # the selection is unique only up to near-ties: the energy the chosen set keeps must match
+    assert E0[idx].sum() >= (1 - 1e-3) * E0[idx0].sum()
+    assert len(set(idx)) == 10 and idx[0] == 0
+    egx, egw = run_backward_case(wl, np.asarray(idx))
+    assert egx <= TOL["bf16"] and egw <= TOL["bf16"]
+
+
 def test_bf16_weight_gradient_output():
     wl = small("gwbf16", 2, 16, 16, 64, 128, 8, "bf16", 320)
     idx = oracle.select_bases(8, 8, "l1")

@@ -113,6 +113,29 @@ def test_preprojected_backward_argument_errors(lib):
     assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 8, idx, 4, P(behind), P(GW), None) in (0, -11)
 
 
+def test_lhe_selection_is_bit_exact_against_the_oracle(lib):
+    rng = np.random.default_rng(5)
+    for p in (2, 4, 8, 16):
+        for trial in range(6):
+            E = rng.random(p * p)
+            if trial % 2:
+                E = np.round(E * 4) / 4              # many exact ties
+            if trial == 4:
+                E[:] = 1.0                           # flat spectrum: LP_L1 order
+            for r in (1, 3, p, p * p):
+                assert binding.select_lhe(E, p, r) == oracle.select_lhe(E, p, r).tolist()
+    assert binding.select_lhe(np.ones(64), 8, 10) == oracle.select_bases(8, 10, "l1").tolist()
+    arr = (ctypes.c_double * 64)()
+    out = (ctypes.c_int32 * 4)()
+    assert lib.lbp_wht_select_lhe(arr, 3, 1, out) == -3
+    assert lib.lbp_wht_select_lhe(arr, 8, 65, out) == -4
+    assert lib.lbp_wht_select_lhe(None, 8, 4, out) == -1
+    assert lib.lbp_wht_energy(None, 2, 16, 16, 64, 1, 8, P(GX), None) == -1
+    assert lib.lbp_wht_energy(P(X), 2, 12, 16, 64, 1, 8, P(GX), None) == -2
+    assert lib.lbp_wht_energy_workspace_bytes(2, 16, 16, 64, 1, 8) >= 2 * 256 * 64 * 2
+    assert lib.lbp_wht_energy_workspace_bytes(2, 16, 16, 64, 1, 5) == 0
+
+
 def test_no_cpu_fallback_without_a_device(lib):
     import torch
     if torch.cuda.is_available():

@@ -363,6 +363,61 @@ def test_grid_must_be_a_multiple_of_the_patch():
         oracle.lbp_wht_backward(x, gy, w, 4, [0])
 
 
+# ---------- energy spectrum and low-heuristic-error selection (Section 3.2, Section 4.4) ----------
+
+def test_energy_obeys_parseval_and_finds_a_planted_basis():
+    p = 8
+    rng = np.random.default_rng(100)
+    X = rng.standard_normal((2, 16, 8, 3))
+    E = oracle.wht_energy(X, p)
+    assert E.shape == (64,) and np.all(E >= 0)
+    assert abs(E.sum() - p * p * np.sum(X ** 2)) < 1e-9 * E.sum()
+    # a tensor made of one basis only: all its energy sits at that index
+    wal = walsh_np(p)
+    u, v = 5, 2
+    patch = np.outer(wal[u], wal[v]).astype(np.float64)
+    Y = np.tile(patch[None, :, :, None], (1, 2, 3, 4)) * 0.5
+    E1 = oracle.wht_energy(Y, p)
+    want = np.zeros(64)
+    want[u * p + v] = 6 * 4 * (0.5 * 64) ** 2          # 6 patches, 4 channels, coefficient 0.5 * p^2
+    assert np.allclose(E1, want, rtol=0, atol=1e-9)
+
+
+def test_energy_matches_kronecker_spectrum():
+    p = 4
+    rng = np.random.default_rng(101)
+    X = rng.standard_normal((1, 8, 4, 2))
+    full = np.kron(walsh_np(p), walsh_np(p)).astype(np.float64)       # [u*p+v, h*p+w]
+    coef = np.einsum("jt,qtc->qjc", full, to_patches(X, p))
+    assert np.allclose(oracle.wht_energy(X, p), (coef ** 2).sum(axis=(0, 2)), rtol=1e-12)
+
+
+def test_lhe_selection_takes_the_largest_energies_and_breaks_ties_low_pass():
+    p = 4
+    E = np.zeros(16)
+    E[[7, 2, 9]] = [5.0, 9.0, 1.0]
+    assert oracle.select_lhe(E, p, 3).tolist() == [2, 7, 9]
+    # remaining entries tie at zero: they follow the LP_L1 order 0, 1, 4, 5, ...
+    assert oracle.select_lhe(E, p, 6).tolist() == [2, 7, 9, 0, 1, 4]
+    # a flat spectrum reproduces LP_L1
+    assert np.array_equal(oracle.select_lhe(np.ones(16), p, 10), oracle.select_bases(p, 10, "l1"))
+    with pytest.raises(ValueError):
+        oracle.select_lhe(E, p, 17)
+
+
+def test_smooth_gradients_put_their_energy_in_the_low_sequency_corner():
+    # the structure the paper reports for g_y (Section 4.4): with the synthetic smooth field the
+    # ten strongest bases are all inside the LP_L1-5 triangle and hold most of the energy
+    from paper_2309_15275_amd import workloads
+    wl = workloads.scaled(workloads.WORKLOADS["cfg2_vitb_fc1"], N=2, Cin=16, Cout=32)
+    gy = workloads.make_inputs(wl)["gy"]
+    E = oracle.wht_energy(gy, 8)
+    top = oracle.select_lhe(E, 8, 10)
+    assert all((i // 8) + (i % 8) <= 4 for i in top)
+    assert E[top].sum() > 0.85 * E.sum()
+    assert top[0] == 0
+
+
 # ---------- cost model (Table 1, Section 3.3) ----------
 
 def test_cost_model_reproduces_the_printed_example():
