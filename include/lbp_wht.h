@@ -13,7 +13,11 @@
  *            (Section 2 writes w in R^{Cy x Cx}; y = x w^T per token.)
  *   Patches  the H x W token grid of every image is tiled into non-overlapping patch x patch
  *            blocks; the order-`patch` 2-D WHT of Section 3 is applied inside each block, and the
- *            weight gradient sums over blocks and images.  H and W must be multiples of patch.
+ *            weight gradient sums over blocks and images.  A grid whose H or W is not a multiple
+ *            of patch (the 7 x 7 = 49-token maps of Section 3.3) is treated as zero-padded at
+ *            its bottom and right edges up to the next multiple: there are
+ *            P = N * ceil(H/patch) * ceil(W/patch) blocks, padding tokens are never read or
+ *            written, and the 1/patch^2 factors are unchanged.  Low-rank buffers have P*r rows.
  *   Bases    basis_idx[k] = u*patch + v, with (u, v) the 0-based SEQUENCY indices along the grid's
  *            H axis (u) and W axis (v): index 0 is the constant basis and a larger index is a
  *            higher frequency (Section 3.2).  Entries must be distinct and in [0, patch^2).
@@ -56,8 +60,8 @@ typedef enum {
 typedef enum {
     LBP_OK = 0,
     LBP_ERR_NULL = -1,     /* a required pointer is NULL                                       */
-    LBP_ERR_SHAPE = -2,    /* non-positive dimension, H or W not a multiple of patch, or a size
-                              beyond what 32-bit row indices address (N*H*W >= 2^31)           */
+    LBP_ERR_SHAPE = -2,    /* non-positive dimension, or a size beyond what 32-bit row indices
+                              address (N*H*W >= 2^31)                                          */
     LBP_ERR_PATCH = -3,    /* patch not in {2, 4, 8, 16}                                       */
     LBP_ERR_RANK = -4,     /* r < 1 or r > patch^2                                             */
     LBP_ERR_BASIS = -5,    /* a basis index out of [0, patch^2) or listed twice                */
@@ -152,7 +156,7 @@ int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_sha
 /*
  * The projection p(.) of Eq. 6 alone (first two statements of Algorithm 1), for one tensor:
  *   in  [N][H][W][C] (device, dtype)  ->  out [(N*H*W/patch^2) * r][C] (device, same dtype),
- * row (q*r + k) holding coefficient k of patch q = (n*(H/patch) + a)*(W/patch) + b, unnormalised.
+ * row (q*r + k) holding coefficient k of patch q = (n*ceil(H/patch) + a)*ceil(W/patch) + b, unnormalised.
  * It is what the backward runs internally on x and gy; exported so that the projection can be
  * measured and checked by itself.
  */

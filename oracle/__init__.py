@@ -21,6 +21,11 @@ from .lbp_oracle import (  # noqa: F401
     flop_model,
     wht_energy,
     select_lhe,
+    pad_grid,
+    project_padded,
+    unproject_padded,
+    lbp_wht_backward_padded,
+    wht_energy_padded,
     max_threads,
     set_threads,
 )

@@ -221,6 +221,44 @@ def select_lhe(energy, p, r):
     return out[:r]
 
 
+# --------------------------------------------------------------------------------------------
+# Token grids that are not multiples of the patch.  The paper's own maps have 7 x 7 = 49 tokens
+# (Section 3.3's worked example, the latency tables of the appendix) and does not say how a
+# power-of-two transform meets them; the reading taken here: every image's grid is zero-padded
+# at the bottom and the right up to the next multiple of p, Algorithm 1 runs on the padded
+# grids unchanged (1/p^2 normalisation included), and the rows of g~x that belong to padding
+# are dropped.  Each function below is literally pad -> the function above -> crop.
+# --------------------------------------------------------------------------------------------
+
+def pad_grid(X, p):
+    """[N,H,W,C] -> [N,ceil(H/p)*p,ceil(W/p)*p,C], new tokens zero."""
+    X = _f64(X)
+    N, H, W, C = X.shape
+    return np.pad(X, ((0, 0), (0, -H % p), (0, -W % p), (0, 0)))
+
+
+def project_padded(X, p, idx):
+    return project(pad_grid(X, p), p, idx)
+
+
+def unproject_padded(Xr, shape, p, idx):
+    N, H, W, C = shape
+    full = unproject(Xr, (N, H + (-H % p), W + (-W % p), C), p, idx)
+    return np.ascontiguousarray(full[:, :H, :W, :])
+
+
+def lbp_wht_backward_padded(x, gy, w, p, idx, want_gx=True, want_gw=True):
+    H, W = x.shape[1:3]
+    gx, gW = lbp_wht_backward(pad_grid(x, p), pad_grid(gy, p), w, p, idx, want_gx, want_gw)
+    if gx is not None:
+        gx = np.ascontiguousarray(gx[:, :H, :W, :])
+    return gx, gW
+
+
+def wht_energy_padded(X, p):
+    return wht_energy(pad_grid(X, p), p)
+
+
 def flop_model(Cx, Cy, L, r):
     """Table 1: dict of FLOPs for vanilla BP, projection, low-rank matmuls, reverse projection."""
     out = (ctypes.c_double * 4)()

@@ -95,6 +95,11 @@ def _idx_array(basis_idx):
     return (ctypes.c_int32 * max(len(vals), 1))(*vals), len(vals)
 
 
+def patch_count(N, H, W, patch):
+    """Patches of N zero-padded H x W grids: N * ceil(H/patch) * ceil(W/patch)."""
+    return N * (-(-H // patch)) * (-(-W // patch))
+
+
 def select_bases(patch, r, order="l1"):
     """Low-pass selection of Section 3.2; returns a list of r indices u*patch + v."""
     if order not in _ORDERS:
@@ -177,7 +182,7 @@ def lbp_wht_backward_preprojected(x_r, gy, w, patch, basis_idx, gx=None, gW=None
     N, H, W, Cout = gy.shape
     Cin = w.shape[1]
     idx, r = _idx_array(basis_idx)
-    if tuple(x_r.shape) != (N * H * W // (patch * patch) * r, Cin) or tuple(w.shape) != (Cout, Cin):
+    if tuple(x_r.shape) != (patch_count(N, H, W, patch) * r, Cin) or tuple(w.shape) != (Cout, Cin):
         raise ValueError("shapes must be x_r[P*r,Cin], gy[N,H,W,Cout], w[Cout,Cin]")
     shape = LbpShape(N, H, W, Cin, Cout, _DTYPES[gy.dtype], _DTYPES[gw_dtype])
     if want_gx and gx is None:
@@ -229,7 +234,7 @@ def wht_project(t, patch, basis_idx, out=None, stream=None):
     N, H, W, C = t.shape
     idx, r = _idx_array(basis_idx)
     if out is None:
-        out = torch.empty((N * H * W // (patch * patch) * r, C), dtype=t.dtype, device=t.device)
+        out = torch.empty((patch_count(N, H, W, patch) * r, C), dtype=t.dtype, device=t.device)
     with torch.cuda.device(t.device):
         _check(load().lbp_wht_project(_dev_tensor(t, "t"), N, H, W, C, _DTYPES[t.dtype], int(patch),
                                       idx, r, _dev_tensor(out, "out", t.dtype), _stream_ptr(stream)))
@@ -241,7 +246,7 @@ def wht_project_pair(x, gy, patch, basis_idx, x_r=None, gy_r=None, stream=None):
     N, H, W, Cin = x.shape
     Cout = gy.shape[-1]
     idx, r = _idx_array(basis_idx)
-    rows = N * H * W // (patch * patch) * r
+    rows = patch_count(N, H, W, patch) * r
     if x_r is None:
         x_r = torch.empty((rows, Cin), dtype=x.dtype, device=x.device)
     if gy_r is None:

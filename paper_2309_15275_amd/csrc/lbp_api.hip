@@ -261,7 +261,7 @@ int lbp_wht_project(const void *in, int N, int H, int W, int C, int dtype, int p
     if (rc) return rc;
     size_t esz = lbp::dtype_size(dtype);
     size_t M = (size_t)N * H * W;
-    if (lbp::ranges_overlap(in, M * C * esz, out, M / (patch * patch) * r * C * esz)) return LBP_ERR_ALIAS;
+    if (lbp::ranges_overlap(in, M * C * esz, out, (size_t)lbp::patch_count(N, H, W, patch) * r * C * esz)) return LBP_ERR_ALIAS;
     int dev;
     DeviceState *st;
     rc = current_device(&dev, &st);
@@ -284,7 +284,7 @@ int lbp_wht_project_pair(const void *x, const void *gy, const lbp_shape_t *shape
     rc = lbp::validate_alignment(ptrs, 4);
     if (rc) return rc;
     const size_t esz = lbp::dtype_size(shape->dtype);
-    const size_t M = (size_t)shape->N * shape->H * shape->W, Mr = M / (patch * patch) * r;
+    const size_t M = (size_t)shape->N * shape->H * shape->W, Mr = (size_t)lbp::patch_count(shape->N, shape->H, shape->W, patch) * r;
     const void *bufs[4] = {x, gy, x_r, gy_r};
     const size_t bytes[4] = {M * shape->Cin * esz, M * shape->Cout * esz, Mr * shape->Cin * esz,
                              Mr * shape->Cout * esz};
@@ -308,9 +308,8 @@ int lbp_wht_select_lhe(const double *energy, int patch, int r, int32_t *basis_id
 size_t lbp_wht_energy_workspace_bytes(int N, int H, int W, int C, int dtype, int patch)
 {
     if (lbp::validate_grid(N, H, W, C, dtype, patch) != LBP_OK || patch == 0) return 0;
-    const size_t M = (size_t)N * H * W;
-    const long Q = (long)(M / ((size_t)patch * patch));
-    size_t coef = (M * C * lbp::dtype_size(dtype) + 255) / 256 * 256;
+    const long Q = lbp::patch_count(N, H, W, patch);
+    size_t coef = ((size_t)Q * patch * patch * C * lbp::dtype_size(dtype) + 255) / 256 * 256;
     return coef + (size_t)patch * patch * lbp::energy_chunks(Q) * sizeof(double);
 }
 
@@ -337,9 +336,8 @@ int lbp_wht_energy(const void *in, int N, int H, int W, int C, int dtype, int pa
     char *base = nullptr;
     rc = get_workspace(st, lbp_wht_energy_workspace_bytes(N, H, W, C, dtype, patch), &base);
     if (rc) return rc;
-    const size_t M = (size_t)N * H * W;
-    const long Q = (long)(M / (size_t)pp);
-    const size_t coef_bytes = (M * C * lbp::dtype_size(dtype) + 255) / 256 * 256;
+    const long Q = lbp::patch_count(N, H, W, patch);
+    const size_t coef_bytes = ((size_t)Q * pp * C * lbp::dtype_size(dtype) + 255) / 256 * 256;
     hipStream_t s = (hipStream_t)stream;
     // all p^2 coefficients of every patch (row q*p^2 + j = basis j in sequency order), then their squares
     LBP_HIP(lbp::launch_project(in, base, N, H, W, C, dtype, plan, wht_path_from_env(), s));
@@ -360,7 +358,7 @@ int lbp_wht_unproject(const void *in, int N, int H, int W, int C, int dtype, int
     rc = lbp::validate_alignment(ptrs, 2);
     if (rc) return rc;
     size_t M = (size_t)N * H * W;
-    if (lbp::ranges_overlap(in, M / (patch * patch) * r * C * 4, out, M * C * lbp::dtype_size(dtype)))
+    if (lbp::ranges_overlap(in, (size_t)lbp::patch_count(N, H, W, patch) * r * C * 4, out, M * C * lbp::dtype_size(dtype)))
         return LBP_ERR_ALIAS;
     int dev;
     DeviceState *st;
@@ -389,7 +387,7 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     lbp::BasisPlan plan;
     rc = lbp::make_basis_plan(patch, basis_idx, r, &plan);
     if (rc) return rc;
-    const size_t rows_r = (size_t)shape->N * shape->H * shape->W / ((size_t)patch * patch) * r;
+    const size_t rows_r = (size_t)lbp::patch_count(shape->N, shape->H, shape->W, patch) * r;
     rc = validate_buffers(x, gy, W, shape, gx, gW, x_projected ? rows_r : 0);
     if (rc) return rc;
 
@@ -399,7 +397,8 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     if (rc) return rc;
     const lbp::GemmPath gpath = gemm_path_from_env();
     const int fuse_env = fuse_unproject_from_env();
-    const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
+    const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath) &&
+                          !lbp::grid_is_ragged(shape->H, shape->W, patch);
     lbp::WorkspacePlan ws;
     rc = lbp::plan_workspace(shape, patch, r, st->num_cus, can_fuse, fuse_env == 1, &ws);
     if (rc) return rc;
@@ -412,7 +411,7 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     const int N = shape->N, H = shape->H, Wd = shape->W, Cin = shape->Cin, Cout = shape->Cout;
     const int dt = shape->dtype;
     const long M = (long)N * H * Wd;
-    const long Mr = M / ((long)patch * patch) * r;
+    const long Mr = lbp::patch_count(N, H, Wd, patch) * r;
     const float inv_pp = 1.0f / (float)(patch * patch);
     void *gy_r = base + ws.gy_r;
     const void *x_r = x_projected ? x : base + ws.x_r;

@@ -124,7 +124,6 @@ int validate_grid(int N, int H, int W, int C, int dtype, int patch)
     if (N < 1 || H < 1 || W < 1 || C < 1) return LBP_ERR_SHAPE;
     if (patch != 0) {
         if (patch_log2(patch) < 0) return LBP_ERR_PATCH;
-        if (H % patch || W % patch) return LBP_ERR_SHAPE;
     }
     long long tokens = (long long)N * H * W;
     if (tokens >= (1ll << 31)) return LBP_ERR_SHAPE;
@@ -226,7 +225,7 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
         ws->total = off;
         return LBP_OK;
     }
-    const long Mr = M / ((long)patch * patch) * r;
+    const long Mr = patch_count(s->N, s->H, s->W, patch) * r;
     ws->gw = plan_gemm(s->Cout, s->Cin, Mr, gw_bytes, true, 0, 0, num_cus);
     // gx: fused epilogue (no split, few workgroups when Mr is small) against split-K partial sums
     // that the reverse-projection kernel adds up while it reads them
@@ -245,7 +244,7 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
     unfused.est_us += 8.0 + ((double)unfused.splits * Mr * s->Cin * 4 + (double)M * s->Cin * esz) / 4.0e6;
     ws->gx = unfused;
     ws->gx_fused = false;
-    if (can_fuse && s->dtype == LBP_BF16) {
+    if (can_fuse && s->dtype == LBP_BF16 && !grid_is_ragged(s->H, s->W, patch)) {
         GemmPlan fused = plan_gemm(Mr, s->Cin, s->Cout, 2, false, r, patch, num_cus);
         if (force_fuse || fused.est_us <= unfused.est_us) {
             ws->gx = fused;
@@ -269,7 +268,7 @@ const char *status_string(int code)
     switch (code) {
         case LBP_OK: return "success";
         case LBP_ERR_NULL: return "a required pointer is NULL";
-        case LBP_ERR_SHAPE: return "bad shape: non-positive dimension, token grid not a multiple of the patch, or too many tokens";
+        case LBP_ERR_SHAPE: return "bad shape: non-positive dimension or too many tokens";
         case LBP_ERR_PATCH: return "patch must be 2, 4, 8 or 16";
         case LBP_ERR_RANK: return "rank r must be in [1, patch^2]";
         case LBP_ERR_BASIS: return "basis index out of range or listed twice";

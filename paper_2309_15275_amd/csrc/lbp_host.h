@@ -19,6 +19,15 @@ int sequency_to_natural(int s, int log2p);
 // -1 if p is not one of 2, 4, 8, 16, else log2(p).
 int patch_log2(int patch);
 
+// Patches of a batch of H x W token grids.  A grid that is not a multiple of the patch is treated
+// as zero-padded at its bottom and right edges up to the next multiple (the paper's own maps are
+// 7 x 7 = 49 tokens, Section 3.3).
+inline long patch_count(int N, int H, int W, int patch)
+{
+    return (long)N * ((H + patch - 1) / patch) * ((W + patch - 1) / patch);
+}
+inline bool grid_is_ragged(int H, int W, int patch) { return H % patch != 0 || W % patch != 0; }
+
 // Everything the projection kernels need to know about the selected bases, passed to them by
 // value in the kernel arguments (no device copy, no host/device synchronisation).
 //

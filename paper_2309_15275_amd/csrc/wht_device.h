@@ -15,21 +15,45 @@ struct PooledSel {
     uint8_t pos[64];
 };
 
-// Decomposition of a patch number into the first token of the patch.
+// Decomposition of a patch number into its place on the token grid.  The grid may end inside the
+// last patch row / column (zero padding): tokens with row >= Ht or column >= Wt do not exist.
 struct GridGeom {
     int Wt;        // tokens per grid row (W)
+    int Ht;        // grid rows (H)
     int HWt;       // tokens per image (H*W)
-    int PW;        // patches per grid row
+    int PW;        // patches per grid row, ceil(W / patch)
     int PHW;       // patches per image
     int patch;
+    // image n, first grid row a0 and first grid column b0 of patch q
+    __device__ __forceinline__ void origin(long q, long &n, int &a0, int &b0) const
+    {
+        n = q / PHW;
+        int rem = (int)(q - n * PHW);
+        int a = rem / PW;
+        a0 = a * patch;
+        b0 = (rem - a * PW) * patch;
+    }
+    // flat index of the patch's first token (only for grids that are multiples of the patch)
     __device__ __forceinline__ long first_token(long q) const
     {
-        long n = q / PHW;
-        int rem = (int)(q - n * PHW);
-        int a = rem / PW, b = rem - a * PW;
-        return n * HWt + (long)a * patch * Wt + (long)b * patch;
+        long n;
+        int a0, b0;
+        origin(q, n, a0, b0);
+        return n * HWt + (long)a0 * Wt + b0;
     }
 };
+
+inline GridGeom make_geom(int H, int W, int patch)
+{
+    GridGeom g;
+    g.Wt = W;
+    g.Ht = H;
+    g.HWt = H * W;
+    g.PW = (W + patch - 1) / patch;
+    g.PHW = ((H + patch - 1) / patch) * g.PW;
+    g.patch = patch;
+    return g;
+}
 
 // Sum-pool a P x P patch over 2^MH x 2^MW token groups, then transform the pooled patch.
 template <int P, int MH, int MW>

@@ -204,7 +204,10 @@ __global__ __launch_bounds__(128) void wht_project_generic_kernel(const uint4 *_
     if (cv >= Cv) return;
     long q = blockIdx.x;
     int p = g.patch, pp = p * p;
-    const uint4 *src = in + (size_t)g.first_token(q) * Cv + cv;
+    long n;
+    int a0, b0;
+    g.origin(q, n, a0, b0);
+    const uint4 *src = in + ((size_t)n * g.HWt + (size_t)a0 * g.Wt + b0) * Cv + cv;
     for (int k0 = 0; k0 < r; k0 += KC) {
         float acc[KC][VN];
 #pragma unroll
@@ -213,6 +216,7 @@ __global__ __launch_bounds__(128) void wht_project_generic_kernel(const uint4 *_
             for (int e = 0; e < VN; ++e) acc[kk][e] = 0.f;
         for (int t = 0; t < pp; ++t) {
             int h = t / p, w = t - h * p;
+            if (a0 + h >= g.Ht || b0 + w >= g.Wt) continue;      // zero padding past the grid's edge
             float f[VN];
             Vec16<BF16>::load(src[((size_t)h * g.Wt + w) * Cv], f);
 #pragma unroll
@@ -245,7 +249,10 @@ __global__ __launch_bounds__(128) void wht_unproject_generic_kernel(const float 
     const int C = Cv * VN;
     const float scale = 1.0f / (float)pp;
     const float *src = in + (size_t)q * r * C + (size_t)cv * VN;
-    uint4 *dst = out + (size_t)g.first_token(q) * Cv + cv;
+    long n;
+    int a0, b0;
+    g.origin(q, n, a0, b0);
+    uint4 *dst = out + ((size_t)n * g.HWt + (size_t)a0 * g.Wt + b0) * Cv + cv;
     for (int t0 = 0; t0 < pp; t0 += TC) {     // pp is a multiple of 4 for every legal patch
         float acc[TC][VN];
 #pragma unroll
@@ -276,7 +283,7 @@ __global__ __launch_bounds__(128) void wht_unproject_generic_kernel(const float 
             int h = t / p, w = t - h * p;
 #pragma unroll
             for (int e = 0; e < VN; ++e) acc[tt][e] *= scale;
-            dst[((size_t)h * g.Wt + w) * Cv] = store_vec(acc[tt]);
+            if (a0 + h < g.Ht && b0 + w < g.Wt) dst[((size_t)h * g.Wt + w) * Cv] = store_vec(acc[tt]);
         }
     }
 }
@@ -284,17 +291,6 @@ __global__ __launch_bounds__(128) void wht_unproject_generic_kernel(const float 
 // ------------------------------------------------------------------------------------------
 // dispatch
 // ------------------------------------------------------------------------------------------
-
-GridGeom make_geom(int H, int W, int patch)
-{
-    GridGeom g;
-    g.Wt = W;
-    g.HWt = H * W;
-    g.PW = W / patch;
-    g.PHW = (H / patch) * (W / patch);
-    g.patch = patch;
-    return g;
-}
 
 // Slices of the reverse direction's input (split-K partial sums) and their pitch in floats.
 struct Slices {
@@ -361,7 +357,7 @@ hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int
 {
     const bool bf16 = dtype == LBP_BF16;
     const int Cd = bf16 ? C / 2 : C;
-    const long Q = (long)N * (H / plan.patch) * (W / plan.patch);
+    const long Q = patch_count(N, H, W, plan.patch);
     const long items = Q * Cd;
     Second sec;
     if (in2) {
@@ -400,7 +396,7 @@ hipError_t launch_generic(const void *in, void *out, int N, int H, int W, int C,
 {
     const bool bf16 = dtype == LBP_BF16;
     const int Cv = bf16 ? C / 8 : C / 4;
-    const long Q = (long)N * (H / plan.patch) * (W / plan.patch);
+    const long Q = patch_count(N, H, W, plan.patch);
     GridGeom g = make_geom(H, W, plan.patch);
     NatTable nat;
     for (int k = 0; k < kMaxBases; ++k) nat.v[k] = plan.nat[k];
@@ -423,18 +419,21 @@ hipError_t launch_generic(const void *in, void *out, int N, int H, int W, int C,
     return hipGetLastError();
 }
 
-bool use_register_path(const BasisPlan &plan, WhtPath path)
+// The register kernels assume whole patches.
+bool use_register_path(const BasisPlan &plan, WhtPath path, int H, int W)
 {
-    if (plan.patch > 8) return false;
+    if (plan.patch > 8 || grid_is_ragged(H, W, plan.patch)) return false;
     return path != WhtPath::kGeneric;
 }
 
 // The matrix-core form takes over where the pooled butterfly cannot prune (more than 16 pooled
 // coefficients per channel) and for patch 16.
-bool use_mfma_path(const BasisPlan &plan, WhtPath path, int dtype, int C)
+bool use_mfma_path(const BasisPlan &plan, WhtPath path, int dtype, int C, int H, int W)
 {
     if (!wht_mfma_supported(plan, dtype, C)) return false;
     if (path == WhtPath::kMfma) return true;
+    if (path == WhtPath::kGeneric) return false;
+    if (grid_is_ragged(H, W, plan.patch)) return true;      // also when the register path was asked for
     if (path != WhtPath::kAuto) return false;
     if (plan.patch > 8) return true;
     return (plan.patch >> plan.mh) * (plan.patch >> plan.mw) > 16;
@@ -445,10 +444,9 @@ bool use_mfma_path(const BasisPlan &plan, WhtPath path, int dtype, int C)
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
                           const BasisPlan &plan, WhtPath path, hipStream_t stream)
 {
-    if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
-    if (use_mfma_path(plan, path, dtype, C))
+    if (use_mfma_path(plan, path, dtype, C, H, W))
         return launch_project_mfma(in, out, C, nullptr, nullptr, 0, N, H, W, plan, stream);
-    if (use_register_path(plan, path))
+    if (use_register_path(plan, path, H, W))
         return launch_reg<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
     return launch_generic<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
 }
@@ -457,10 +455,9 @@ hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *
                                int N, int H, int W, int dtype, const BasisPlan &plan, WhtPath path,
                                hipStream_t stream)
 {
-    if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
-    if (use_mfma_path(plan, path, dtype, C0) && use_mfma_path(plan, path, dtype, C1))
+    if (use_mfma_path(plan, path, dtype, C0, H, W) && use_mfma_path(plan, path, dtype, C1, H, W))
         return launch_project_mfma(in0, out0, C0, in1, out1, C1, N, H, W, plan, stream);
-    if (use_register_path(plan, path))
+    if (use_register_path(plan, path, H, W))
         return launch_reg<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream, in1, out1, C1);
     hipError_t e = launch_generic<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream);
     if (e != hipSuccess) return e;
@@ -470,14 +467,13 @@ hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *
 hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H, int W, int C,
                             int dtype, const BasisPlan &plan, WhtPath path, hipStream_t stream)
 {
-    if (path == WhtPath::kRegister && plan.patch > 8) return hipErrorInvalidValue;
     if (slices < 1) return hipErrorInvalidValue;
-    if (use_mfma_path(plan, path, dtype, C))
+    if (use_mfma_path(plan, path, dtype, C, H, W))
         return launch_unproject_mfma(in, slices, out, N, H, W, C, plan, stream);
     Slices sl;
     sl.count = slices;
-    sl.stride = (size_t)N * (H / plan.patch) * (W / plan.patch) * plan.r * C;
-    if (use_register_path(plan, path))
+    sl.stride = (size_t)patch_count(N, H, W, plan.patch) * plan.r * C;
+    if (use_register_path(plan, path, H, W))
         return launch_reg<true>(in, out, N, H, W, C, dtype, plan, sl, stream);
     return launch_generic<true>(in, out, N, H, W, C, dtype, plan, sl, stream);
 }

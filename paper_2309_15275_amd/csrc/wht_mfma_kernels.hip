@@ -117,14 +117,17 @@ __global__ __launch_bounds__(256) void wht_project_mfma_kernel(MfmaTensor t0, Mf
     for (long item = wg * items_per_wg; item < min(t.items, (wg + 1) * (long)items_per_wg); ++item) {
         const long q = item / t.chunks;
         const int c0 = (int)(item - q * t.chunks) * CB;
-        const size_t tok0 = (size_t)g.first_token(q);
+        long n;
+        int a0, b0;
+        g.origin(q, n, a0, b0);
+        const size_t tok0 = (size_t)n * g.HWt + (size_t)a0 * g.Wt + b0;
         __syncthreads();                      // the previous item's stores have left LDS
         // ---- tokens -> LDS [token][channel]
         for (int c = tid; c < P2PAD * (CB / 8); c += 256) {
             int tk = c >> 4, cc = c & 15;
             u32x4_t v = {0u, 0u, 0u, 0u};
-            if (tk < p2 && c0 + cc * 8 < t.C) {
-                int h = tk / p, w = tk - h * p;
+            int h = tk / p, w = tk - h * p;
+            if (tk < p2 && c0 + cc * 8 < t.C && a0 + h < g.Ht && b0 + w < g.Wt) {   // else zero padding
                 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(
                     t.in + (tok0 + (size_t)h * g.Wt + w) * t.C + c0 + cc * 8));
             }
@@ -216,7 +219,10 @@ __global__ __launch_bounds__(256) void wht_unproject_mfma_kernel(const float *__
     for (long item = wg * items_per_wg; item < min(items, (wg + 1) * (long)items_per_wg); ++item) {
         const long q = item / chunks;
         const int c0 = (int)(item - q * chunks) * CB;
-        const size_t tok0 = (size_t)g.first_token(q);
+        long n;
+        int a0, b0;
+        g.origin(q, n, a0, b0);
+        const size_t tok0 = (size_t)n * g.HWt + (size_t)a0 * g.Wt + b0;
         __syncthreads();
         // ---- coefficients (fp32, split-K slices summed in fixed order) -> bf16 -> LDS [basis][channel]
         for (int c = tid; c < ksteps * 16 * (CB / 4); c += 256) {
@@ -270,24 +276,13 @@ __global__ __launch_bounds__(256) void wht_unproject_mfma_kernel(const float *__
         __syncthreads();
         for (int c = tid; c < p2 * (CB / 8); c += 256) {
             int tk = c >> 4, cc = c & 15;
-            if (c0 + cc * 8 < C) {
-                int h = tk / p, w = tk - h * p;
+            int h = tk / p, w = tk - h * p;
+            if (c0 + cc * 8 < C && a0 + h < g.Ht && b0 + w < g.Wt) {
                 u32x4_t v = *reinterpret_cast<const u32x4_t *>(smem + tk * S_OUT + cc * 16);
                 __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(out + (tok0 + (size_t)h * g.Wt + w) * C + c0 + cc * 8));
             }
         }
     }
-}
-
-GridGeom make_geom(int H, int W, int patch)
-{
-    GridGeom g;
-    g.Wt = W;
-    g.HWt = H * W;
-    g.PW = W / patch;
-    g.PHW = (H / patch) * (W / patch);
-    g.patch = patch;
-    return g;
 }
 
 NatTable make_nat(const BasisPlan &plan)
@@ -322,7 +317,7 @@ bool wht_mfma_supported(const BasisPlan &plan, int dtype, int C)
 hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
                                int N, int H, int W, const BasisPlan &plan, hipStream_t stream)
 {
-    const long Q = (long)N * (H / plan.patch) * (W / plan.patch);
+    const long Q = patch_count(N, H, W, plan.patch);
     GridGeom g = make_geom(H, W, plan.patch);
     NatTable nat = make_nat(plan);
     MfmaTensor t[2] = {};
@@ -364,7 +359,7 @@ hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *
 hipError_t launch_unproject_mfma(const float *in, int slices, void *out, int N, int H, int W, int C,
                                  const BasisPlan &plan, hipStream_t stream)
 {
-    const long Q = (long)N * (H / plan.patch) * (W / plan.patch);
+    const long Q = patch_count(N, H, W, plan.patch);
     GridGeom g = make_geom(H, W, plan.patch);
     NatTable nat = make_nat(plan);
     const int chunks = (C + CB - 1) / CB;

@@ -42,7 +42,7 @@ class Workload:
 
     @property
     def patches(self):
-        return self.tokens // (self.patch * self.patch)
+        return self.N * (-(-self.H // self.patch)) * (-(-self.W // self.patch))
 
 
 # The five configurations the benchmark contract names.  cfg4 is a pair of layers.
@@ -57,6 +57,9 @@ WORKLOADS = {
                               "bf16", 1014),
     "cfg5_vitb_attnproj": Workload("cfg5_vitb_attnproj", 128, 32, 32, 768, 768, 8, (4, 8, 16, 64),
                                    ("l1", "linf"), "bf16", 1005),
+    # Beyond the five: the 49-token maps of Section 3.3's worked example, (Cx, Cy, L) = (3072, 768, 49);
+    # a 7 x 7 grid inside one zero-padded 8 x 8 patch.
+    "pad_7x7_fc2": Workload("pad_7x7_fc2", 128, 7, 7, 3072, 768, 8, (8, 36), ("l1",), "bf16", 1006),
 }
 
 

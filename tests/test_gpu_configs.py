@@ -71,6 +71,18 @@ def test_cfg3_thin_channels_whole_oracle():
     assert egx <= TOL["bf16"] and egw <= TOL["bf16"], (egx, egw)
 
 
+@pytest.mark.parametrize("r", [8, 36])
+def test_49_token_maps_whole_oracle(r):
+    # 7 x 7 grids inside one zero-padded 8 x 8 patch each, at the channel counts of Section 3.3's example
+    wl = workloads.WORKLOADS["pad_7x7_fc2"]
+    host, dev = device_inputs(wl)
+    idx = oracle.select_bases(wl.patch, r, "l1")
+    gx, gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], wl.patch, idx)
+    gx0, gW0 = oracle.lbp_wht_backward_padded(host["x"], host["gy"], host["w"], wl.patch, idx)
+    egx, egw = rel_fro(to_host(gx), gx0), rel_fro(to_host(gW), gW0)
+    assert egx <= TOL["bf16"] and egw <= TOL["bf16"], (egx, egw)
+
+
 @pytest.mark.parametrize("layer", ["cfg4_vitl_fc1", "cfg4_vitl_fc2"])
 def test_cfg4_vitl_rank_sweep(layer):
     wl = workloads.WORKLOADS[layer]

@@ -155,6 +155,87 @@ def test_backward_matches_oracle_on_ragged_shapes(dtype, case, variant):
     assert egx <= TOL[dtype] and egw <= TOL[dtype], (egx, egw)
 
 
+# Grids that are not multiples of the patch: zero-padded at the bottom and right (the 49-token maps
+# of Section 3.3).  N, H, W, Cin, Cout, patch, basis list
+PADDED = [
+    (3, 7, 7, 72, 200, 8, lambda: oracle.select_bases(8, 8, "l1")),
+    (2, 7, 7, 64, 136, 8, lambda: oracle.select_bases(8, 36, "l1")),       # the paper's largest rank
+    (2, 7, 7, 40, 24, 8, lambda: oracle.select_bases(8, 64, "l1")),        # all bases: exact on real tokens
+    (2, 10, 13, 48, 72, 4, lambda: oracle.select_bases(4, 4, "l1")),
+    (2, 10, 13, 48, 72, 8, lambda: np.array([63, 5, 17, 40, 9])),
+    (1, 3, 5, 16, 8, 2, lambda: np.array([0, 3])),
+    (2, 17, 30, 24, 40, 16, lambda: oracle.select_bases(16, 10, "l1")),
+    (4, 14, 14, 136, 264, 8, lambda: oracle.select_bases(8, 16, "linf")),  # 2 x 2 patches, 6 rows of padding
+    (2, 8, 12, 40, 24, 8, lambda: oracle.select_bases(8, 4, "l1")),        # only W is ragged
+]
+
+
+@pytest.mark.parametrize("path", ["auto", "generic", "register"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", range(len(PADDED)))
+def test_projections_on_zero_padded_grids(dtype, case, path):
+    N, H, W, Cin, Cout, patch, mk = PADDED[case]
+    idx = np.asarray(mk())
+    os.environ["LBP_WHT_PATH"] = path       # "register" cannot serve these grids and must not be taken
+    wl = small("padded", N, H, W, Cin, Cout, patch, dtype, 300 + case)
+    host, dev = device_inputs(wl)
+    for name in ("x", "gy"):
+        got = to_host(binding.wht_project(dev[name], patch, idx))
+        want = oracle.project_padded(host[name], patch, idx)
+        assert got.shape == want.shape
+        assert rel_fro(got, want) <= (1e-6 if dtype == "f32" else 4e-3), name
+    xr, gyr = binding.wht_project_pair(dev["x"], dev["gy"], patch, idx)
+    assert rel_fro(to_host(xr), oracle.project_padded(host["x"], patch, idx)) <= (1e-6 if dtype == "f32" else 4e-3)
+    assert rel_fro(to_host(gyr), oracle.project_padded(host["gy"], patch, idx)) <= (1e-6 if dtype == "f32" else 4e-3)
+    rng = np.random.default_rng(400 + case)
+    coef = rng.standard_normal((wl.patches * len(idx), Cin)).astype(np.float32)
+    tdtype = torch.float32 if dtype == "f32" else torch.bfloat16
+    # the output starts as NaN: every real token must be written
+    out = torch.full((N, H, W, Cin), float("nan"), dtype=tdtype, device="cuda")
+    binding.wht_unproject(torch.from_numpy(coef).cuda(), (N, H, W, Cin), tdtype, patch, idx, out=out)
+    want = oracle.unproject_padded(coef, (N, H, W, Cin), patch, idx)
+    assert rel_fro(to_host(out), want) <= (1e-6 if dtype == "f32" else 6e-3)
+
+
+@pytest.mark.parametrize("gemm", ["auto", "simple"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", range(len(PADDED)))
+def test_backward_on_zero_padded_grids(dtype, case, gemm):
+    if dtype == "f32" and gemm != "auto":
+        pytest.skip("the fp32 path has one implementation")
+    os.environ["LBP_GEMM_PATH"] = gemm
+    os.environ["LBP_FUSE_UNPROJECT"] = "1"      # asked for, but not available on these grids
+    N, H, W, Cin, Cout, patch, mk = PADDED[case]
+    idx = np.asarray(mk())
+    wl = small("padded", N, H, W, Cin, Cout, patch, dtype, 500 + case)
+    host, dev = device_inputs(wl)
+    # guard rows behind gx: nothing may be written past the last real token
+    gx_buf = torch.full((N * H * W + 64, Cin), 7.0, dtype=dev["x"].dtype, device="cuda")
+    gx = gx_buf[:N * H * W].view(N, H, W, Cin)
+    _, gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx, gx=gx)
+    gx0, gW0 = oracle.lbp_wht_backward_padded(host["x"], host["gy"], host["w"], patch, idx)
+    egx, egw = rel_fro(to_host(gx), gx0), rel_fro(to_host(gW), gW0)
+    assert egx <= TOL[dtype] and egw <= TOL[dtype], (egx, egw)
+    assert bool((gx_buf[N * H * W:] == 7.0).all())
+    if len(idx) == patch * patch:
+        fx, fW = oracle.full_bp_backward(host["x"], host["gy"], host["w"])
+        assert rel_fro(to_host(gx), fx) <= TOL[dtype] and rel_fro(to_host(gW), fW) <= TOL[dtype]
+    # x projected ahead of time gives the same bits
+    x_r = binding.wht_project(dev["x"], patch, idx)
+    gx2, gW2 = binding.lbp_wht_backward_preprojected(x_r, dev["gy"], dev["w"], patch, idx)
+    assert torch.equal(gx2, gx) and torch.equal(gW2, gW)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_energy_spectrum_on_a_zero_padded_grid(dtype):
+    wl = small("padded-energy", 3, 7, 7, 48, 72, 8, dtype, 77)
+    host, dev = device_inputs(wl)
+    got = binding.wht_energy(dev["gy"], 8).cpu().numpy()
+    want = oracle.wht_energy_padded(host["gy"], 8)
+    tol = 1e-5 if dtype == "f32" else 5e-3          # bf16: coefficients are rounded before squaring
+    assert np.max(np.abs(got - want)) <= tol * want.max()
+
+
 @pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5])
 @pytest.mark.parametrize("case", [0, 3, 10, 13])
 def test_every_gemm_tile_shape_matches_oracle(case, tile):

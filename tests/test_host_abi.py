@@ -65,8 +65,7 @@ def test_backward_argument_errors_are_reported_before_any_device_work(lib):
     assert call_backward(lib, x=0) == -1
     assert call_backward(lib, gx=0, gw=0) == -1
     assert call_backward(lib, shape=S(0, 16, 16, 64, 128, 1, 0)) == -2
-    assert call_backward(lib, shape=S(2, 12, 16, 64, 128, 1, 0)) == -2           # H % patch
-    assert call_backward(lib, shape=S(2, 16, 20, 64, 128, 1, 0)) == -2           # W % patch
+    assert call_backward(lib, shape=S(2, -12, 16, 64, 128, 1, 0)) == -2
     assert call_backward(lib, shape=S(1 << 15, 1 << 8, 1 << 8, 8, 8, 1, 0)) == -2  # 2^31 tokens
     assert call_backward(lib, patch=3) == -3
     assert call_backward(lib, patch=32) == -3
@@ -95,7 +94,7 @@ def test_full_bp_and_projection_argument_errors(lib):
     assert lib.lbp_wht_project(None, 2, 16, 16, 64, 1, 8, idx, 2, P(GX), None) == -1
     assert lib.lbp_wht_project(P(X), 2, 16, 16, 64, 1, 8, idx, 2, P(X), None) == -7
     assert lib.lbp_wht_project(P(X), 2, 16, 16, 64, 1, 5, idx, 2, P(GX), None) == -3
-    assert lib.lbp_wht_project(P(X), 2, 16, 12, 64, 1, 8, idx, 2, P(GX), None) == -2
+    assert lib.lbp_wht_project(P(X), 2, 16, 0, 64, 1, 8, idx, 2, P(GX), None) == -2
     assert lib.lbp_wht_unproject(P(X), 2, 16, 16, 64, 9, 8, idx, 2, P(GX), None) == -6
     assert lib.lbp_wht_unproject(P(X), 2, 16, 16, 64, 1, 8, idx, 3, P(GX), None) in (-5, -4)
 
@@ -131,7 +130,7 @@ def test_lhe_selection_is_bit_exact_against_the_oracle(lib):
     assert lib.lbp_wht_select_lhe(arr, 8, 65, out) == -4
     assert lib.lbp_wht_select_lhe(None, 8, 4, out) == -1
     assert lib.lbp_wht_energy(None, 2, 16, 16, 64, 1, 8, P(GX), None) == -1
-    assert lib.lbp_wht_energy(P(X), 2, 12, 16, 64, 1, 8, P(GX), None) == -2
+    assert lib.lbp_wht_energy(P(X), 2, 0, 16, 64, 1, 8, P(GX), None) == -2
     assert lib.lbp_wht_energy_workspace_bytes(2, 16, 16, 64, 1, 8) >= 2 * 256 * 64 * 2
     assert lib.lbp_wht_energy_workspace_bytes(2, 16, 16, 64, 1, 5) == 0
 

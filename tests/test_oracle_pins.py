@@ -363,6 +363,63 @@ def test_grid_must_be_a_multiple_of_the_patch():
         oracle.lbp_wht_backward(x, gy, w, 4, [0])
 
 
+# ---------- grids that are not multiples of the patch: zero padding (Section 3.3's 49-token maps) ----------
+
+@pytest.mark.parametrize("H,W,p", [(7, 7, 8), (3, 5, 4), (10, 12, 8), (5, 2, 2)])
+def test_padded_grid_with_all_bases_kept_is_exact_backprop_on_the_real_tokens(H, W, p):
+    x, gy, w = rand_case(91, N=2, H=H, W=W, Cin=3, Cout=5)
+    gx, gW = oracle.lbp_wht_backward_padded(x, gy, w, p, np.arange(p * p))
+    X, G = x.reshape(-1, 3), gy.reshape(-1, 5)
+    np.testing.assert_allclose(gx.reshape(-1, 3), G @ w, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(gW, G.T @ X, rtol=0, atol=1e-12)
+
+
+def test_padding_changes_nothing_when_the_grid_already_fits():
+    x, gy, w = rand_case(92, N=2, H=8, W=4, Cin=3, Cout=2)
+    idx = oracle.select_bases(4, 6, "l1")
+    a = oracle.lbp_wht_backward(x, gy, w, 4, idx)
+    b = oracle.lbp_wht_backward_padded(x, gy, w, 4, idx)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    assert np.array_equal(oracle.project(x, 4, idx), oracle.project_padded(x, 4, idx))
+
+
+def test_one_basis_on_a_7x7_map_is_token_sum_matmul_broadcast_over_64():
+    # The whole 49-token map sits in one zero-padded 8 x 8 patch; with the constant basis alone the
+    # coefficients are plain sums over the 49 tokens and every token receives the same gradient,
+    # divided by the 64 points of the padded patch (not by 49).
+    x, gy, w = rand_case(93, N=3, H=7, W=7, Cin=4, Cout=6)
+    gx, gW = oracle.lbp_wht_backward_padded(x, gy, w, 8, [0])
+    sx, sg = x.sum(axis=(1, 2)), gy.sum(axis=(1, 2))          # [N, C]
+    np.testing.assert_allclose(gW, sg.T @ sx / 64.0, rtol=0, atol=1e-12)
+    want = np.broadcast_to(((sg @ w) / 64.0)[:, None, None, :], gx.shape)
+    np.testing.assert_allclose(gx, want, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("H,W,p,r,order", [(7, 7, 8, 10, "l1"), (6, 10, 4, 4, "linf"), (9, 3, 2, 3, "l1")])
+def test_padded_projection_is_a_masked_kronecker_product(H, W, p, r, order):
+    # Different algorithm: per patch, multiply the (zero-filled) patch by the Kronecker basis matrix.
+    x, _, _ = rand_case(94, N=2, H=H, W=W, Cin=3, Cout=1)
+    idx = oracle.select_bases(p, r, order)
+    B = basis_np(p, idx)                                       # [p*p, r]
+    Hp, Wp = -(-H // p) * p, -(-W // p) * p
+    big = np.zeros((2, Hp, Wp, 3))
+    big[:, :H, :W] = x
+    want = np.einsum("qtc,tk->qkc", to_patches(big, p), B).reshape(-1, 3)
+    np.testing.assert_allclose(oracle.project_padded(x, p, idx), want, rtol=0, atol=1e-12)
+    # reverse direction: crop of the padded synthesis
+    coef = np.random.default_rng(5).standard_normal(want.shape)
+    full = np.einsum("qkc,tk->qtc", coef.reshape(-1, r, 3), B) / (p * p)
+    full = full.reshape(2, Hp // p, Wp // p, p, p, 3).transpose(0, 1, 3, 2, 4, 5).reshape(2, Hp, Wp, 3)
+    np.testing.assert_allclose(oracle.unproject_padded(coef, (2, H, W, 3), p, idx), full[:, :H, :W],
+                               rtol=0, atol=1e-12)
+
+
+def test_padded_energy_is_the_energy_of_the_real_tokens_when_all_bases_are_counted():
+    x, _, _ = rand_case(95, N=2, H=7, W=5, Cin=3, Cout=1)
+    e = oracle.wht_energy_padded(x, 8)
+    np.testing.assert_allclose(e.sum(), 64.0 * np.sum(x * x), rtol=1e-12)
+
+
 # ---------- energy spectrum and low-heuristic-error selection (Section 3.2, Section 4.4) ----------
 
 def test_energy_obeys_parseval_and_finds_a_planted_basis():
