@@ -197,7 +197,7 @@ def main():
         best = 1e30
         for _ in range(2):
             t0 = time.perf_counter()
-            oracle.lbp_wht_backward(sample["x"], sample["gy"], sample["w"], wl.patch, np.asarray(idx))
+            oracle.lbp_wht_backward_padded(sample["x"], sample["gy"], sample["w"], wl.patch, np.asarray(idx))
             best = min(best, time.perf_counter() - t0)
         cpu = {"value": round(lbp_flops(wl_s, r) / best / 1e12, 6), "unit": "TFLOP/s",
                "cores": oracle.max_threads(), "kind": "oracle",
