@@ -101,7 +101,7 @@ int lbp_wht_select_bases(int patch, int r, int order, int32_t *basis_idx);
 int lbp_wht_select_lhe(const double *energy, int patch, int r, int32_t *basis_idx);
 
 /*
- * Profiling step of the LHE selection (Section 3.2; the spectrum shown in Section 4.4): adds to
+ * Profiling step of the LHE selection (Section 3.2; the spectrum shown in Section 4.5): adds to
  * energy[u*patch + v] (DEVICE, patch^2 doubles, caller zeroes it before the first call) the sum over
  * all patches and channels of the squared unnormalised WHT coefficient (Eq. 6) of basis (u, v) of
  * `in` [N][H][W][C].  Call it on gy for a few training steps, copy `energy` back, then call

@@ -434,7 +434,7 @@ int oracle_full_gw_entries(const double *x, const double *gy, long M, int Cin, i
     return 0;
 }
 
-/* Energy of every basis (Section 3.2, low-heuristic-error selection; the spectrum of Section 4.4):
+/* Energy of every basis (Section 3.2, low-heuristic-error selection; the spectrum of Section 4.5):
  * E[u*p + v] = sum over patches and channels of (coefficient of basis (u,v))^2, unnormalised
  * coefficients of Eq. 6.  By Parseval sum_j E[j] = p^2 * ||X||^2. */
 int oracle_wht_energy(const double *X, int N, int H, int W, int C, int p, double *E)

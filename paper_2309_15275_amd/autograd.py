@@ -1,0 +1,74 @@
+"""A linear layer whose backward pass is LBP-WHT (Algorithm 1), for use inside torch.autograd.
+
+Forward: y = x w^T (+ b) is an ordinary dense product and is left to torch (the method does not
+touch it); alongside it the layer's own projection kernel computes x^ = WHT(x; I), and ONLY x^ is
+kept for the backward pass (Algorithm 1's second statement depends on x and I alone), so the saved
+activation is r/patch^2 of x.  Backward: the library's lbp_wht_backward_preprojected produces
+g~x and g~w from x^, g_y and w; there is no fallback if the library is missing.  The bias gradient
+is the exact column sum of g_y (the paper's layer has no bias, Section 2).
+
+Tensors are token-major: x [N, H, W, Cin] (or [N, H*W, Cin] with `grid=(H, W)`), float32 or bfloat16.
+"""
+import torch
+
+from . import binding
+
+
+class _LbpWhtLinearFn(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, weight, bias, patch, basis_idx):
+        if x.dim() != 4:
+            raise ValueError("x must be [N, H, W, Cin]")
+        xc = x.detach().contiguous()
+        y = torch.nn.functional.linear(xc, weight, bias)
+        ctx.save_for_backward(binding.wht_project(xc, patch, basis_idx), weight)
+        ctx.lbp = (int(patch), tuple(int(v) for v in basis_idx), bias is not None)
+        return y
+
+    @staticmethod
+    def backward(ctx, gy):
+        x_r, weight = ctx.saved_tensors
+        patch, basis_idx, has_bias = ctx.lbp
+        gy = gy.contiguous()
+        want_gx, want_gw = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
+        gx = gW = None
+        if want_gx or want_gw:
+            gx, gW = binding.lbp_wht_backward_preprojected(
+                x_r, gy, weight.detach(), patch, basis_idx, want_gx=want_gx, want_gw=want_gw,
+                gw_dtype=weight.dtype)
+        gb = gy.sum(dim=(0, 1, 2)) if has_bias and ctx.needs_input_grad[2] else None
+        return gx, gW, gb, None, None
+
+
+def lbp_wht_linear(x, weight, bias, patch, basis_idx):
+    """Functional form: y = x w^T + b with the LBP-WHT backward."""
+    return _LbpWhtLinearFn.apply(x, weight, bias, patch, basis_idx)
+
+
+class LBPWHTLinear(torch.nn.Module):
+    """torch.nn.Linear with the LBP-WHT backward.  `order` / `rank` choose a low-pass selection
+    (Eq. 8 / Eq. 9); `set_bases` installs any other list, e.g. one from select_lhe."""
+
+    def __init__(self, in_features, out_features, bias=True, patch=8, rank=8, order="l1", device=None,
+                 dtype=None):
+        super().__init__()
+        self.in_features, self.out_features, self.patch = in_features, out_features, patch
+        self.weight = torch.nn.Parameter(torch.empty(out_features, in_features, device=device, dtype=dtype))
+        self.bias = torch.nn.Parameter(torch.zeros(out_features, device=device, dtype=dtype)) if bias else None
+        torch.nn.init.normal_(self.weight, std=0.02)
+        self.basis_idx = tuple(binding.select_bases(patch, rank, order))
+
+    def set_bases(self, basis_idx):
+        self.basis_idx = tuple(int(v) for v in basis_idx)
+
+    def forward(self, x, grid=None):
+        if x.dim() == 3:
+            if grid is None:
+                raise ValueError("a [N, L, C] input needs grid=(H, W)")
+            N, L, C = x.shape
+            if grid[0] * grid[1] != L:
+                raise ValueError("grid does not match the token count")
+            y = lbp_wht_linear(x.reshape(N, grid[0], grid[1], C), self.weight, self.bias, self.patch,
+                               self.basis_idx)
+            return y.reshape(N, L, self.out_features)
+        return lbp_wht_linear(x, self.weight, self.bias, self.patch, self.basis_idx)

@@ -1,5 +1,5 @@
 // Energy of every WHT basis of a tensor (Section 3.2, low-heuristic-error selection; the spectrum
-// of Section 4.4): E[j] = sum over patches and channels of (coefficient j)^2.
+// of Section 4.5): E[j] = sum over patches and channels of (coefficient j)^2.
 //
 // The coefficients of ALL p^2 bases are first produced by the projection kernels (row q*p^2 + j of
 // the coefficient matrix is basis j of patch q); the kernels here square and add them up.  Sums

@@ -1,6 +1,6 @@
 """Seeded synthetic workloads: shapes of ViT linear layers, values with the spectral
 structure the paper reports for the output gradient (energy concentrated in the
-low-sequency corner, Section 4.4 / Figure 5).
+low-sequency corner, Section 4.5 / Figure 5).
 
 This module only draws random numbers and shapes them.  It holds none of the method's
 arithmetic (no Hadamard matrix, no projection, no matmul) so that the CPU oracle and the

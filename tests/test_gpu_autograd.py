@@ -1,0 +1,102 @@
+"""The autograd wrapper and a chained pair of layers (fc1 -> GELU -> fc2, the MLP of a transformer
+block): gradients through torch.autograd with both layers on the LBP-WHT backward, against the
+same chain written out with the CPU oracle in double precision."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from _gpu_util import TOL, rel_fro, to_device, to_host
+from paper_2309_15275_amd import workloads
+from paper_2309_15275_amd.autograd import LBPWHTLinear, lbp_wht_linear
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    yield
+    torch.cuda.synchronize()
+
+
+def gelu_np(a):
+    from scipy.special import erf
+    return 0.5 * a * (1.0 + erf(a / np.sqrt(2.0)))
+
+
+def gelu_grad_np(a):
+    from scipy.special import erf
+    return 0.5 * (1.0 + erf(a / np.sqrt(2.0))) + a * np.exp(-0.5 * a * a) / np.sqrt(2.0 * np.pi)
+
+
+def mlp_case(dtype, seed, N=2, H=16, W=16, C=64, Hid=256):
+    wl1 = workloads.Workload("mlp_fc1", N, H, W, C, Hid, 8, (), ("l1",), dtype, seed)
+    wl2 = workloads.Workload("mlp_fc2", N, H, W, Hid, C, 8, (), ("l1",), dtype, seed + 1)
+    a, b = workloads.make_inputs(wl1), workloads.make_inputs(wl2)
+    return a["x"], a["w"] * 4.0, b["w"] * 4.0, b["gy"]      # x, W1, W2, gradient of the loss w.r.t. the MLP's output
+
+
+def oracle_chain(x, w1, w2, gy2, patch, idx, round_bf16):
+    """fc1 -> GELU -> fc2 backward with Algorithm 1 in both layers, fp64.  Where the GPU chain stores
+    a tensor in bf16 (activations and the gradient handed from fc2 to fc1) the same rounding is applied."""
+    rnd = (lambda t: workloads.round_to_bf16(t.astype(np.float32)).astype(np.float64)) if round_bf16 else (lambda t: t)
+    x64, w164, w264 = x.astype(np.float64), w1.astype(np.float64), w2.astype(np.float64)
+    a = rnd(x64 @ w164.T)
+    h = rnd(gelu_np(a))
+    gh, gW2 = oracle.lbp_wht_backward(h, gy2, w264, patch, idx)
+    ga = rnd(rnd(gh) * gelu_grad_np(a))
+    gx, gW1 = oracle.lbp_wht_backward(x64, ga, w164, patch, idx)
+    return gx, gW1, gW2
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mlp_pair_gradients_match_the_oracle_chain(dtype):
+    patch, idx = 8, oracle.select_bases(8, 8, "l1")
+    x, w1, w2, gy2 = mlp_case(dtype, 4100)
+    if dtype == "bf16":
+        w1, w2 = workloads.round_to_bf16(w1), workloads.round_to_bf16(w2)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    fc1 = LBPWHTLinear(x.shape[-1], w1.shape[0], bias=False, patch=patch, rank=8, device="cuda", dtype=tdt)
+    fc2 = LBPWHTLinear(w1.shape[0], w2.shape[0], bias=False, patch=patch, rank=8, device="cuda", dtype=tdt)
+    with torch.no_grad():
+        fc1.weight.copy_(to_device(w1, dtype))
+        fc2.weight.copy_(to_device(w2, dtype))
+    xd = to_device(x, dtype).requires_grad_(True)
+    y = fc2(torch.nn.functional.gelu(fc1(xd)))
+    y.backward(to_device(gy2, dtype))
+    gx0, gW10, gW20 = oracle_chain(x, w1, w2, gy2, patch, idx, dtype == "bf16")
+    tol = TOL[dtype] if dtype == "bf16" else 1e-4       # fp32: two layers and an erf in between
+    assert rel_fro(to_host(fc2.weight.grad), gW20) <= tol
+    assert rel_fro(to_host(xd.grad), gx0) <= tol
+    assert rel_fro(to_host(fc1.weight.grad), gW10) <= tol
+
+
+def test_all_bases_give_the_gradients_of_plain_autograd():
+    # r = patch^2: the layer's backward is exact, so autograd through it equals autograd through F.linear
+    torch.manual_seed(0)
+    x = torch.randn(2, 8, 8, 32, device="cuda", requires_grad=True)
+    w = (0.1 * torch.randn(48, 32, device="cuda")).requires_grad_(True)
+    b = torch.randn(48, device="cuda", requires_grad=True)
+    g = torch.randn(2, 8, 8, 48, device="cuda")
+    lbp_wht_linear(x, w, b, 4, list(range(16))).backward(g)
+    got = [t.grad.clone() for t in (x, w, b)]
+    for t in (x, w, b):
+        t.grad = None
+    torch.nn.functional.linear(x, w, b).backward(g)
+    for a, t in zip(got, (x, w, b)):
+        assert rel_fro(to_host(a), to_host(t.grad)) <= 1e-5
+
+
+def test_only_the_projected_activation_is_saved():
+    fc = LBPWHTLinear(64, 128, bias=True, patch=8, rank=8, device="cuda", dtype=torch.bfloat16)
+    x = torch.randn(2, 16, 16, 64, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+    y = fc(x)
+    saved = [t for t in y.grad_fn.saved_tensors]
+    assert sorted(tuple(t.shape) for t in saved) == sorted([(2 * 4 * 8, 64), (128, 64)])      # x^ and w: no x
+    # [N, L, C] inputs with a grid
+    y2 = fc(x.detach().reshape(2, 256, 64), grid=(16, 16))
+    assert torch.equal(y2.reshape(y.shape), y)
+    with pytest.raises(ValueError):
+        fc(x.detach().reshape(2, 256, 64))

@@ -420,7 +420,7 @@ def test_padded_energy_is_the_energy_of_the_real_tokens_when_all_bases_are_count
     np.testing.assert_allclose(e.sum(), 64.0 * np.sum(x * x), rtol=1e-12)
 
 
-# ---------- energy spectrum and low-heuristic-error selection (Section 3.2, Section 4.4) ----------
+# ---------- energy spectrum and low-heuristic-error selection (Section 3.2, Section 4.5) ----------
 
 def test_energy_obeys_parseval_and_finds_a_planted_basis():
     p = 8
@@ -463,7 +463,7 @@ def test_lhe_selection_takes_the_largest_energies_and_breaks_ties_low_pass():
 
 
 def test_smooth_gradients_put_their_energy_in_the_low_sequency_corner():
-    # the structure the paper reports for g_y (Section 4.4): with the synthetic smooth field the
+    # the structure the paper reports for g_y (Section 4.5): with the synthetic smooth field the
     # ten strongest bases are all inside the LP_L1-5 triangle and hold most of the energy
     from paper_2309_15275_amd import workloads
     wl = workloads.scaled(workloads.WORKLOADS["cfg2_vitb_fc1"], N=2, Cin=16, Cout=32)
@@ -494,3 +494,25 @@ def test_cost_model_reproduces_the_printed_example():
     assert abs(100 * overhead / lbp - g["overhead_over_lbp_percent"]) < 0.05
     # speedup of the matmuls alone is L / r
     assert abs(f["vanilla_bp"] / f["low_rank_mm"] - g["L"] / g["r"]) < 1e-12
+
+
+# ---------- a chain of two approximated layers (Section 4.6: errors accumulate with depth) ----------
+
+def test_error_of_the_weight_gradient_grows_along_a_chain_of_approximated_layers():
+    # fc1 -> fc2 (no nonlinearity needed for the point): fc2's weight gradient sees one projection,
+    # fc1's sees the projection of an already approximated gradient.
+    from paper_2309_15275_amd import workloads
+    wl = workloads.scaled(workloads.WORKLOADS["cfg2_vitb_fc1"], N=2, Cin=24, Cout=40)
+    d = workloads.make_inputs(wl)
+    rng = np.random.default_rng(9)
+    x0 = rng.standard_normal((2, 16, 16, 16))
+    w1 = rng.standard_normal((24, 16)) / 4.0
+    h = x0 @ w1.T
+    w2, gy = d["w"].astype(np.float64) * 10.0, d["gy"].astype(np.float64)
+    idx = oracle.select_bases(8, 8, "l1")
+    gh_exact, gW2_exact = oracle.full_bp_backward(h, gy, w2)
+    _, gW1_exact = oracle.full_bp_backward(x0, gh_exact, w1)
+    gh, gW2 = oracle.lbp_wht_backward(h, gy, w2, 8, idx)
+    _, gW1 = oracle.lbp_wht_backward(x0, gh, w1, 8, idx)
+    e2, e1 = relerr(gW2, gW2_exact), relerr(gW1, gW1_exact)
+    assert 0 < e2 < 1 and e1 >= e2 * 0.999
