@@ -171,7 +171,7 @@ def main():
     # fraction of each.
     proj_bytes = esz * (wl.tokens + Mr) * (wl.Cout + wl.Cin)
     proj_gbs = proj_bytes / (ms_proj * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "wht_project_reg_kernel (gy and x, one launch)",
+    roofline = {"bound": "hbm", "kernel": "projection of gy and x (one launch)",
                 "achieved": round(proj_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(proj_gbs / HBM_PEAK_GBS, 4),
                 "traffic": read_traffic(f"wht_project_{wl.name}_hbm_traffic.txt"),
