@@ -84,9 +84,8 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
         p.bm_step = t.bm / bp.r * bp.r;
         p.sel.mask = bp.pooled_mask;
         for (int j = 0; j < 64; ++j) p.sel.pos[j] = bp.pooled_pos[j];
-        if (grid_is_ragged(a.grid_h, a.grid_w, bp.patch)) return hipErrorInvalidValue;   // epilogue writes whole patches
         p.geom = make_geom(a.grid_h, a.grid_w, bp.patch);
-        p.Q = a.M / bp.r;
+        p.Q = a.M / bp.r;     // = patches of the zero-padded grids
     }
     p.tiles_m = (a.M + p.bm_step - 1) / p.bm_step;
     return kLaunch[tile](p, a.a_kfast, a.out, lp, a.splits, stream);

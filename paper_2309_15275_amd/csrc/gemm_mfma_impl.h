@@ -84,13 +84,18 @@ __device__ __forceinline__ void unproject_tile(const float *ct, int cts, const P
         }
         fwht_inplace<NC>(c0);
         fwht_inplace<NC>(c1);
-        uint32_t *dst = reinterpret_cast<uint32_t *>(p.C) + (size_t)p.geom.first_token(q) * Cd + (n0 >> 1) + cp;
+        long img;
+        int a0, b0;
+        p.geom.origin(q, img, a0, b0);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(p.C) + ((size_t)img * p.geom.HWt + (size_t)a0 * p.geom.Wt + b0) * Cd + (n0 >> 1) + cp;
+        const int hv = p.geom.Ht - a0, wv = p.geom.Wt - b0;     // tokens of the patch inside the grid (>= P: all)
 #pragma unroll
         for (int h = 0; h < P; ++h) {
 #pragma unroll
             for (int w = 0; w < P; ++w) {
                 int j = (h >> MH) * PWd + (w >> MW);
-                __builtin_nontemporal_store(pack_bf16x2(c0[j] * scale, c1[j] * scale), dst + ((size_t)h * p.geom.Wt + w) * Cd);
+                if (h < hv && w < wv)
+                    __builtin_nontemporal_store(pack_bf16x2(c0[j] * scale, c1[j] * scale), dst + ((size_t)h * p.geom.Wt + w) * Cd);
             }
         }
     }

@@ -397,8 +397,7 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     if (rc) return rc;
     const lbp::GemmPath gpath = gemm_path_from_env();
     const int fuse_env = fuse_unproject_from_env();
-    const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath) &&
-                          !lbp::grid_is_ragged(shape->H, shape->W, patch);
+    const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
     lbp::WorkspacePlan ws;
     rc = lbp::plan_workspace(shape, patch, r, st->num_cus, can_fuse, fuse_env == 1, &ws);
     if (rc) return rc;
@@ -410,7 +409,6 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     const lbp::WhtPath path = wht_path_from_env();
     const int N = shape->N, H = shape->H, Wd = shape->W, Cin = shape->Cin, Cout = shape->Cout;
     const int dt = shape->dtype;
-    const long M = (long)N * H * Wd;
     const long Mr = lbp::patch_count(N, H, Wd, patch) * r;
     const float inv_pp = 1.0f / (float)(patch * patch);
     void *gy_r = base + ws.gy_r;

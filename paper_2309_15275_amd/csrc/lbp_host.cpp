@@ -244,7 +244,7 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
     unfused.est_us += 8.0 + ((double)unfused.splits * Mr * s->Cin * 4 + (double)M * s->Cin * esz) / 4.0e6;
     ws->gx = unfused;
     ws->gx_fused = false;
-    if (can_fuse && s->dtype == LBP_BF16 && !grid_is_ragged(s->H, s->W, patch)) {
+    if (can_fuse && s->dtype == LBP_BF16) {
         GemmPlan fused = plan_gemm(Mr, s->Cin, s->Cout, 2, false, r, patch, num_cus);
         if (force_fuse || fused.est_us <= unfused.est_us) {
             ws->gx = fused;

@@ -33,14 +33,6 @@ struct GridGeom {
         a0 = a * patch;
         b0 = (rem - a * PW) * patch;
     }
-    // flat index of the patch's first token (only for grids that are multiples of the patch)
-    __device__ __forceinline__ long first_token(long q) const
-    {
-        long n;
-        int a0, b0;
-        origin(q, n, a0, b0);
-        return n * HWt + (long)a0 * Wt + b0;
-    }
 };
 
 inline GridGeom make_geom(int H, int W, int patch)

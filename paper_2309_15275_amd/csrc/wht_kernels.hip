@@ -48,14 +48,31 @@ __global__ __launch_bounds__(256) void wht_project_reg_kernel(ProjTensor t0, Pro
     if (item >= t.items) return;
     long q = item / Cd;
     int cd = (int)(item - q * Cd);
-    const uint32_t *src = t.in + (size_t)g.first_token(q) * Cd + cd;
+    long n;
+    int a0, b0;
+    g.origin(q, n, a0, b0);
+    const uint32_t *src = t.in + ((size_t)n * g.HWt + (size_t)a0 * g.Wt + b0) * Cd + cd;
 
     uint32_t raw[P * P];
+    if (a0 + P <= g.Ht && b0 + P <= g.Wt) {
 #pragma unroll
-    for (int h = 0; h < P; ++h) {
+        for (int h = 0; h < P; ++h) {
 #pragma unroll
-        for (int w = 0; w < P; ++w)
-            raw[h * P + w] = __builtin_nontemporal_load(src + ((size_t)h * g.Wt + w) * Cd);   // read once
+            for (int w = 0; w < P; ++w)
+                raw[h * P + w] = __builtin_nontemporal_load(src + ((size_t)h * g.Wt + w) * Cd);   // read once
+        }
+    } else {
+        // a patch that hangs over the bottom or right edge of the grid: the missing tokens are zeros
+        const int hv = g.Ht - a0, wv = g.Wt - b0;
+#pragma unroll
+        for (int h = 0; h < P; ++h) {
+#pragma unroll
+            for (int w = 0; w < P; ++w) {
+                uint32_t v = 0u;
+                if (h < hv && w < wv) v = __builtin_nontemporal_load(src + ((size_t)h * g.Wt + w) * Cd);
+                raw[h * P + w] = v;
+            }
+        }
     }
 
     uint32_t *dst = t.out + (size_t)q * r * Cd + cd;
@@ -100,7 +117,11 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
     if (item >= items) return;
     long q = item / Cd;
     int cd = (int)(item - q * Cd);
-    uint32_t *dst = out + (size_t)g.first_token(q) * Cd + cd;
+    long n;
+    int a0, b0;
+    g.origin(q, n, a0, b0);
+    uint32_t *dst = out + ((size_t)n * g.HWt + (size_t)a0 * g.Wt + b0) * Cd + cd;
+    const int hv = g.Ht - a0, wv = g.Wt - b0;      // tokens of the patch that exist (>= P: all of them)
 
     if (BF16) {
         const int C = Cd * 2;
@@ -128,7 +149,8 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
 #pragma unroll
             for (int w = 0; w < P; ++w) {
                 int j = (h >> MH) * PWd + (w >> MW);
-                __builtin_nontemporal_store(pack_bf16x2(c0[j] * scale, c1[j] * scale), dst + ((size_t)h * g.Wt + w) * Cd);
+                if (h < hv && w < wv)
+                    __builtin_nontemporal_store(pack_bf16x2(c0[j] * scale, c1[j] * scale), dst + ((size_t)h * g.Wt + w) * Cd);
             }
         }
     } else {
@@ -148,7 +170,8 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
 #pragma unroll
             for (int w = 0; w < P; ++w) {
                 int j = (h >> MH) * PWd + (w >> MW);
-                __builtin_nontemporal_store(__float_as_uint(c0[j] * scale), dst + ((size_t)h * g.Wt + w) * Cd);
+                if (h < hv && w < wv)
+                    __builtin_nontemporal_store(__float_as_uint(c0[j] * scale), dst + ((size_t)h * g.Wt + w) * Cd);
             }
         }
     }
@@ -419,21 +442,18 @@ hipError_t launch_generic(const void *in, void *out, int N, int H, int W, int C,
     return hipGetLastError();
 }
 
-// The register kernels assume whole patches.
-bool use_register_path(const BasisPlan &plan, WhtPath path, int H, int W)
+bool use_register_path(const BasisPlan &plan, WhtPath path)
 {
-    if (plan.patch > 8 || grid_is_ragged(H, W, plan.patch)) return false;
+    if (plan.patch > 8) return false;
     return path != WhtPath::kGeneric;
 }
 
 // The matrix-core form takes over where the pooled butterfly cannot prune (more than 16 pooled
 // coefficients per channel) and for patch 16.
-bool use_mfma_path(const BasisPlan &plan, WhtPath path, int dtype, int C, int H, int W)
+bool use_mfma_path(const BasisPlan &plan, WhtPath path, int dtype, int C)
 {
     if (!wht_mfma_supported(plan, dtype, C)) return false;
     if (path == WhtPath::kMfma) return true;
-    if (path == WhtPath::kGeneric) return false;
-    if (grid_is_ragged(H, W, plan.patch)) return true;      // also when the register path was asked for
     if (path != WhtPath::kAuto) return false;
     if (plan.patch > 8) return true;
     return (plan.patch >> plan.mh) * (plan.patch >> plan.mw) > 16;
@@ -444,9 +464,9 @@ bool use_mfma_path(const BasisPlan &plan, WhtPath path, int dtype, int C, int H,
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
                           const BasisPlan &plan, WhtPath path, hipStream_t stream)
 {
-    if (use_mfma_path(plan, path, dtype, C, H, W))
+    if (use_mfma_path(plan, path, dtype, C))
         return launch_project_mfma(in, out, C, nullptr, nullptr, 0, N, H, W, plan, stream);
-    if (use_register_path(plan, path, H, W))
+    if (use_register_path(plan, path))
         return launch_reg<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
     return launch_generic<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
 }
@@ -455,9 +475,9 @@ hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *
                                int N, int H, int W, int dtype, const BasisPlan &plan, WhtPath path,
                                hipStream_t stream)
 {
-    if (use_mfma_path(plan, path, dtype, C0, H, W) && use_mfma_path(plan, path, dtype, C1, H, W))
+    if (use_mfma_path(plan, path, dtype, C0) && use_mfma_path(plan, path, dtype, C1))
         return launch_project_mfma(in0, out0, C0, in1, out1, C1, N, H, W, plan, stream);
-    if (use_register_path(plan, path, H, W))
+    if (use_register_path(plan, path))
         return launch_reg<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream, in1, out1, C1);
     hipError_t e = launch_generic<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream);
     if (e != hipSuccess) return e;
@@ -468,12 +488,12 @@ hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H
                             int dtype, const BasisPlan &plan, WhtPath path, hipStream_t stream)
 {
     if (slices < 1) return hipErrorInvalidValue;
-    if (use_mfma_path(plan, path, dtype, C, H, W))
+    if (use_mfma_path(plan, path, dtype, C))
         return launch_unproject_mfma(in, slices, out, N, H, W, C, plan, stream);
     Slices sl;
     sl.count = slices;
     sl.stride = (size_t)patch_count(N, H, W, plan.patch) * plan.r * C;
-    if (use_register_path(plan, path, H, W))
+    if (use_register_path(plan, path))
         return launch_reg<true>(in, out, N, H, W, C, dtype, plan, sl, stream);
     return launch_generic<true>(in, out, N, H, W, C, dtype, plan, sl, stream);
 }
