@@ -51,7 +51,8 @@ bool gemm_can_fuse_unproject(const BasisPlan &plan, int dtype, GemmPath path)
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
 {
     if (a.dtype != LBP_BF16) return hipErrorInvalidValue;
-    if (a.M < 8 || a.N < 8 || a.K < 1) return hipErrorInvalidValue;
+    // rows of a k-fast A are clamped one by one (any M); a k-slow A and B are read in 8-element pieces
+    if (a.M < (a.a_kfast ? 1 : 8) || a.N < 8 || a.K < 1) return hipErrorInvalidValue;
     if (a.N % 8 || a.ldb % 8 || a.lda % 8 || (a.a_kfast ? a.K % 8 : a.M % 8)) return hipErrorInvalidValue;
     if (a.out != GemmOut::kF32 && a.splits != 1) return hipErrorInvalidValue;
     int tile = tile_from_env();     // testing: force one tile shape for every product

@@ -1,0 +1,55 @@
+"""Seeded random shapes through the whole backward call: grids that are and are not multiples of
+the patch, channel counts with ragged tiles, low-pass and arbitrary basis lists, both dtypes,
+default kernel choices.  Every case is compared element by element with the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from _gpu_util import TOL, device_inputs, rel_fro, to_host
+from paper_2309_15275_amd import binding
+from paper_2309_15275_amd.workloads import Workload
+
+pytestmark = pytest.mark.gpu
+
+N_CASES = 48
+
+
+def draw_case(i):
+    rng = np.random.default_rng(7000 + i)
+    dtype = "bf16" if i % 3 else "f32"
+    patch = int(rng.choice([2, 4, 8, 8, 8, 16]))
+    vec = 8 if dtype == "bf16" else 4
+    N = int(rng.integers(1, 5))
+    if rng.random() < 0.5:
+        H, W = int(rng.integers(1, 4)) * patch, int(rng.integers(1, 4)) * patch
+    else:
+        H, W = int(rng.integers(1, 3 * patch + 1)), int(rng.integers(1, 3 * patch + 1))
+    Cin, Cout = int(rng.integers(1, 40)) * vec, int(rng.integers(1, 40)) * vec
+    pp = patch * patch
+    kind = int(rng.integers(0, 3))
+    if kind == 0:
+        r = int(rng.integers(1, min(pp, 40) + 1))
+        idx = oracle.select_bases(patch, r, "l1" if rng.random() < 0.5 else "linf")
+    elif kind == 1:
+        r = int(rng.integers(1, min(pp, 24) + 1))
+        idx = rng.permutation(pp)[:r].astype(np.int32)          # arbitrary and unordered, as LHE could return
+    else:
+        k = int(rng.integers(1, min(patch, 4) + 1))             # a whole LP_Linf square: poolable
+        idx = oracle.select_bases(patch, k * k, "linf")
+    return Workload(f"random{i}", N, H, W, Cin, Cout, patch, (), ("l1",), dtype, 9000 + i), np.asarray(idx)
+
+
+@pytest.mark.parametrize("i", range(N_CASES))
+def test_random_case_matches_the_oracle(i):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    wl, idx = draw_case(i)
+    print(f"case {i}: N={wl.N} grid={wl.H}x{wl.W} Cin={wl.Cin} Cout={wl.Cout} patch={wl.patch} dtype={wl.dtype} idx={idx.tolist()}",
+          flush=True)
+    host, dev = device_inputs(wl)
+    gx, gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], wl.patch, idx)
+    torch.cuda.synchronize()
+    gx0, gW0 = oracle.lbp_wht_backward_padded(host["x"], host["gy"], host["w"], wl.patch, idx)
+    egx, egw = rel_fro(to_host(gx), gx0), rel_fro(to_host(gW), gW0)
+    assert egx <= TOL[wl.dtype] and egw <= TOL[wl.dtype], (egx, egw)
