@@ -404,3 +404,31 @@ def test_selection_on_the_library_side_is_bit_exact():
         for order in ("l1", "linf"):
             for r in (1, 2, 3, p, p * p // 2, p * p):
                 assert binding.select_bases(p, r, order) == oracle.select_bases(p, r, order).tolist()
+
+
+def test_backward_inside_a_captured_graph_replays_correctly():
+    # After one eager call (workspace grown, kernels configured) the call makes no allocation and no
+    # synchronisation, so it can be recorded into a HIP graph.  Replays, with new inputs written in place
+    # and eager work in between, must reproduce the eager results bit for bit.
+    wl = small("graph", 4, 16, 16, 136, 264, 8, "bf16", 77)
+    idx = oracle.select_bases(8, 8, "l1")
+    host, dev = device_inputs(wl)
+    gx = torch.empty_like(dev["x"])
+    gW = torch.empty(dev["w"].shape, dtype=torch.float32, device="cuda")
+    binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx, gx=gx, gW=gW)      # warm-up, eager
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx, gx=gx, gW=gW)
+    for rep in range(4):
+        with torch.no_grad():
+            dev["gy"].mul_(-0.5 if rep % 2 else 2.0)           # exact in bf16: new inputs, same buffers
+            dev["x"].copy_(dev["x"].roll(1, dims=0))
+        gx.fill_(float("nan"))
+        gW.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got_gx, got_gW = gx.clone(), gW.clone()
+        ref_gx, ref_gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx)
+        torch.cuda.synchronize()
+        assert torch.equal(got_gx, ref_gx) and torch.equal(got_gW, ref_gW), rep
