@@ -226,17 +226,42 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDevF32 g)
 
 // ---- split-K reduction ------------------------------------------------------------------------
 
+// out[i] = scale * sum_z part[z][i] in a FIXED order (results repeat bit for bit).  A workgroup
+// owns 64 consecutive float4 elements; its four wavefronts take every fourth slice each, with all
+// loads of a wavefront independent of one another (a small output split into many slices is bound
+// by load latency, not bandwidth), and the four partial sums are combined through LDS:
+// ((w0 + w1) + (w2 + w3)), w_g = part[g] + part[g+4] + ...
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float4 *__restrict__ part, int splits,
                                                             long count4, float scale, void *out)
 {
-    long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= count4) return;
-    float4 s = part[i];
-    for (int z = 1; z < splits; ++z) {
-        float4 t = part[(size_t)z * count4 + i];
-        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    __shared__ float4 partial[3][64];
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const long i = (long)blockIdx.x * 64 + lane;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < count4) {
+        int z = g;
+        for (; z + 12 < splits; z += 16) {          // four slices of this wavefront in flight together
+            float4 t0 = part[(size_t)z * count4 + i], t1 = part[(size_t)(z + 4) * count4 + i];
+            float4 t2 = part[(size_t)(z + 8) * count4 + i], t3 = part[(size_t)(z + 12) * count4 + i];
+            s.x += t0.x; s.y += t0.y; s.z += t0.z; s.w += t0.w;
+            s.x += t1.x; s.y += t1.y; s.z += t1.z; s.w += t1.w;
+            s.x += t2.x; s.y += t2.y; s.z += t2.z; s.w += t2.w;
+            s.x += t3.x; s.y += t3.y; s.z += t3.z; s.w += t3.w;
+        }
+        for (; z < splits; z += 4) {
+            float4 t = part[(size_t)z * count4 + i];
+            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
     }
+    if (g > 0) partial[g - 1][lane] = s;
+    __syncthreads();
+    if (g != 0 || i >= count4) return;
+    const float4 w1 = partial[0][lane], w2 = partial[1][lane], w3 = partial[2][lane];
+    s.x = (s.x + w1.x) + (w2.x + w3.x);
+    s.y = (s.y + w1.y) + (w2.y + w3.y);
+    s.z = (s.z + w1.z) + (w2.z + w3.z);
+    s.w = (s.w + w1.w) + (w2.w + w3.w);
     s.x *= scale; s.y *= scale; s.z *= scale; s.w *= scale;
     if (OUT_BF16)
         reinterpret_cast<uint2 *>(out)[i] = make_uint2(pack_bf16x2(s.x, s.y), pack_bf16x2(s.z, s.w));
@@ -295,7 +320,7 @@ hipError_t launch_splitk_reduce(const float *part, int splits, long count, float
 {
     if (count % 4 || splits < 1) return hipErrorInvalidValue;
     long count4 = count / 4;
-    unsigned blocks = (unsigned)((count4 + 255) / 256);
+    unsigned blocks = (unsigned)((count4 + 63) / 64);
     if (out_dtype == LBP_BF16)
         hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3(blocks), dim3(256), 0, stream,
                            (const float4 *)part, splits, count4, scale, out);
