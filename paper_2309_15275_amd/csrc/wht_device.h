@@ -24,14 +24,17 @@ struct GridGeom {
     int PW;        // patches per grid row, ceil(W / patch)
     int PHW;       // patches per image
     int patch;
-    // image n, first grid row a0 and first grid column b0 of patch q
+    // image n, first grid row a0 and first grid column b0 of patch q (patch numbers fit 31 bits:
+    // the token count does; 32-bit divisions are several times cheaper than 64-bit ones)
     __device__ __forceinline__ void origin(long q, long &n, int &a0, int &b0) const
     {
-        n = q / PHW;
-        int rem = (int)(q - n * PHW);
-        int a = rem / PW;
-        a0 = a * patch;
-        b0 = (rem - a * PW) * patch;
+        const unsigned uq = (unsigned)q;
+        const unsigned un = uq / (unsigned)PHW;
+        const unsigned rem = uq - un * (unsigned)PHW;
+        const unsigned a = rem / (unsigned)PW;
+        n = (long)un;
+        a0 = (int)(a * (unsigned)patch);
+        b0 = (int)((rem - a * (unsigned)PW) * (unsigned)patch);
     }
 };
 

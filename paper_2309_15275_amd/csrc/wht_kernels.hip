@@ -46,7 +46,9 @@ __global__ __launch_bounds__(256) void wht_project_reg_kernel(ProjTensor t0, Pro
     const int Cd = t.Cd;
     long item = (long)(blockIdx.x - (second ? t0.blocks : 0u)) * 256 + threadIdx.x;
     if (item >= t.items) return;
-    long q = item / Cd;
+    long q;
+    if (t.items <= 0xffffffffLL) q = (long)((unsigned)item / (unsigned)Cd);      // a 64-bit division costs ~100 instructions
+    else q = item / Cd;
     int cd = (int)(item - q * Cd);
     long n;
     int a0, b0;
@@ -115,7 +117,9 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
     constexpr float scale = 1.0f / (float)(P * P);
     long item = (long)blockIdx.x * 256 + threadIdx.x;
     if (item >= items) return;
-    long q = item / Cd;
+    long q;
+    if (items <= 0xffffffffLL) q = (long)((unsigned)item / (unsigned)Cd);      // a 64-bit division costs ~100 instructions
+    else q = item / Cd;
     int cd = (int)(item - q * Cd);
     long n;
     int a0, b0;

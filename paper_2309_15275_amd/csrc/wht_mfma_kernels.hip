@@ -114,24 +114,87 @@ __global__ __launch_bounds__(256) void wht_project_mfma_kernel(MfmaTensor t0, Mf
         }
     }
 
-    for (long item = wg * items_per_wg; item < min(t.items, (wg + 1) * (long)items_per_wg); ++item) {
-        const long q = item / t.chunks;
-        const int c0 = (int)(item - q * t.chunks) * CB;
+    // The loads of the next item are issued before the current one is multiplied, so that a
+    // workgroup always has one item (16 KB) on its way from HBM (not for patch 16: no registers left).
+    constexpr bool PREFETCH = KSTEPS <= 4 && MTILES == 1;
+    constexpr int LOADS = P2PAD * (CB / 8) / 256 > 0 ? P2PAD * (CB / 8) / 256 : 1;      // 16-byte loads per lane per item
+    static_assert(P2PAD * (CB / 8) % 256 == 0 || P2PAD * (CB / 8) < 256, "loads must divide over the lanes");
+    const long item_end = min(t.items, (wg + 1) * (long)items_per_wg);
+    u32x4_t stage_regs[PREFETCH ? LOADS : 1];
+    const int lp = 31 - __clz(p);             // patch is a power of two
+    // per-lane constants of the staging loads: element offset inside a patch, token row/column
+    size_t ld_off[PREFETCH ? LOADS : 1];
+    int ld_h[PREFETCH ? LOADS : 1], ld_w[PREFETCH ? LOADS : 1];
+    const int cc8 = (tid & 15) * 8;
+#pragma unroll
+    for (int j = 0; j < (PREFETCH ? LOADS : 1); ++j) {
+        const int tk = (tid + j * 256) >> 4;
+        ld_h[j] = tk < p2 ? tk >> lp : 0x7fffffff;        // rows past the patch never pass the edge test
+        ld_w[j] = tk & (p - 1);
+        ld_off[j] = ((size_t)(tk >> lp) * g.Wt + (tk & (p - 1))) * t.C + cc8;
+    }
+    auto fetch = [&](unsigned q, int chunk) {
+        const int c0 = chunk * CB;
         long n;
         int a0, b0;
         g.origin(q, n, a0, b0);
-        const size_t tok0 = (size_t)n * g.HWt + (size_t)a0 * g.Wt + b0;
+        const unsigned short *base = t.in + ((size_t)n * g.HWt + (size_t)a0 * g.Wt + b0) * t.C + c0;
+        const int hv = g.Ht - a0, wv = g.Wt - b0;         // tokens of the patch inside the grid
+        const bool chan_ok = c0 + cc8 < t.C;
+        if (hv >= p && wv >= p && P2PAD == p2) {
+#pragma unroll
+            for (int j = 0; j < (PREFETCH ? LOADS : 1); ++j) {
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (chan_ok) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(base + ld_off[j]));
+                stage_regs[j] = v;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < (PREFETCH ? LOADS : 1); ++j) {
+                u32x4_t v = {0u, 0u, 0u, 0u};           // zero padding past the patch, the grid or the channels
+                if (chan_ok && ld_h[j] < hv && ld_w[j] < wv && tid + j * 256 < P2PAD * (CB / 8))
+                    v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(base + ld_off[j]));
+                stage_regs[j] = v;
+            }
+        }
+    };
+    // (patch, chunk) of the items of this workgroup: one division, then counting
+    long item = wg * items_per_wg;
+    unsigned q = (unsigned)(item / t.chunks);
+    int chunk = (int)(item - (long)q * t.chunks);
+    if (PREFETCH && item < item_end) fetch(q, chunk);
+    for (; item < item_end; ++item) {
+        const int c0 = chunk * CB;
+        unsigned q_next = q;
+        int chunk_next = chunk + 1;
+        if (chunk_next == t.chunks) {
+            chunk_next = 0;
+            ++q_next;
+        }
         __syncthreads();                      // the previous item's stores have left LDS
         // ---- tokens -> LDS [token][channel]
-        for (int c = tid; c < P2PAD * (CB / 8); c += 256) {
-            int tk = c >> 4, cc = c & 15;
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            int h = tk / p, w = tk - h * p;
-            if (tk < p2 && c0 + cc * 8 < t.C && a0 + h < g.Ht && b0 + w < g.Wt) {   // else zero padding
-                v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(
-                    t.in + (tok0 + (size_t)h * g.Wt + w) * t.C + c0 + cc * 8));
+        if constexpr (PREFETCH) {
+#pragma unroll
+            for (int j = 0; j < LOADS; ++j) {
+                const int c = tid + j * 256;
+                if (c < P2PAD * (CB / 8)) *reinterpret_cast<u32x4_t *>(smem + (c >> 4) * S_IN + (c & 15) * 16) = stage_regs[j];
             }
-            *reinterpret_cast<u32x4_t *>(smem + tk * S_IN + cc * 16) = v;
+            if (item + 1 < item_end) fetch(q_next, chunk_next);
+        } else {
+            long n;
+            int a0, b0;
+            g.origin(q, n, a0, b0);
+            const size_t tok0 = (size_t)n * g.HWt + (size_t)a0 * g.Wt + b0;
+            for (int c = tid; c < P2PAD * (CB / 8); c += 256) {
+                int tk = c >> 4, cc = c & 15;
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                int h = tk >> lp, w = tk & (p - 1);
+                if (tk < p2 && c0 + cc * 8 < t.C && a0 + h < g.Ht && b0 + w < g.Wt) {   // else zero padding
+                    v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(
+                        t.in + (tok0 + (size_t)h * g.Wt + w) * t.C + c0 + cc * 8));
+                }
+                *reinterpret_cast<u32x4_t *>(smem + tk * S_IN + cc * 16) = v;
+            }
         }
         __syncthreads();
         // ---- matrix cores: each wavefront 32 channels, all bases
@@ -181,6 +244,8 @@ __global__ __launch_bounds__(256) void wht_project_mfma_kernel(MfmaTensor t0, Mf
                 *reinterpret_cast<uint4 *>(t.out + ((size_t)q * r + k) * t.C + c0 + cc * 8) =
                     *reinterpret_cast<const uint4 *>(smem + k * S_OUT + cc * 16);
         }
+        q = q_next;
+        chunk = chunk_next;
     }
 }
 
@@ -216,9 +281,28 @@ __global__ __launch_bounds__(256) void wht_unproject_mfma_kernel(const float *__
     }
 
     const long wg = blockIdx.x;
-    for (long item = wg * items_per_wg; item < min(items, (wg + 1) * (long)items_per_wg); ++item) {
-        const long q = item / chunks;
-        const int c0 = (int)(item - q * chunks) * CB;
+    const int lp = 31 - __clz(p);             // patch is a power of two
+    // per-lane constants of the token stores (16 bytes each): element offset inside a patch, row, column
+    // (only where registers allow: up to 32 bases of an 8 x 8 patch)
+    constexpr bool HOIST = MTILES <= 2 && KSTEPS <= 2;
+    constexpr int STORES = HOIST ? MTILES * 32 * (CB / 8) / 256 : 1;
+    size_t st_off[STORES];
+    int st_h[STORES], st_w[STORES];
+    const int cc8 = (tid & 15) * 8;
+#pragma unroll
+    for (int j = 0; j < STORES; ++j) {
+        const int tk = (tid + j * 256) >> 4;
+        st_h[j] = tk < p2 ? tk >> lp : 0x7fffffff;        // rows past the patch never pass the edge test
+        st_w[j] = tk & (p - 1);
+        st_off[j] = ((size_t)(tk >> lp) * g.Wt + (tk & (p - 1))) * C + cc8;
+    }
+    // (patch, chunk) of the items of this workgroup: one division, then counting
+    long item = wg * items_per_wg;
+    const long item_end = min(items, (wg + 1) * (long)items_per_wg);
+    unsigned q = (unsigned)(item / chunks);
+    int chunk = (int)(item - (long)q * chunks);
+    for (; item < item_end; ++item) {
+        const int c0 = chunk * CB;
         long n;
         int a0, b0;
         g.origin(q, n, a0, b0);
@@ -274,13 +358,30 @@ __global__ __launch_bounds__(256) void wht_unproject_mfma_kernel(const float *__
             }
         }
         __syncthreads();
-        for (int c = tid; c < p2 * (CB / 8); c += 256) {
-            int tk = c >> 4, cc = c & 15;
-            int h = tk / p, w = tk - h * p;
-            if (c0 + cc * 8 < C && a0 + h < g.Ht && b0 + w < g.Wt) {
-                u32x4_t v = *reinterpret_cast<const u32x4_t *>(smem + tk * S_OUT + cc * 16);
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(out + (tok0 + (size_t)h * g.Wt + w) * C + c0 + cc * 8));
+        if constexpr (!HOIST) {
+            for (int c = tid; c < p2 * (CB / 8); c += 256) {
+                int tk = c >> 4, cc = c & 15;
+                int h = tk >> lp, w = tk & (p - 1);
+                if (c0 + cc * 8 < C && a0 + h < g.Ht && b0 + w < g.Wt) {
+                    u32x4_t v = *reinterpret_cast<const u32x4_t *>(smem + tk * S_OUT + cc * 16);
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(out + (tok0 + (size_t)h * g.Wt + w) * C + c0 + cc * 8));
+                }
             }
+        } else if (c0 + cc8 < C) {
+            unsigned short *base = out + tok0 * C + c0;
+            const int hv = g.Ht - a0, wv = g.Wt - b0;     // tokens of the patch inside the grid
+            const unsigned char *row = smem + (tid >> 4) * S_OUT + (tid & 15) * 16;
+#pragma unroll
+            for (int j = 0; j < STORES; ++j) {
+                if (st_h[j] < hv && st_w[j] < wv) {
+                    u32x4_t v = *reinterpret_cast<const u32x4_t *>(row + j * 16 * S_OUT);
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(base + st_off[j]));
+                }
+            }
+        }
+        if (++chunk == chunks) {
+            chunk = 0;
+            ++q;
         }
     }
 }
