@@ -396,5 +396,6 @@ hipError_t mfma_tile_256x128(const mfma::Params &p, bool a_kfast, GemmOut out, i
 hipError_t mfma_tile_256x256(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
 hipError_t mfma_tile_128x128w8(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
 hipError_t mfma_tile_64x128w8(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
+hipError_t mfma_tile_64x64(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
 
 }  // namespace lbp

@@ -156,12 +156,13 @@ bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb)
 }
 
 const GemmTileInfo kGemmTiles[kNumGemmTiles] = {
-    {128, 128, true, 1.0},
-    {64, 128, true, 1.0},
-    {256, 128, false, 1.15},
-    {256, 256, false, 1.4},
-    {128, 128, true, 0.92},    // 8 wavefronts: hides more of the LDS -> matrix-core latency
-    {64, 128, true, 0.88},     // 8 wavefronts
+    {128, 128, true, 1.0, 0},
+    {64, 128, true, 1.0, 0},
+    {256, 128, false, 1.15, 0},
+    {256, 256, false, 1.4, 0},
+    {128, 128, true, 0.92, 0},    // 8 wavefronts: hides more of the LDS -> matrix-core latency
+    {64, 128, true, 0.88, 0},     // 8 wavefronts
+    {64, 64, true, 1.0, 64},      // thin layers only: on wide ones it measured 10-15 % behind 64 x 128
 };
 
 GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split, int fused_r,
@@ -176,6 +177,8 @@ GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split,
     for (int t = 0; t < kNumGemmTiles; ++t) {
         const GemmTileInfo &ti = kGemmTiles[t];
         if (fused_r > 0 && (!ti.fused || fused_r > ti.bm)) continue;
+        if (ti.max_n > 0 && N > ti.max_n) continue;
+        if (N <= 64 && ti.bn > 64) continue;      // a thin product always takes the 64-wide tile (measured)
         const long bm_step = fused_r > 0 ? ti.bm / fused_r * fused_r : ti.bm;
         const long tiles = ((M + bm_step - 1) / bm_step) * ((N + ti.bn - 1) / ti.bn);
         const int max_splits = (allow_split && fused_r == 0) ? 64 : 1;

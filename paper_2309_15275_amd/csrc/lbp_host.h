@@ -77,8 +77,9 @@ struct GemmTileInfo {
     int bm, bn;        // output tile of one workgroup
     bool fused;        // has the fused reverse-projection epilogue
     double slowdown;   // measured factor over the simple cost model below
+    int max_n;         // only offered to products with at most this many columns (0: any)
 };
-constexpr int kNumGemmTiles = 6;
+constexpr int kNumGemmTiles = 7;
 extern const GemmTileInfo kGemmTiles[kNumGemmTiles];
 
 // How one matrix product is run.
