@@ -309,18 +309,47 @@ __global__ __launch_bounds__(256) void wht_unproject_mfma_kernel(const float *__
         const size_t tok0 = (size_t)n * g.HWt + (size_t)a0 * g.Wt + b0;
         __syncthreads();
         // ---- coefficients (fp32, split-K slices summed in fixed order) -> bf16 -> LDS [basis][channel]
-        for (int c = tid; c < ksteps * 16 * (CB / 4); c += 256) {
-            int k = c >> 5, cc = c & 31;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k < r && c0 + cc * 4 < C) {
-                const float *src = in + ((size_t)q * r + k) * C + c0 + cc * 4;
-                v = *reinterpret_cast<const float4 *>(src);
-                for (int z = 1; z < slices; ++z) {
-                    float4 u = *reinterpret_cast<const float4 *>(src + z * slice_stride);
-                    v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+        // lane: 4 channels (cc4) of basis rows tid/32, tid/32 + 8, ...: all loads of a slice are issued
+        // before any is used (patch 16 has no registers for that and keeps the plain loop)
+        if constexpr (KSTEPS > 4) {
+            for (int c = tid; c < ksteps * 16 * (CB / 4); c += 256) {
+                int k = c >> 5, cc = c & 31;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (k < r && c0 + cc * 4 < C) {
+                    const float *src = in + ((size_t)q * r + k) * C + c0 + cc * 4;
+                    v = *reinterpret_cast<const float4 *>(src);
+                    for (int z = 1; z < slices; ++z) {
+                        float4 u = *reinterpret_cast<const float4 *>(src + z * slice_stride);
+                        v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+                    }
+                }
+                *reinterpret_cast<uint2 *>(smem + k * S_IN + cc * 8) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+            }
+        } else {
+            const int cc4 = (tid & 31) * 4, k0 = tid >> 5;
+            const bool chan_ok = c0 + cc4 < C;
+            const float *src = in + ((size_t)q * r + k0) * C + c0 + cc4;
+            float4 v[2 * KSTEPS];
+#pragma unroll
+            for (int j = 0; j < 2 * KSTEPS; ++j) {
+                v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (j * 8 < ksteps * 16 && chan_ok && k0 + j * 8 < r) v[j] = *reinterpret_cast<const float4 *>(src + (size_t)j * 8 * C);
+            }
+            for (int z = 1; z < slices; ++z) {
+                const float *sz = src + z * slice_stride;
+#pragma unroll
+                for (int j = 0; j < 2 * KSTEPS; ++j) {
+                    if (j * 8 < ksteps * 16 && chan_ok && k0 + j * 8 < r) {
+                        float4 u = *reinterpret_cast<const float4 *>(sz + (size_t)j * 8 * C);
+                        v[j].x += u.x; v[j].y += u.y; v[j].z += u.z; v[j].w += u.w;
+                    }
                 }
             }
-            *reinterpret_cast<uint2 *>(smem + k * S_IN + cc * 8) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+#pragma unroll
+            for (int j = 0; j < 2 * KSTEPS; ++j)
+                if (j * 8 < ksteps * 16)
+                    *reinterpret_cast<uint2 *>(smem + (k0 + j * 8) * S_IN + cc4 * 2) =
+                        make_uint2(pack_bf16x2(v[j].x, v[j].y), pack_bf16x2(v[j].z, v[j].w));
         }
         __syncthreads();
         f32x16_t acc[MTILES];
