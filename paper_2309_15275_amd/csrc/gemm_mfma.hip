@@ -42,10 +42,15 @@ bool gemm_can_fuse_unproject(const BasisPlan &plan, int dtype, GemmPath path)
 {
     if (path == GemmPath::kSimple || dtype != LBP_BF16) return false;
     if (plan.patch != 4 && plan.patch != 8) return false;
-    // The fused epilogue expands coefficients with the pooled register butterfly; beyond 16 pooled
-    // coefficients per channel that is register bound and the stand-alone matrix-core kernel wins.
-    int nc = (plan.patch >> plan.mh) * (plan.patch >> plan.mw);
-    return nc <= 16;     // r <= patch^2 <= 64 always fits the smallest tile
+    // Up to 16 pooled coefficients per channel the epilogue expands them with the register
+    // butterfly; beyond that (selections that cannot be pooled) an 8 x 8 patch goes through the
+    // matrix-core epilogue.  r <= patch^2 <= 64 always fits the smallest tile.
+    return gemm_unproject_pooled(plan) || plan.patch == 8;
+}
+
+bool gemm_unproject_pooled(const BasisPlan &plan)
+{
+    return (plan.patch >> plan.mh) * (plan.patch >> plan.mw) <= 16;
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
@@ -56,12 +61,15 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
     if (a.N % 8 || a.ldb % 8 || a.lda % 8 || (a.a_kfast ? a.K % 8 : a.M % 8)) return hipErrorInvalidValue;
     if (a.out != GemmOut::kF32 && a.splits != 1) return hipErrorInvalidValue;
     int tile = tile_from_env();     // testing: force one tile shape for every product
-    if (tile >= 0 && a.out == GemmOut::kUnproject && !kGemmTiles[tile].fused) tile = -1;
+    if (tile >= 0 && a.out == GemmOut::kUnproject &&
+        (!kGemmTiles[tile].fused || (a.plan && !gemm_unproject_pooled(*a.plan) && kGemmTiles[tile].bn != 128)))
+        tile = -1;
     if (tile < 0) tile = a.tile;
     if (tile < 0 || tile >= kNumGemmTiles) {
         const bool fused = a.out == GemmOut::kUnproject;
         tile = plan_gemm(a.M, a.N, a.K / a.splits, a.out == GemmOut::kF32 ? 4 : 2, false,
-                         fused && a.plan ? a.plan->r : 0, fused && a.plan ? a.plan->patch : 0, device_cus()).tile;
+                         fused && a.plan ? a.plan->r : 0, fused && a.plan ? a.plan->patch : 0, device_cus(),
+                         fused && a.plan && !gemm_unproject_pooled(*a.plan)).tile;
     }
     const GemmTileInfo &t = kGemmTiles[tile];
 
@@ -83,6 +91,9 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
         lp = bp.log2p;
         p.r = bp.r; p.mh = bp.mh; p.mw = bp.mw;
         p.bm_step = t.bm / bp.r * bp.r;
+        p.mfma_epilogue = gemm_unproject_pooled(bp) ? 0 : 1;
+        if (p.mfma_epilogue && t.bn != 128) return hipErrorInvalidValue;
+        for (int k = 0; k < 64; ++k) p.nat[k] = k < bp.r ? (unsigned char)bp.nat[k] : (unsigned char)0;
         p.sel.mask = bp.pooled_mask;
         for (int j = 0; j < 64; ++j) p.sel.pos[j] = bp.pooled_pos[j];
         p.geom = make_geom(a.grid_h, a.grid_w, bp.patch);

@@ -38,7 +38,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 64;
 
-enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_UNPROJECT = 2 };
+enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_UNPROJECT = 2, EPI_UNPROJECT_MFMA = 3 };
 
 struct Params {
     const unsigned short *A;
@@ -55,6 +55,8 @@ struct Params {
     PooledSel sel;
     int r, mh, mw;
     long Q;               // number of patches
+    unsigned char nat[64];   // natural (Sylvester) index of every selected basis (matrix-core epilogue, patch 8)
+    int mfma_epilogue;    // 1: the selection cannot be pooled, Eq. 7 runs on the matrix cores in the epilogue
 };
 
 // Reverse projection of one tile held in LDS as fp32 ct[row][cts]; rows are (patch, basis).
@@ -293,7 +295,106 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
     }
 
     // accumulator element 4*g4 + e of a 32x32 tile: row 8*g4 + 4*(lane/32) + e, column lane%32
-    if constexpr (EPI == EPI_UNPROJECT) {
+    if constexpr (EPI == EPI_UNPROJECT_MFMA) {
+        // Eq. 7 for selections that cannot be pooled (patch 8): per patch, tokens[64][BN] =
+        // (1/64) * S[64][r] * coefficients[r][BN] with S the +-1 matrix, on the matrix cores.
+        // The tile's rows (patch, basis) go to LDS as bf16 in the layout of a reduction-slow
+        // operand; the sign operand is built in registers from the bases' natural indices;
+        // token rows are staged in LDS so that global stores are 16 bytes per lane.
+        static_assert(BN == 128 && LP == 3, "matrix-core epilogue: 128 channels per tile, patch 8");
+        constexpr int S_CO = BN * 2 + 64;       // pitch of the coefficient rows (transposing LDS reads)
+        constexpr int S_TK = BN * 2 + 16;       // pitch of the staged token rows
+        constexpr int MTW = NT == 256 ? 2 : 1;  // 32-token tiles per wavefront (4 wavefronts: both; 8: one each)
+        static_assert(NT == 256 || NT == 512, "4 or 8 wavefronts");
+        static_assert((BM + 16) * S_CO + 64 * S_TK <= S::TOTAL, "epilogue does not fit in LDS");
+        __shared__ unsigned char lds_nat[64];
+        unsigned char *cot = smem, *stg = smem + (BM + 16) * S_CO;
+        if (tid < 64) lds_nat[tid] = p.nat[tid];
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        int row = wm * WM + mi * 32 + g4 * 8 + kg * 4 + e;
+                        int col = wn * WN + ni * 32 + li;
+                        *reinterpret_cast<unsigned short *>(cot + row * S_CO + col * 2) =
+                            (unsigned short)f32_to_bf16_bits(acc[mi][ni][g4 * 4 + e]);
+                    }
+        // the last sub-step of the last patch reads up to 15 rows past the tile: zeros
+        for (int c = tid; c < 16 * (S_CO / 16); c += NT)
+            *reinterpret_cast<uint4 *>(cot + BM * S_CO + c * 16) = make_uint4(0u, 0u, 0u, 0u);
+        __syncthreads();
+        const int ch = wave & 3, mt0 = NT == 256 ? 0 : wave >> 2;
+        const int ksteps = (p.r + 15) >> 4;
+        bf16x8_t sgn[MTW][4];
+#pragma unroll
+        for (int m = 0; m < MTW; ++m)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const unsigned tk = (unsigned)((mt0 + m) * 32 + li);
+                i16x8_t v;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int k = ks * 16 + kg * 8 + e;
+                    const unsigned nk = lds_nat[k < p.r ? k : 0];
+                    v[e] = k < p.r ? (short)((__popc(nk & tk) & 1) ? 0xBF80 - 0x10000 : 0x3F80) : (short)0;     // bf16 -1, +1, 0
+                }
+                sgn[m][ks] = __builtin_bit_cast(bf16x8_t, v);
+            }
+        const int patches = p.bm_step / p.r;
+        const float inv = 1.0f / 64.0f;
+        for (int pt = 0; pt < patches; ++pt) {
+            const long q = (long)(m0 / p.r) + pt;
+            if (q >= p.Q) break;                    // the same for every lane of the workgroup
+            f32x16_t o[MTW];
+#pragma unroll
+            for (int m = 0; m < MTW; ++m)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[m][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks < ksteps) {
+                    const unsigned char *qd = cot + (pt * p.r + ks * 16 + 8 * (grp >> 1) + (i16 >> 2)) * S_CO +
+                                              (ch * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2;
+                    i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, qd));
+                    i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, qd + 4 * S_CO));
+                    bf16x8_t b = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                    for (int m = 0; m < MTW; ++m)      // rows of the product = channels, columns = tokens
+                        o[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, sgn[m][ks], o[m], 0, 0, 0);
+                }
+            }
+            // element 4*g4+e of o: channel ch*32 + 8*g4 + 4*kg + e, token (mt0+m)*32 + li
+#pragma unroll
+            for (int m = 0; m < MTW; ++m) {
+                const int tk = (mt0 + m) * 32 + li;
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4)
+                    *reinterpret_cast<uint2 *>(stg + tk * S_TK + (ch * 32 + g4 * 8 + kg * 4) * 2) =
+                        make_uint2(pack_bf16x2(o[m][g4 * 4] * inv, o[m][g4 * 4 + 1] * inv),
+                                   pack_bf16x2(o[m][g4 * 4 + 2] * inv, o[m][g4 * 4 + 3] * inv));
+            }
+            __syncthreads();
+            long img;
+            int a0, b0;
+            p.geom.origin(q, img, a0, b0);
+            unsigned short *dst = reinterpret_cast<unsigned short *>(p.C) +
+                                  ((size_t)img * p.geom.HWt + (size_t)a0 * p.geom.Wt + b0) * p.N + n0;
+            const int hv = p.geom.Ht - a0, wv = p.geom.Wt - b0;     // tokens of the patch inside the grid
+            for (int c = tid; c < 64 * (BN / 8); c += NT) {
+                const int tk = c >> 4, cc = c & 15, h = tk >> 3, w = tk & 7;
+                if (n0 + cc * 8 < p.N && h < hv && w < wv) {
+                    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+                    u32x4_t v = *reinterpret_cast<const u32x4_t *>(stg + tk * S_TK + cc * 16);
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(dst + ((size_t)h * p.geom.Wt + w) * p.N + cc * 8));
+                }
+            }
+            __syncthreads();                        // the staging rows are free again
+        }
+    } else if constexpr (EPI == EPI_UNPROJECT) {
         constexpr int CTS = BN + 8;
         static_assert(BM * CTS * 4 <= S::TOTAL, "tile does not fit in LDS");
         float *ct = reinterpret_cast<float *>(smem);
@@ -374,6 +475,12 @@ hipError_t launch_tile(const Params &p, bool a_kfast, GemmOut out, int lp, int s
 {
     if (out == GemmOut::kUnproject) {
         if constexpr (FUSED) {
+            if (p.mfma_epilogue) {
+                if constexpr (BN == 128) {
+                    if (lp == 3) return launch_one<BM, BN, WGM, WGN, PF, true, EPI_UNPROJECT_MFMA, 3>(p, 1, s);
+                }
+                return hipErrorInvalidValue;
+            }
             if (lp == 3) return launch_one<BM, BN, WGM, WGN, PF, true, EPI_UNPROJECT, 3>(p, 1, s);
             if (lp == 2) return launch_one<BM, BN, WGM, WGN, PF, true, EPI_UNPROJECT, 2>(p, 1, s);
         }

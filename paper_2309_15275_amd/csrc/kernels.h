@@ -70,6 +70,9 @@ struct GemmArgs {
 
 // True if launch_gemm supports GemmOut::kUnproject for this selection and dtype.
 bool gemm_can_fuse_unproject(const BasisPlan &plan, int dtype, GemmPath path);
+// True if the fused epilogue is the pooled register butterfly (else the matrix-core form, which
+// needs a tile 128 columns wide).
+bool gemm_unproject_pooled(const BasisPlan &plan);
 
 hipError_t launch_gemm(const GemmArgs &g, GemmPath path, hipStream_t stream);
 

@@ -399,7 +399,8 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     const int fuse_env = fuse_unproject_from_env();
     const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
     lbp::WorkspacePlan ws;
-    rc = lbp::plan_workspace(shape, patch, r, st->num_cus, can_fuse, fuse_env == 1, &ws);
+    rc = lbp::plan_workspace(shape, patch, r, st->num_cus, can_fuse, fuse_env == 1, &ws,
+                             !lbp::gemm_unproject_pooled(plan));
     if (rc) return rc;
     char *base = nullptr;
     rc = get_workspace(st, ws.total, &base);

@@ -166,7 +166,7 @@ const GemmTileInfo kGemmTiles[kNumGemmTiles] = {
 };
 
 GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split, int fused_r,
-                   int fused_patch, int num_cus)
+                   int fused_patch, int num_cus, bool fused_wide)
 {
     const double kFill = 20.0;            // bytes per clock a compute unit takes in from L2
     const double kClkPerUs = 2400.0;
@@ -178,7 +178,8 @@ GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split,
         const GemmTileInfo &ti = kGemmTiles[t];
         if (fused_r > 0 && (!ti.fused || fused_r > ti.bm)) continue;
         if (ti.max_n > 0 && N > ti.max_n) continue;
-        if (N <= 64 && ti.bn > 64) continue;      // a thin product always takes the 64-wide tile (measured)
+        if (fused_r > 0 && fused_wide && ti.bn != 128) continue;
+        if (N <= 64 && ti.bn > 64 && !(fused_r > 0 && fused_wide)) continue;      // a thin product takes the 64-wide tile (measured)
         const long bm_step = fused_r > 0 ? ti.bm / fused_r * fused_r : ti.bm;
         const long tiles = ((M + bm_step - 1) / bm_step) * ((N + ti.bn - 1) / ti.bn);
         const int max_splits = (allow_split && fused_r == 0) ? 64 : 1;
@@ -210,7 +211,7 @@ GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split,
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
-                   bool force_fuse, WorkspacePlan *ws)
+                   bool force_fuse, WorkspacePlan *ws, bool fused_wide)
 {
     if (!s || !ws) return LBP_ERR_NULL;
     std::memset(ws, 0, sizeof *ws);
@@ -248,7 +249,7 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
     ws->gx = unfused;
     ws->gx_fused = false;
     if (can_fuse && s->dtype == LBP_BF16) {
-        GemmPlan fused = plan_gemm(Mr, s->Cin, s->Cout, 2, false, r, patch, num_cus);
+        GemmPlan fused = plan_gemm(Mr, s->Cin, s->Cout, 2, false, r, patch, num_cus, fused_wide);
         if (force_fuse || fused.est_us <= unfused.est_us) {
             ws->gx = fused;
             ws->gx_fused = true;

@@ -97,8 +97,9 @@ struct GemmPlan {
 // The model: a compute unit takes in about 20 bytes a clock from L2 however many loads are in
 // flight, so a workgroup's time is its operand and output bytes over that rate (or its matrix-core
 // time if larger), and the workgroups run in ceil(count / compute units) rounds.
+// fused_wide: the fused epilogue is the matrix-core one, which needs a 128-column tile.
 GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split, int fused_r,
-                   int fused_patch, int num_cus);
+                   int fused_patch, int num_cus, bool fused_wide = false);
 
 // Workspace layout of one backward call; offsets in bytes from the workspace base, each
 // 256-byte aligned.  Sizes of 0 mean "not used".
@@ -112,9 +113,9 @@ struct WorkspacePlan {
 
 // num_cus: compute units of the device (the GEMM plans depend on it); pass 256 when unknown.
 // can_fuse: the selection allows the fused reverse projection (false gives the larger workspace);
-// force_fuse: take it whenever allowed instead of comparing estimates.
+// force_fuse: take it whenever allowed instead of comparing estimates; fused_wide: see plan_gemm.
 int plan_workspace(const lbp_shape_t *shape, int patch, int r, int num_cus, bool can_fuse,
-                   bool force_fuse, WorkspacePlan *ws);
+                   bool force_fuse, WorkspacePlan *ws, bool fused_wide = false);
 
 const char *status_string(int code);
 
