@@ -91,13 +91,24 @@ __device__ __forceinline__ void unproject_tile(const float *ct, int cts, const P
         p.geom.origin(q, img, a0, b0);
         uint32_t *dst = reinterpret_cast<uint32_t *>(p.C) + ((size_t)img * p.geom.HWt + (size_t)a0 * p.geom.Wt + b0) * Cd + (n0 >> 1) + cp;
         const int hv = p.geom.Ht - a0, wv = p.geom.Wt - b0;     // tokens of the patch inside the grid (>= P: all)
+        if (hv >= P && wv >= P) {                 // the whole patch is inside the grid
 #pragma unroll
-        for (int h = 0; h < P; ++h) {
+            for (int h = 0; h < P; ++h) {
 #pragma unroll
-            for (int w = 0; w < P; ++w) {
-                int j = (h >> MH) * PWd + (w >> MW);
-                if (h < hv && w < wv)
+                for (int w = 0; w < P; ++w) {
+                    int j = (h >> MH) * PWd + (w >> MW);
                     __builtin_nontemporal_store(pack_bf16x2(c0[j] * scale, c1[j] * scale), dst + ((size_t)h * p.geom.Wt + w) * Cd);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int h = 0; h < P; ++h) {
+#pragma unroll
+                for (int w = 0; w < P; ++w) {
+                    int j = (h >> MH) * PWd + (w >> MW);
+                    if (h < hv && w < wv)
+                        __builtin_nontemporal_store(pack_bf16x2(c0[j] * scale, c1[j] * scale), dst + ((size_t)h * p.geom.Wt + w) * Cd);
+                }
             }
         }
     }

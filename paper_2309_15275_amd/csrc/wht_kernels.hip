@@ -148,13 +148,24 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
         }
         fwht_inplace<NC>(c0);
         fwht_inplace<NC>(c1);
+        if (hv >= P && wv >= P) {                 // the whole patch is inside the grid
 #pragma unroll
-        for (int h = 0; h < P; ++h) {
+            for (int h = 0; h < P; ++h) {
 #pragma unroll
-            for (int w = 0; w < P; ++w) {
-                int j = (h >> MH) * PWd + (w >> MW);
-                if (h < hv && w < wv)
+                for (int w = 0; w < P; ++w) {
+                    int j = (h >> MH) * PWd + (w >> MW);
                     __builtin_nontemporal_store(pack_bf16x2(c0[j] * scale, c1[j] * scale), dst + ((size_t)h * g.Wt + w) * Cd);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int h = 0; h < P; ++h) {
+#pragma unroll
+                for (int w = 0; w < P; ++w) {
+                    int j = (h >> MH) * PWd + (w >> MW);
+                    if (h < hv && w < wv)
+                        __builtin_nontemporal_store(pack_bf16x2(c0[j] * scale, c1[j] * scale), dst + ((size_t)h * g.Wt + w) * Cd);
+                }
             }
         }
     } else {
