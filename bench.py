@@ -66,6 +66,7 @@ def main():
     ap.add_argument("--order", default="l1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-library-gemm", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing")
     ap.add_argument("--warm-cache", action="store_true", help="reuse one buffer set (cache-warm timing)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for the HBM byte counters)")
@@ -142,6 +143,17 @@ def main():
         binding.lbp_wht_backward_preprojected(xr, s["gy"], s["w"], wl.patch, idx, gx=s["gx"], gW=s["gW"])
 
     ms_lbp, wall_lbp = timed(lbp_step, args.steps, args.warmup)
+    # the same steps recorded once into a HIP graph (one step per buffer set) and replayed: what a
+    # training loop that captures its backward pass sees; launch gaps between the kernels shrink
+    ms_graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(n_sets):
+                lbp_step(i)
+        reps = max(1, args.steps // n_sets)
+        ms_graph, _ = timed(lambda i: graph.replay(), reps, max(1, args.warmup // n_sets))
+        ms_graph /= n_sets
     # the variant that keeps x^ from the forward pass (never reads x)
     ms_pre, _ = timed(pre_step, args.steps, args.warmup)
     # the dominant kernel by itself, back to back on the launch stream (same rotation of buffers)
@@ -228,6 +240,7 @@ def main():
         "library_gemm_full_bp_ms": None if ms_lib is None else round(ms_lib, 5),
         "speedup_vs_library_gemm_full_bp": None if ms_lib is None else round(ms_lib / ms_lbp, 3),
         "preprojected_x_ms_per_step": round(ms_pre, 5),
+        "graph_replay_ms_per_step": None if ms_graph is None else round(ms_graph, 5),
         "host_wall_ms_per_step": round(wall_lbp, 5),
         "stages": stages,
         "roofline": roofline,
