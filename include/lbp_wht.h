@@ -120,6 +120,8 @@ size_t lbp_wht_energy_workspace_bytes(int N, int H, int W, int C, int dtype, int
  *   basis_idx  host array of r indices (see "Bases" above); r in [1, patch^2].
  * Uses the workspace set by lbp_set_workspace, else an internal per-device buffer that grows on
  * demand (the first call at a new size allocates device memory; later calls do not).
+ * The two products depend only on the projections, not on each other: when both gradients are
+ * requested they may run as one kernel launch.
  */
 int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
                      int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream);
@@ -139,8 +141,9 @@ int lbp_wht_backward_preprojected(const void *x_r, const void *gy, const void *W
  * For measurement, not part of the method: the same call as lbp_wht_backward, bracketed by HIP
  * events on `stream`.  It WAITS for the work to finish and returns the elapsed milliseconds of the
  * three stages in stage_ms (host, 3 floats): [0] projection of gy and x, [1] weight-gradient
- * product, [2] input-gradient product with the reverse projection.  Callers: benchmarks that
- * report where the time of a call goes.
+ * product, [2] input-gradient product with the reverse projection; here the two products are
+ * always launched one after the other (each with the tiles that suit it alone).  Callers:
+ * benchmarks that report where the time of a call goes.
  */
 int lbp_wht_backward_profile(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
                              int patch, const int32_t *basis_idx, int r, void *gx, void *gW,

@@ -53,7 +53,10 @@ bool gemm_unproject_pooled(const BasisPlan &plan)
     return (plan.patch >> plan.mh) * (plan.patch >> plan.mw) <= 16;
 }
 
-hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
+namespace {
+
+// Checks one product, picks its tile and fills the kernel parameters.
+hipError_t prepare(const GemmArgs &a, int *tile_out, mfma::Params *out, int *lp_out)
 {
     if (a.dtype != LBP_BF16) return hipErrorInvalidValue;
     // rows of a k-fast A are clamped one by one (any M); a k-slow A and B are read in 8-element pieces
@@ -83,6 +86,7 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
     p.tiles_n = (a.N + t.bn - 1) / t.bn;
     p.C = a.C;
     p.scale = a.scale;
+    p.store_bf16 = a.out == GemmOut::kBF16 ? 1 : 0;
     int lp = 0;
     if (a.out == GemmOut::kUnproject) {
         if (!a.plan || !a.a_kfast || !t.fused || a.plan->r > t.bm || !gemm_can_fuse_unproject(*a.plan, a.dtype, GemmPath::kAuto))
@@ -100,7 +104,51 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
         p.Q = a.M / bp.r;     // = patches of the zero-padded grids
     }
     p.tiles_m = (a.M + p.bm_step - 1) / p.bm_step;
+    *tile_out = tile;
+    *out = p;
+    *lp_out = lp;
+    return hipSuccess;
+}
+
+// Tiles of the grouped launch: 128x128 with 8 wavefronts for the weight gradient, that or 64x128
+// with 8 wavefronts for the input gradient.
+constexpr int kPairTileW = 4, kPairTileX0 = 4, kPairTileX1 = 5;
+
+}  // namespace
+
+hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
+{
+    int tile, lp;
+    mfma::Params p;
+    hipError_t e = prepare(a, &tile, &p, &lp);
+    if (e != hipSuccess) return e;
     return kLaunch[tile](p, a.a_kfast, a.out, lp, a.splits, stream);
+}
+
+bool gemm_pair_supported(const GemmArgs &x, const GemmArgs &w, GemmPath path)
+{
+    if (path == GemmPath::kSimple) return false;
+    if (x.dtype != LBP_BF16 || w.dtype != LBP_BF16 || !x.a_kfast || w.a_kfast) return false;
+    if (w.out == GemmOut::kUnproject) return false;
+    if (x.out == GemmOut::kUnproject && (!x.plan || x.plan->patch != 8)) return false;
+    int tx, tw, lp;
+    mfma::Params p;
+    if (prepare(x, &tx, &p, &lp) != hipSuccess || prepare(w, &tw, &p, &lp) != hipSuccess) return false;
+    return tw == kPairTileW && (tx == kPairTileX0 || tx == kPairTileX1);
+}
+
+hipError_t launch_gemm_pair(const GemmArgs &x, const GemmArgs &w, hipStream_t stream)
+{
+    int tx, tw, lpx, lpw;
+    mfma::Params px, pw;
+    hipError_t e = prepare(x, &tx, &px, &lpx);
+    if (e != hipSuccess) return e;
+    e = prepare(w, &tw, &pw, &lpw);
+    if (e != hipSuccess) return e;
+    if (tw != kPairTileW || (tx != kPairTileX0 && tx != kPairTileX1) || !x.a_kfast || w.a_kfast ||
+        w.out == GemmOut::kUnproject || (x.out == GemmOut::kUnproject && lpx != 3))
+        return hipErrorInvalidValue;
+    return mfma_pair_w8(px, kGemmTiles[tx].bm, x.out, x.splits, pw, w.splits, stream);
 }
 
 }  // namespace lbp

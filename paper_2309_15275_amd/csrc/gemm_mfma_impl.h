@@ -38,7 +38,8 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 64;
 
-enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_UNPROJECT = 2, EPI_UNPROJECT_MFMA = 3 };
+// EPI_PLAIN: fp32 or bf16 store chosen at run time by Params::store_bf16 (grouped launches)
+enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_UNPROJECT = 2, EPI_UNPROJECT_MFMA = 3, EPI_PLAIN = 4 };
 
 struct Params {
     const unsigned short *A;
@@ -57,6 +58,7 @@ struct Params {
     long Q;               // number of patches
     unsigned char nat[64];   // natural (Sylvester) index of every selected basis (matrix-core epilogue, patch 8)
     int mfma_epilogue;    // 1: the selection cannot be pooled, Eq. 7 runs on the matrix cores in the epilogue
+    int store_bf16;       // EPI_PLAIN: 1 stores bf16, 0 stores fp32 (slice by slice)
 };
 
 // Reverse projection of one tile held in LDS as fp32 ct[row][cts]; rows are (patch, basis).
@@ -114,18 +116,27 @@ __device__ __forceinline__ void unproject_tile(const float *ct, int cts, const P
     }
 }
 
+// LDS layout of one stage.  A reduction-slow operand keeps its rows [k][row]; the transposing reads
+// of one instruction touch 64 consecutive bytes of four consecutive k-rows, which must fall into
+// different banks: rows of 128 bytes are padded to a pitch of 192, rows of 256 bytes or more are
+// not padded but have their 64-byte pieces permuted per row (piece index xor k % 4), which keeps
+// two workgroups of the 128-wide tiles inside one compute unit's LDS.
 template <int BM, int BN, bool A_KFAST>
 struct Smem {
-    static constexpr int SA = A_KFAST ? (BK + 8) * 2 : BM * 2 + 64;   // LDS row pitch of A in bytes
-    static constexpr int SB = BN * 2 + 64;
+    static constexpr bool A_SWZ = !A_KFAST && BM >= 128;
+    static constexpr bool B_SWZ = BN >= 128;
+    static constexpr int SA = A_KFAST ? (BK + 8) * 2 : (A_SWZ ? BM * 2 : BM * 2 + 64);   // row pitch of A in bytes
+    static constexpr int SB = B_SWZ ? BN * 2 : BN * 2 + 64;
     static constexpr int A_BYTES = (A_KFAST ? BM : BK) * SA;
     static constexpr int B_BYTES = BK * SB;
     static constexpr int STAGE = A_BYTES + B_BYTES;
     static constexpr int TOTAL = 2 * STAGE;
 };
 
+// One workgroup's share of a product: output tile `tile_id` (before the XCD renumbering), split-K
+// slice `slice`; `smem` is the workgroup's dynamic LDS (at least Smem<BM, BN, A_KFAST>::TOTAL bytes).
 template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
+__device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, const int slice, unsigned char *smem)
 {
     static_assert(PF == 2 || PF == 4, "prefetch depth must be even");
     using S = Smem<BM, BN, A_KFAST>;
@@ -136,19 +147,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
     constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;       // 16-byte chunks per thread per step
     static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile does not divide over the threads");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 tiles");
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave - wm * WGN;
 
     // XCD-aware tile numbering: workgroup ids go round-robin over the 8 XCDs
     const int T = p.tiles_m * p.tiles_n;
-    int t = blockIdx.x;
+    int t = tile_id;
     if ((T & 7) == 0) t = (t & 7) * (T >> 3) + (t >> 3);
     const int tm = t / p.tiles_n, tn = t - tm * p.tiles_n;
     const int m0 = tm * p.bm_step, n0 = tn * BN;
-    const int kbeg = blockIdx.y * p.k_per_split;
+    const int kbeg = slice * p.k_per_split;
     const int kend = min(p.K, kbeg + p.k_per_split);
 
     // ---- per-thread load descriptors (rows / columns clamped into the matrix)
@@ -166,7 +175,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
             ga[i] = p.A + (size_t)min(m0 + row, p.M - 1) * p.lda + kc * 8;
         } else {
             int krow = c / (BM / 8), cc = c - krow * (BM / 8);
-            sa_off[i] = krow * SA + cc * 16;
+            sa_off[i] = krow * SA + ((cc * 16) ^ (S::A_SWZ ? (krow & 3) << 6 : 0));
             ka[i] = krow;
             ga[i] = p.A + (size_t)krow * p.lda + min(m0 + cc * 8, p.M - 8);
         }
@@ -175,7 +184,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
     for (int i = 0; i < B_CH; ++i) {
         int c = tid + i * NT;
         int krow = c / (BN / 8), cc = c - krow * (BN / 8);
-        sb_off[i] = A_BYTES + krow * SB + cc * 16;
+        sb_off[i] = A_BYTES + krow * SB + ((cc * 16) ^ (S::B_SWZ ? (krow & 3) << 6 : 0));
         kb[i] = krow;
         gb[i] = p.B + (size_t)krow * p.ldb + min(n0 + cc * 8, p.N - 8);
     }
@@ -222,11 +231,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
         if (A_KFAST)
             a_off[mi] = (wm * WM + mi * 32 + li) * SA + kg * 16;
         else
-            a_off[mi] = (8 * (grp >> 1) + (i16 >> 2)) * SA + (wm * WM + mi * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2;
+            a_off[mi] = (8 * (grp >> 1) + (i16 >> 2)) * SA +
+                        (((wm * WM + mi * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2) ^ (S::A_SWZ ? (i16 >> 2) << 6 : 0));
     }
+    // (every k-row a lane reads is its first one plus a multiple of 4, so its permutation is fixed)
 #pragma unroll
     for (int ni = 0; ni < TN; ++ni)
-        b_off[ni] = A_BYTES + (8 * (grp >> 1) + (i16 >> 2)) * SB + (wn * WN + ni * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2;
+        b_off[ni] = A_BYTES + (8 * (grp >> 1) + (i16 >> 2)) * SB +
+                    (((wn * WN + ni * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2) ^ (S::B_SWZ ? (i16 >> 2) << 6 : 0));
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -449,8 +461,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
                         int row = m0 + wm * WM + mi * 32 + g4 * 8 + kg * 4 + e;
                         if (row < p.M && col < p.N) {
                             float v = acc[mi][ni][g4 * 4 + e] * p.scale;
-                            if (EPI == EPI_F32) {
-                                float *Cz = reinterpret_cast<float *>(p.C) + (size_t)blockIdx.y * p.M * p.N;
+                            if (EPI == EPI_F32 || (EPI == EPI_PLAIN && !p.store_bf16)) {
+                                float *Cz = reinterpret_cast<float *>(p.C) + (size_t)slice * p.M * p.N;
                                 Cz[(size_t)row * p.N + col] = v;
                             } else {
                                 reinterpret_cast<unsigned short *>(p.C)[(size_t)row * p.N + col] =
@@ -460,6 +472,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
                     }
             }
     }
+}
+
+template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    gemm_body<BM, BN, WGM, WGN, PF, A_KFAST, EPI, LP>(p, blockIdx.x, blockIdx.y, smem);
 }
 
 template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
@@ -476,6 +495,59 @@ hipError_t launch_one(const Params &p, int splits, hipStream_t stream)
     }
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)splits);
     hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), LDS, stream, p);
+    return hipGetLastError();
+}
+
+// Two independent products in one launch: workgroups [0, blocks_first) run `first`, the rest run
+// `second`; inside each range the index is tile + tiles * slice.  A low-rank product alone leaves
+// compute units idle (a hundred-odd tiles on 256 units); launched together the two products of
+// Algorithm 1 (the weight gradient and the input gradient only share the read-only g^y) fill them
+// and save one launch gap.  Both bodies are the ones of the single-product kernels, so results are
+// bit-identical to separate launches.
+struct PairParams {
+    Params first, second;
+    int blocks_first;
+};
+
+template <int WGM, int WGN, int PF, int BM1, int BN1, bool KF1, int EPI1, int LP1, int BM2, int BN2, bool KF2,
+          int EPI2, int LP2>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_pair_kernel(PairParams pp)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int b = blockIdx.x;
+    if (b < pp.blocks_first) {
+        const int T = pp.first.tiles_m * pp.first.tiles_n;
+        const int z = b / T;
+        gemm_body<BM1, BN1, WGM, WGN, PF, KF1, EPI1, LP1>(pp.first, b - z * T, z, smem);
+    } else {
+        const int c = b - pp.blocks_first;
+        const int T = pp.second.tiles_m * pp.second.tiles_n;
+        const int z = c / T;
+        gemm_body<BM2, BN2, WGM, WGN, PF, KF2, EPI2, LP2>(pp.second, c - z * T, z, smem);
+    }
+}
+
+template <int WGM, int WGN, int PF, int BM1, int BN1, bool KF1, int EPI1, int LP1, int BM2, int BN2, bool KF2,
+          int EPI2, int LP2>
+hipError_t launch_pair(const Params &first, int splits_first, const Params &second, int splits_second,
+                       hipStream_t stream)
+{
+    constexpr int L1 = Smem<BM1, BN1, KF1>::TOTAL, L2 = Smem<BM2, BN2, KF2>::TOTAL;
+    constexpr int LDS = L1 > L2 ? L1 : L2;
+    auto kern = gemm_pair_kernel<WGM, WGN, PF, BM1, BN1, KF1, EPI1, LP1, BM2, BN2, KF2, EPI2, LP2>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    PairParams pp;
+    pp.first = first;
+    pp.second = second;
+    pp.blocks_first = first.tiles_m * first.tiles_n * splits_first;
+    const unsigned blocks = (unsigned)(pp.blocks_first + second.tiles_m * second.tiles_n * splits_second);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(64 * WGM * WGN), LDS, stream, pp);
     return hipGetLastError();
 }
 
@@ -515,5 +587,12 @@ hipError_t mfma_tile_256x256(const mfma::Params &p, bool a_kfast, GemmOut out, i
 hipError_t mfma_tile_128x128w8(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
 hipError_t mfma_tile_64x128w8(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
 hipError_t mfma_tile_64x64(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
+
+// Grouped launch of the input-gradient product `x` (A reduction-fast; tile 128x128 or 64x128 with 8
+// wavefronts: bm_x = 128 or 64; out_x as in launch_gemm, kUnproject needs patch 8) and the
+// weight-gradient product `w` (A reduction-slow, 128x128 tile with 8 wavefronts, fp32 or bf16 store
+// by w.store_bf16).  hipErrorInvalidValue for a combination that is not instantiated.
+hipError_t mfma_pair_w8(const mfma::Params &x, int bm_x, GemmOut out_x, int splits_x, const mfma::Params &w,
+                        int splits_w, hipStream_t s);
 
 }  // namespace lbp

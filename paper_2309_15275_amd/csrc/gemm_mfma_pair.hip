@@ -1,0 +1,33 @@
+// Instantiations of the grouped launch (input-gradient product + weight-gradient product in one
+// grid) for the 8-wavefront tiles the planner gives the low-rank products.
+#include "gemm_mfma_impl.h"
+namespace lbp {
+namespace {
+using namespace mfma;
+
+template <int BMX, int EPIX, int LPX>
+hipError_t pair(const Params &x, int splits_x, const Params &w, int splits_w, hipStream_t s)
+{
+    return launch_pair<2, 4, 2, BMX, 128, true, EPIX, LPX, 128, 128, false, EPI_PLAIN, 0>(x, splits_x, w, splits_w, s);
+}
+
+template <int BMX>
+hipError_t pair_bm(const Params &x, GemmOut out_x, int splits_x, const Params &w, int splits_w, hipStream_t s)
+{
+    if (out_x == GemmOut::kUnproject) {
+        if (splits_x != 1) return hipErrorInvalidValue;
+        if (x.mfma_epilogue) return pair<BMX, EPI_UNPROJECT_MFMA, 3>(x, 1, w, splits_w, s);
+        return pair<BMX, EPI_UNPROJECT, 3>(x, 1, w, splits_w, s);
+    }
+    return pair<BMX, EPI_PLAIN, 0>(x, splits_x, w, splits_w, s);
+}
+}  // namespace
+
+hipError_t mfma_pair_w8(const mfma::Params &x, int bm_x, GemmOut out_x, int splits_x, const mfma::Params &w,
+                        int splits_w, hipStream_t s)
+{
+    if (bm_x == 128) return pair_bm<128>(x, out_x, splits_x, w, splits_w, s);
+    if (bm_x == 64) return pair_bm<64>(x, out_x, splits_x, w, splits_w, s);
+    return hipErrorInvalidValue;
+}
+}  // namespace lbp

@@ -76,6 +76,13 @@ bool gemm_unproject_pooled(const BasisPlan &plan);
 
 hipError_t launch_gemm(const GemmArgs &g, GemmPath path, hipStream_t stream);
 
+// The two products of one backward call in a single launch (bf16 matrix-core path only): `x` is
+// the input-gradient product (A reduction-fast), `w` the weight-gradient product (A reduction-slow).
+// gemm_pair_supported says whether the tiles chosen for the two have a grouped kernel; results
+// are bit-identical to two launch_gemm calls.
+bool gemm_pair_supported(const GemmArgs &x, const GemmArgs &w, GemmPath path);
+hipError_t launch_gemm_pair(const GemmArgs &x, const GemmArgs &w, hipStream_t stream);
+
 // out[i] = scale * sum_z part[z][i], i < count (count % 4 == 0), written as `out_dtype`.
 hipError_t launch_splitk_reduce(const float *part, int splits, long count, float scale, void *out,
                                 int out_dtype, hipStream_t stream);

@@ -92,6 +92,13 @@ lbp::GemmPath gemm_path_from_env()
     return lbp::GemmPath::kAuto;
 }
 
+// LBP_GEMM_GROUP=0 keeps the two products of a backward call in separate launches (testing).
+bool group_from_env()
+{
+    const char *s = std::getenv("LBP_GEMM_GROUP");
+    return !(s && s[0] == '0' && s[1] == 0);
+}
+
 // LBP_FUSE_UNPROJECT: "0" keeps the reverse projection a kernel of its own, "1" fuses it into the
 // input-gradient product whenever the kernel supports the selection, unset lets the planner choose
 // (for testing and measurement).  Returns -1 when unset.
@@ -104,10 +111,6 @@ int fuse_unproject_from_env()
 
 // gW = scale * A^T-style product with split-K: direct store when one slice suffices and the
 // kernel can write the output type, otherwise fp32 partial sums and a fixed-order reduction.
-int weight_gradient(const void *A, const void *B, int Cout, int Cin, long K, int dtype, int gw_dtype,
-                    const lbp::GemmPlan &plan, float scale, float *part, void *gW, lbp::GemmPath gpath,
-                    hipStream_t s);
-
 lbp::WhtPath wht_path_from_env()
 {
     const char *s = std::getenv("LBP_WHT_PATH");
@@ -147,11 +150,12 @@ int validate_buffers(const void *x, const void *gy, const void *W, const lbp_sha
         if (e_ != hipSuccess) return hip_fail(e_);     \
     } while (0)
 
-int weight_gradient(const void *A, const void *B, int Cout, int Cin, long K, int dtype, int gw_dtype,
-                    const lbp::GemmPlan &plan, float scale, float *part, void *gW, lbp::GemmPath gpath,
-                    hipStream_t s)
+// Describes the weight-gradient product; returns true when it leaves fp32 partial sums in `part`
+// that launch_splitk_reduce still has to combine (scaled) into gW.
+bool weight_gradient_args(const void *A, const void *B, int Cout, int Cin, long K, int dtype, int gw_dtype,
+                          const lbp::GemmPlan &plan, float scale, float *part, void *gW, lbp::GemmPath gpath,
+                          lbp::GemmArgs *out)
 {
-    const int splits = plan.splits;
     lbp::GemmArgs g;
     g.tile = plan.tile;
     g.A = A; g.B = B;
@@ -160,20 +164,30 @@ int weight_gradient(const void *A, const void *B, int Cout, int Cin, long K, int
     g.a_kfast = false;
     g.dtype = dtype;
     const bool mfma = dtype == LBP_BF16 && gpath != lbp::GemmPath::kSimple;
-    if (splits == 1 && (gw_dtype == LBP_F32 || mfma)) {
+    const bool direct = plan.splits == 1 && (gw_dtype == LBP_F32 || mfma);
+    if (direct) {
         g.splits = 1;
         g.out = gw_dtype == LBP_F32 ? lbp::GemmOut::kF32 : lbp::GemmOut::kBF16;
         g.C = gW;
         g.scale = scale;
-        LBP_HIP(lbp::launch_gemm(g, gpath, s));
-        return LBP_OK;
+    } else {
+        g.splits = plan.splits;
+        g.out = lbp::GemmOut::kF32;
+        g.C = part;
+        g.scale = 1.0f;
     }
-    g.splits = splits;
-    g.out = lbp::GemmOut::kF32;
-    g.C = part;
-    g.scale = 1.0f;
+    *out = g;
+    return !direct;
+}
+
+int weight_gradient(const void *A, const void *B, int Cout, int Cin, long K, int dtype, int gw_dtype,
+                    const lbp::GemmPlan &plan, float scale, float *part, void *gW, lbp::GemmPath gpath,
+                    hipStream_t s)
+{
+    lbp::GemmArgs g;
+    const bool reduce = weight_gradient_args(A, B, Cout, Cin, K, dtype, gw_dtype, plan, scale, part, gW, gpath, &g);
     LBP_HIP(lbp::launch_gemm(g, gpath, s));
-    LBP_HIP(lbp::launch_splitk_reduce(part, splits, (long)Cout * Cin, scale, gW, gw_dtype, s));
+    if (reduce) LBP_HIP(lbp::launch_splitk_reduce(part, plan.splits, (long)Cout * Cin, scale, gW, gw_dtype, s));
     return LBP_OK;
 }
 
@@ -399,8 +413,10 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     const int fuse_env = fuse_unproject_from_env();
     const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
     lbp::WorkspacePlan ws;
+    // both gradients wanted: the two products may share one launch (not when timed stage by stage)
+    const bool allow_group = gx && gW && !ev && gpath != lbp::GemmPath::kSimple && group_from_env();
     rc = lbp::plan_workspace(shape, patch, r, st->num_cus, can_fuse, fuse_env == 1, &ws,
-                             !lbp::gemm_unproject_pooled(plan));
+                             !lbp::gemm_unproject_pooled(plan), allow_group);
     if (rc) return rc;
     char *base = nullptr;
     rc = get_workspace(st, ws.total, &base);
@@ -425,17 +441,15 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     else
         LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s));
     if (ev) LBP_HIP(hipEventRecord(ev[1], s));
-    if (gW) {
-        // g~w = g^w = g^y^T x^  (with the 1/p^2 of the normalisation)
-        rc = weight_gradient(gy_r, x_r, Cout, Cin, Mr, dt, shape->gw_dtype, ws.gw, inv_pp, part, gW,
-                             gpath, s);
-        if (rc) return rc;
-    }
-    if (ev) LBP_HIP(hipEventRecord(ev[2], s));
+    // g~w = g^w = g^y^T x^  (with the 1/p^2 of the normalisation)
+    lbp::GemmArgs gw_args, g;
+    bool gw_reduce = false;
+    if (gW)
+        gw_reduce = weight_gradient_args(gy_r, x_r, Cout, Cin, Mr, dt, shape->gw_dtype, ws.gw, inv_pp, part, gW,
+                                         gpath, &gw_args);
     if (gx) {
         // g^x = g^y w, then g~x = WHT^-1(g^x; I): fused into the product's epilogue when the
         // kernel supports the selection, else through an fp32 buffer and a kernel of its own
-        lbp::GemmArgs g;
         g.A = gy_r; g.B = W;
         g.M = (int)Mr; g.N = Cin; g.K = Cout;
         g.lda = Cout; g.ldb = Cin;
@@ -448,14 +462,25 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
             g.C = gx;
             g.grid_h = H; g.grid_w = Wd;
             g.plan = &plan;
-            LBP_HIP(lbp::launch_gemm(g, gpath, s));
         } else {
             g.splits = ws.gx.splits;
             g.out = lbp::GemmOut::kF32;
             g.C = gx_r;
-            LBP_HIP(lbp::launch_gemm(g, gpath, s));
-            LBP_HIP(lbp::launch_unproject(gx_r, ws.gx.splits, gx, N, H, Wd, Cin, dt, plan, path, s));
         }
+    }
+    // The two products are independent: one launch for both where a grouped kernel exists (not
+    // when the stages are timed one by one).
+    const bool grouped = ws.grouped && gW && gx && lbp::gemm_pair_supported(g, gw_args, gpath);
+    if (grouped)
+        LBP_HIP(lbp::launch_gemm_pair(g, gw_args, s));
+    else if (gW)
+        LBP_HIP(lbp::launch_gemm(gw_args, gpath, s));
+    if (gW && gw_reduce)
+        LBP_HIP(lbp::launch_splitk_reduce(part, ws.gw.splits, (long)Cout * Cin, inv_pp, gW, shape->gw_dtype, s));
+    if (ev) LBP_HIP(hipEventRecord(ev[2], s));
+    if (gx) {
+        if (!grouped) LBP_HIP(lbp::launch_gemm(g, gpath, s));
+        if (!ws.gx_fused) LBP_HIP(lbp::launch_unproject(gx_r, ws.gx.splits, gx, N, H, Wd, Cin, dt, plan, path, s));
     }
     if (ev) LBP_HIP(hipEventRecord(ev[3], s));
     return LBP_OK;

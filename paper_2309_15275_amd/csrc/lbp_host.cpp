@@ -166,7 +166,7 @@ const GemmTileInfo kGemmTiles[kNumGemmTiles] = {
 };
 
 GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split, int fused_r,
-                   int fused_patch, int num_cus, bool fused_wide)
+                   int fused_patch, int num_cus, bool fused_wide, int only_tile)
 {
     const double kFill = 20.0;            // bytes per clock a compute unit takes in from L2
     const double kClkPerUs = 2400.0;
@@ -176,6 +176,7 @@ GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split,
     GemmPlan best{0, 1, 1e300};
     for (int t = 0; t < kNumGemmTiles; ++t) {
         const GemmTileInfo &ti = kGemmTiles[t];
+        if (only_tile >= 0 && t != only_tile) continue;
         if (fused_r > 0 && (!ti.fused || fused_r > ti.bm)) continue;
         if (ti.max_n > 0 && N > ti.max_n) continue;
         if (fused_r > 0 && fused_wide && ti.bn != 128) continue;
@@ -208,10 +209,17 @@ GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split,
     return best;
 }
 
+long gemm_workgroups(const GemmPlan &g, long M, long N, int fused_r)
+{
+    const GemmTileInfo &ti = kGemmTiles[g.tile];
+    const long bm_step = fused_r > 0 ? ti.bm / fused_r * fused_r : ti.bm;
+    return ((M + bm_step - 1) / bm_step) * ((N + ti.bn - 1) / ti.bn) * g.splits;
+}
+
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
-                   bool force_fuse, WorkspacePlan *ws, bool fused_wide)
+                   bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group)
 {
     if (!s || !ws) return LBP_ERR_NULL;
     std::memset(ws, 0, sizeof *ws);
@@ -253,6 +261,40 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
         if (force_fuse || fused.est_us <= unfused.est_us) {
             ws->gx = fused;
             ws->gx_fused = true;
+        }
+    }
+    // Both products in one launch (kernels exist for the 8-wavefront tiles: 128 x 128 for gW, that
+    // or 64 x 128 for gx).  Measured on the benchmark layers: the grouped launch takes 0.65-0.9 of
+    // the two launches' sum while the two grids together are below about four workgroups per
+    // compute unit, and the better gx tile is the one that fills the chip once (else twice) with
+    // the most workgroups, else the larger tile.
+    if (allow_group && s->dtype == LBP_BF16 && (patch == 8 || !(can_fuse && ws->gx_fused))) {
+        const int kTileW = 4, kTileX[2] = {5, 4};       // indices into kGemmTiles
+        const bool fuse = can_fuse && patch == 8 && (ws->gx_fused || force_fuse || !fused_wide);
+        const GemmPlan w = plan_gemm(s->Cout, s->Cin, Mr, gw_bytes, true, 0, 0, num_cus, false, kTileW);
+        const long n_w = gemm_workgroups(w, s->Cout, s->Cin, 0);
+        GemmPlan x[2];
+        long n_x[2];
+        for (int i = 0; i < 2; ++i) {
+            x[i] = fuse ? plan_gemm(Mr, s->Cin, s->Cout, 2, false, r, patch, num_cus, fused_wide, kTileX[i])
+                        : plan_gemm(Mr, s->Cin, s->Cout, 4, false, 0, 0, num_cus, false, kTileX[i]);
+            n_x[i] = gemm_workgroups(x[i], Mr, s->Cin, fuse ? r : 0);
+        }
+        int pick;
+        if (n_w + n_x[0] <= num_cus) pick = 0;
+        else if (n_w + n_x[1] <= num_cus) pick = 1;
+        else if (n_w + n_x[0] <= 2 * num_cus) pick = 0;
+        else pick = 1;
+        double est = 0.85 * (w.est_us + x[pick].est_us);
+        if (!fuse) est += 8.0 + ((double)Mr * s->Cin * 4 + (double)M * s->Cin * esz) / 4.0e6;
+        const double launch_gap = 3.0;
+        if (w.est_us < 1e200 && x[pick].est_us < 1e200 && n_w + n_x[pick] <= 4L * num_cus &&
+            est < ws->gw.est_us + ws->gx.est_us + launch_gap) {
+            ws->gw = w;
+            ws->gx = x[pick];
+            ws->gx.est_us = est - w.est_us;
+            ws->gx_fused = fuse;
+            ws->grouped = true;
         }
     }
     ws->gy_r = off;

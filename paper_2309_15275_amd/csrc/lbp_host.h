@@ -98,8 +98,12 @@ struct GemmPlan {
 // flight, so a workgroup's time is its operand and output bytes over that rate (or its matrix-core
 // time if larger), and the workgroups run in ceil(count / compute units) rounds.
 // fused_wide: the fused epilogue is the matrix-core one, which needs a 128-column tile.
+// only_tile >= 0: consider that tile shape alone (est_us is 1e300 / clock when it cannot run the product).
 GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split, int fused_r,
-                   int fused_patch, int num_cus, bool fused_wide = false);
+                   int fused_patch, int num_cus, bool fused_wide = false, int only_tile = -1);
+
+// Workgroups the plan launches for an M x N output (fused_r as in plan_gemm).
+long gemm_workgroups(const GemmPlan &g, long M, long N, int fused_r);
 
 // Workspace layout of one backward call; offsets in bytes from the workspace base, each
 // 256-byte aligned.  Sizes of 0 mean "not used".
@@ -109,13 +113,15 @@ struct WorkspacePlan {
     GemmPlan gw;                       // the weight-gradient product
     GemmPlan gx;                       // the input-gradient product
     bool gx_fused;                     // reverse projection fused into that product's epilogue
+    bool grouped;                      // both products run in one launch (tiles chosen for that)
 };
 
 // num_cus: compute units of the device (the GEMM plans depend on it); pass 256 when unknown.
 // can_fuse: the selection allows the fused reverse projection (false gives the larger workspace);
-// force_fuse: take it whenever allowed instead of comparing estimates; fused_wide: see plan_gemm.
+// force_fuse: take it whenever allowed instead of comparing estimates; fused_wide: see plan_gemm;
+// allow_group: the caller wants both gradients and can launch the two products as one grid.
 int plan_workspace(const lbp_shape_t *shape, int patch, int r, int num_cus, bool can_fuse,
-                   bool force_fuse, WorkspacePlan *ws, bool fused_wide = false);
+                   bool force_fuse, WorkspacePlan *ws, bool fused_wide = false, bool allow_group = false);
 
 const char *status_string(int code);
 

@@ -2,6 +2,8 @@
 bench.py times (default paths, planner-chosen tiles).  Where the whole oracle takes seconds the
 comparison is element by element; at the larger sizes it is on sampled gx rows and gW entries
 that the oracle computes one by one, plus properties that hold at any size."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -18,6 +20,7 @@ def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     yield
+    os.environ.pop("LBP_GEMM_GROUP", None)
     torch.cuda.synchronize()
 
 
@@ -132,3 +135,32 @@ def test_rank_one_is_pool_matmul_upsample_at_full_size():
     g = gx.reshape(wl.N, wl.H // 8, 8, wl.W // 8, 8, wl.Cin)
     first = g[:, :, :1, :, :1, :]
     assert torch.equal(g, first.expand_as(g))
+
+
+# (workload, r, order): the planner runs both products of these in one launch, with, in turn, the
+# pooled fused epilogue, the matrix-core fused epilogue, few input-gradient tiles beside many
+# weight-gradient tiles, a split weight-gradient product, and zero-padded maps.
+GROUPED = [("cfg2_vitb_fc1", 8, "l1"), ("cfg2_vitb_fc1", 15, "l1"), ("cfg4_vitl_fc1", 4, "l1"),
+           ("cfg4_vitl_fc1", 16, "l1"), ("cfg5_vitb_attnproj", 4, "l1"), ("pad_7x7_fc2", 8, "l1")]
+
+
+@pytest.mark.parametrize("case", range(len(GROUPED)))
+def test_grouped_and_separate_launches_of_the_products_agree(case):
+    # the planner may give the two modes different tiles, so the comparison between them is by
+    # norm (bit equality under equal tiles is tested on the small shapes); both must match the oracle
+    name, r, order = GROUPED[case]
+    wl = workloads.WORKLOADS[name]
+    host, dev = device_inputs(wl)
+    idx = oracle.select_bases(wl.patch, r, order)
+    os.environ["LBP_GEMM_GROUP"] = "0"
+    gx0, gW0 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], wl.patch, idx)
+    os.environ.pop("LBP_GEMM_GROUP")
+    gx1, gW1 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], wl.patch, idx)
+    assert rel_fro(to_host(gx1), to_host(gx0)) <= TOL["bf16"] and rel_fro(to_host(gW1), to_host(gW0)) <= 1e-5
+    for gx, gW in ((gx0, gW0), (gx1, gW1)):
+        if wl.H % wl.patch or wl.W % wl.patch:
+            gxo, gWo = oracle.lbp_wht_backward_padded(host["x"], host["gy"], host["w"], wl.patch, idx)
+            egx, egw = rel_fro(to_host(gx), gxo), rel_fro(to_host(gW), gWo)
+        else:
+            egx, egw = check_sampled(wl, host, gx, gW, idx, 77 + case)
+        assert egx <= TOL["bf16"] and egw <= TOL["bf16"], (egx, egw)

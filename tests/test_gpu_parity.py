@@ -21,7 +21,7 @@ def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     yield
-    for var in ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT", "LBP_GEMM_TILE"):
+    for var in ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT", "LBP_GEMM_TILE", "LBP_GEMM_GROUP"):
         os.environ.pop(var, None)
     torch.cuda.synchronize()
 
@@ -254,6 +254,26 @@ def test_every_gemm_tile_shape_matches_oracle(case, tile):
     gx, gW = binding.full_bp_backward(dev["x"], dev["gy"], dev["w"])
     gx0, gW0 = oracle.full_bp_backward(host["x"], host["gy"], host["w"])
     assert rel_fro(to_host(gx), gx0) <= 5e-3 and rel_fro(to_host(gW), gW0) <= 5e-3
+
+
+@pytest.mark.parametrize("fuse", ["1", "0"])
+@pytest.mark.parametrize("case", [0, 3, 5, 10, 13])
+def test_grouped_launch_on_ragged_shapes(case, fuse):
+    # tile 4 for both products is a pair the grouped kernel covers: one launch runs both; the
+    # result must equal the separate launches bit for bit and the oracle within tolerance
+    N, H, W, Cin, Cout, patch, r, order = RAGGED[case]
+    wl = small("group", N, H, W, Cin, Cout, patch, "bf16", 430 + case)
+    idx = oracle.select_bases(patch, r, order)
+    host, dev = device_inputs(wl)
+    os.environ["LBP_GEMM_TILE"], os.environ["LBP_FUSE_UNPROJECT"] = "4", fuse
+    os.environ["LBP_GEMM_GROUP"] = "0"
+    gx0, gW0 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx)
+    os.environ["LBP_GEMM_GROUP"] = "1"
+    gx1, gW1 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx)
+    assert torch.equal(gx0.view(torch.int16), gx1.view(torch.int16))
+    assert torch.equal(gW0.view(torch.int32), gW1.view(torch.int32))
+    gxo, gWo = oracle.lbp_wht_backward(host["x"], host["gy"], host["w"], patch, idx)
+    assert rel_fro(to_host(gx1), gxo) <= TOL["bf16"] and rel_fro(to_host(gW1), gWo) <= TOL["bf16"]
 
 
 def test_split_k_partial_sums_feed_the_reverse_projection():
