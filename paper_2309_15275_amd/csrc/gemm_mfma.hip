@@ -113,6 +113,13 @@ hipError_t prepare(const GemmArgs &a, int *tile_out, mfma::Params *out, int *lp_
 // Tiles of the grouped launch: 128x128 with 8 wavefronts for the weight gradient, that or 64x128
 // with 8 wavefronts for the input gradient.
 constexpr int kPairTileW = 4, kPairTileX0 = 4, kPairTileX1 = 5;
+// ... and 64x64 for both on thin layers
+constexpr int kPairTileThin = 6;
+
+bool pair_tiles_ok(int tx, int tw)
+{
+    return (tw == kPairTileW && (tx == kPairTileX0 || tx == kPairTileX1)) || (tw == kPairTileThin && tx == kPairTileThin);
+}
 
 }  // namespace
 
@@ -134,7 +141,8 @@ bool gemm_pair_supported(const GemmArgs &x, const GemmArgs &w, GemmPath path)
     int tx, tw, lp;
     mfma::Params p;
     if (prepare(x, &tx, &p, &lp) != hipSuccess || prepare(w, &tw, &p, &lp) != hipSuccess) return false;
-    return tw == kPairTileW && (tx == kPairTileX0 || tx == kPairTileX1);
+    if (tw == kPairTileThin && x.out == GemmOut::kUnproject && !gemm_unproject_pooled(*x.plan)) return false;
+    return pair_tiles_ok(tx, tw);
 }
 
 hipError_t launch_gemm_pair(const GemmArgs &x, const GemmArgs &w, hipStream_t stream)
@@ -145,9 +153,10 @@ hipError_t launch_gemm_pair(const GemmArgs &x, const GemmArgs &w, hipStream_t st
     if (e != hipSuccess) return e;
     e = prepare(w, &tw, &pw, &lpw);
     if (e != hipSuccess) return e;
-    if (tw != kPairTileW || (tx != kPairTileX0 && tx != kPairTileX1) || !x.a_kfast || w.a_kfast ||
-        w.out == GemmOut::kUnproject || (x.out == GemmOut::kUnproject && lpx != 3))
+    if (!pair_tiles_ok(tx, tw) || !x.a_kfast || w.a_kfast || w.out == GemmOut::kUnproject ||
+        (x.out == GemmOut::kUnproject && lpx != 3))
         return hipErrorInvalidValue;
+    if (tw == kPairTileThin) return mfma_pair_64x64(px, x.out, x.splits, pw, w.splits, stream);
     return mfma_pair_w8(px, kGemmTiles[tx].bm, x.out, x.splits, pw, w.splits, stream);
 }
 

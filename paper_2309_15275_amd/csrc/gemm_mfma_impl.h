@@ -594,5 +594,8 @@ hipError_t mfma_tile_64x64(const mfma::Params &p, bool a_kfast, GemmOut out, int
 // by w.store_bf16).  hipErrorInvalidValue for a combination that is not instantiated.
 hipError_t mfma_pair_w8(const mfma::Params &x, int bm_x, GemmOut out_x, int splits_x, const mfma::Params &w,
                         int splits_w, hipStream_t s);
+// The same for 64 x 64 tiles with 4 wavefronts on both products (pooled fused epilogue only).
+hipError_t mfma_pair_64x64(const mfma::Params &x, GemmOut out_x, int splits_x, const mfma::Params &w, int splits_w,
+                           hipStream_t s);
 
 }  // namespace lbp

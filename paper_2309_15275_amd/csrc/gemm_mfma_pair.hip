@@ -1,5 +1,6 @@
 // Instantiations of the grouped launch (input-gradient product + weight-gradient product in one
-// grid) for the 8-wavefront tiles the planner gives the low-rank products.
+// grid) for the tiles the planner gives the low-rank products: the 8-wavefront ones, and 64 x 64
+// for layers with few channels.
 #include "gemm_mfma_impl.h"
 namespace lbp {
 namespace {
@@ -22,6 +23,17 @@ hipError_t pair_bm(const Params &x, GemmOut out_x, int splits_x, const Params &w
     return pair<BMX, EPI_PLAIN, 0>(x, splits_x, w, splits_w, s);
 }
 }  // namespace
+
+// thin layers: 64 x 64 tiles with 4 wavefronts for both products
+hipError_t mfma_pair_64x64(const mfma::Params &x, GemmOut out_x, int splits_x, const mfma::Params &w, int splits_w,
+                           hipStream_t s)
+{
+    if (out_x == GemmOut::kUnproject) {
+        if (splits_x != 1 || x.mfma_epilogue) return hipErrorInvalidValue;
+        return launch_pair<2, 2, 2, 64, 64, true, EPI_UNPROJECT, 3, 64, 64, false, EPI_PLAIN, 0>(x, 1, w, splits_w, s);
+    }
+    return launch_pair<2, 2, 2, 64, 64, true, EPI_PLAIN, 0, 64, 64, false, EPI_PLAIN, 0>(x, splits_x, w, splits_w, s);
+}
 
 hipError_t mfma_pair_w8(const mfma::Params &x, int bm_x, GemmOut out_x, int splits_x, const mfma::Params &w,
                         int splits_w, hipStream_t s)

@@ -264,12 +264,13 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
         }
     }
     // Both products in one launch (kernels exist for the 8-wavefront tiles: 128 x 128 for gW, that
-    // or 64 x 128 for gx).  Measured on the benchmark layers: the grouped launch takes 0.65-0.9 of
+    // or 64 x 128 for gx; and for 64 x 64 tiles on layers with few channels).  Measured on the benchmark layers: the grouped launch takes 0.65-0.9 of
     // the two launches' sum while the two grids together are below about four workgroups per
     // compute unit, and the better gx tile is the one that fills the chip once (else twice) with
     // the most workgroups, else the larger tile.
     if (allow_group && s->dtype == LBP_BF16 && (patch == 8 || !(can_fuse && ws->gx_fused))) {
-        const int kTileW = 4, kTileX[2] = {5, 4};       // indices into kGemmTiles
+        const bool thin = s->Cin <= 64;                  // 64 x 64 tiles for both
+        const int kTileW = thin ? 6 : 4, kTileX[2] = {thin ? 6 : 5, thin ? 6 : 4};       // indices into kGemmTiles
         const bool fuse = can_fuse && patch == 8 && (ws->gx_fused || force_fuse || !fused_wide);
         const GemmPlan w = plan_gemm(s->Cout, s->Cin, Mr, gw_bytes, true, 0, 0, num_cus, false, kTileW);
         const long n_w = gemm_workgroups(w, s->Cout, s->Cin, 0);

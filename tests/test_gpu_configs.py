@@ -139,9 +139,10 @@ def test_rank_one_is_pool_matmul_upsample_at_full_size():
 
 # (workload, r, order): the planner runs both products of these in one launch, with, in turn, the
 # pooled fused epilogue, the matrix-core fused epilogue, few input-gradient tiles beside many
-# weight-gradient tiles, a split weight-gradient product, and zero-padded maps.
+# weight-gradient tiles, a split weight-gradient product, zero-padded maps, and a thin layer.
 GROUPED = [("cfg2_vitb_fc1", 8, "l1"), ("cfg2_vitb_fc1", 15, "l1"), ("cfg4_vitl_fc1", 4, "l1"),
-           ("cfg4_vitl_fc1", 16, "l1"), ("cfg5_vitb_attnproj", 4, "l1"), ("pad_7x7_fc2", 8, "l1")]
+           ("cfg4_vitl_fc1", 16, "l1"), ("cfg5_vitb_attnproj", 4, "l1"), ("pad_7x7_fc2", 8, "l1"),
+           ("cfg3_effformer_early", 8, "l1")]
 
 
 @pytest.mark.parametrize("case", range(len(GROUPED)))

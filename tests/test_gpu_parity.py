@@ -256,16 +256,17 @@ def test_every_gemm_tile_shape_matches_oracle(case, tile):
     assert rel_fro(to_host(gx), gx0) <= 5e-3 and rel_fro(to_host(gW), gW0) <= 5e-3
 
 
+@pytest.mark.parametrize("tile", ["4", "6"])
 @pytest.mark.parametrize("fuse", ["1", "0"])
 @pytest.mark.parametrize("case", [0, 3, 5, 10, 13])
-def test_grouped_launch_on_ragged_shapes(case, fuse):
-    # tile 4 for both products is a pair the grouped kernel covers: one launch runs both; the
+def test_grouped_launch_on_ragged_shapes(case, fuse, tile):
+    # tiles 4 and 6 for both products are pairs the grouped kernel covers: one launch runs both; the
     # result must equal the separate launches bit for bit and the oracle within tolerance
     N, H, W, Cin, Cout, patch, r, order = RAGGED[case]
     wl = small("group", N, H, W, Cin, Cout, patch, "bf16", 430 + case)
     idx = oracle.select_bases(patch, r, order)
     host, dev = device_inputs(wl)
-    os.environ["LBP_GEMM_TILE"], os.environ["LBP_FUSE_UNPROJECT"] = "4", fuse
+    os.environ["LBP_GEMM_TILE"], os.environ["LBP_FUSE_UNPROJECT"] = tile, fuse
     os.environ["LBP_GEMM_GROUP"] = "0"
     gx0, gW0 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx)
     os.environ["LBP_GEMM_GROUP"] = "1"
