@@ -138,6 +138,29 @@ int lbp_wht_backward_preprojected(const void *x_r, const void *gy, const void *W
                                   void *gx, void *gW, void *stream);
 
 /*
+ * Token sequences with tokens that are not on the grid.  A ViT layer sees, per image, `extra` tokens
+ * (a class token, a distillation token) followed by the H*W patch tokens: x, gy and gx are
+ * [N][extra + H*W][C] here.  Algorithm 1 is stated for the H x W map; the paper does not say what
+ * happens to the others.  This library keeps them exact: a token outside the grid belongs to no
+ * patch, its row of gx is g_y,row W and its outer product g_y,row^T x_row is added to gW (its share of
+ * Eq. 2); the grid tokens go through Algorithm 1 as in lbp_wht_backward.  extra = 0 is
+ * lbp_wht_backward itself.  shape->H, shape->W describe the grid only.
+ *
+ * lbp_wht_project_tokens is the forward-pass half for x: out is [P*r + N*extra][C], the projected grid
+ * (as lbp_wht_project) followed by the extra tokens unchanged, image-major; that tensor is the x_r of
+ * lbp_wht_backward_tokens_preprojected.  LBP_ERR_SHAPE for a negative `extra`.
+ */
+int lbp_wht_backward_tokens(const void *x, const void *gy, const void *W, const lbp_shape_t *shape, int extra,
+                            int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream);
+int lbp_wht_project_tokens(const void *in, int N, int H, int W, int extra, int C, int dtype, int patch,
+                           const int32_t *basis_idx, int r, void *out, void *stream);
+int lbp_wht_backward_tokens_preprojected(const void *x_r, const void *gy, const void *W, const lbp_shape_t *shape,
+                                         int extra, int patch, const int32_t *basis_idx, int r, void *gx, void *gW,
+                                         void *stream);
+/* Workspace of the three calls above (lbp_wht_workspace_bytes with `extra` tokens per image). */
+size_t lbp_wht_workspace_bytes_tokens(const lbp_shape_t *shape, int extra, int patch, int r);
+
+/*
  * For measurement, not part of the method: the same call as lbp_wht_backward, bracketed by HIP
  * events on `stream`.  It WAITS for the work to finish and returns the elapsed milliseconds of the
  * three stages in stage_ms (host, 3 floats): [0] projection of gy and x, [1] weight-gradient

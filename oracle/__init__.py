@@ -26,6 +26,7 @@ from .lbp_oracle import (  # noqa: F401
     unproject_padded,
     lbp_wht_backward_padded,
     wht_energy_padded,
+    lbp_wht_backward_tokens,
     max_threads,
     set_threads,
 )

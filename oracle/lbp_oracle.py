@@ -259,6 +259,38 @@ def wht_energy_padded(X, p):
     return wht_energy(pad_grid(X, p), p)
 
 
+# --------------------------------------------------------------------------------------------
+# Token sequences with tokens that are not on the grid.  A ViT layer sees [class token, H*W
+# patch tokens] (a distilled model one more); Algorithm 1 is stated for the H x W map only and
+# the paper does not say what happens to the others.  The reading taken here: a token outside
+# the grid belongs to no patch, so nothing is projected for it and its part of Eq. 2 is kept
+# exactly: its row of g~x is g_y,row w, and its outer product g_y,row^T x_row is added to g~w.
+# The grid tokens go through Algorithm 1 (zero-padded if the grid is not a multiple of p).
+# --------------------------------------------------------------------------------------------
+
+def lbp_wht_backward_tokens(x, gy, w, grid, p, idx, want_gx=True, want_gw=True):
+    """x [N,T,Cin], gy [N,T,Cout] with T = extra + H*W, the extra tokens first; grid = (H, W)."""
+    x, gy, w = _f64(x), _f64(gy), _f64(w)
+    N, T, Cin = x.shape
+    H, W = grid
+    extra = T - H * W
+    if extra < 0 or gy.shape[:2] != (N, T):
+        raise ValueError("token count does not match the grid")
+    xg = np.ascontiguousarray(x[:, extra:, :]).reshape(N, H, W, Cin)
+    gyg = np.ascontiguousarray(gy[:, extra:, :]).reshape(N, H, W, gy.shape[2])
+    gxg, gW = lbp_wht_backward_padded(xg, gyg, w, p, idx, want_gx, want_gw)
+    gx = None
+    if want_gx:
+        gx = np.empty_like(x)
+        gx[:, extra:, :] = gxg.reshape(N, H * W, Cin)
+        gx[:, :extra, :] = gy[:, :extra, :] @ w                    # Eq. 2 for the tokens outside the grid
+    if want_gw:
+        ge = gy[:, :extra, :].reshape(N * extra, gy.shape[2])
+        xe = x[:, :extra, :].reshape(N * extra, Cin)
+        gW = gW + ge.T @ xe                                        # their share of Eq. 2's sum over tokens
+    return gx, gW
+
+
 def flop_model(Cx, Cy, L, r):
     """Table 1: dict of FLOPs for vanilla BP, projection, low-rank matmuls, reverse projection."""
     out = (ctypes.c_double * 4)()

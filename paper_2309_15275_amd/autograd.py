@@ -7,7 +7,10 @@ activation is r/patch^2 of x.  Backward: the library's lbp_wht_backward_preproje
 g~x and g~w from x^, g_y and w; there is no fallback if the library is missing.  The bias gradient
 is the exact column sum of g_y (the paper's layer has no bias, Section 2).
 
-Tensors are token-major: x [N, H, W, Cin] (or [N, H*W, Cin] with `grid=(H, W)`), float32 or bfloat16.
+Tensors are token-major: x [N, H, W, Cin], or a token sequence [N, T, Cin] with `grid=(H, W)` whose
+last H*W tokens are the grid; T - H*W leading tokens (a class token) are not on the grid and are
+treated exactly (their rows of the input gradient and their share of the weight gradient are those
+of Eq. 2).  float32 or bfloat16.
 """
 import torch
 
@@ -40,8 +43,40 @@ class _LbpWhtLinearFn(torch.autograd.Function):
         return gx, gW, gb, None, None
 
 
-def lbp_wht_linear(x, weight, bias, patch, basis_idx):
-    """Functional form: y = x w^T + b with the LBP-WHT backward."""
+class _LbpWhtLinearTokensFn(torch.autograd.Function):
+    """The same for token sequences [N, T, Cin] with T - H*W tokens in front of the grid."""
+
+    @staticmethod
+    def forward(ctx, x, weight, bias, patch, basis_idx, grid):
+        if x.dim() != 3:
+            raise ValueError("x must be [N, T, Cin]")
+        xc = x.detach().contiguous()
+        y = torch.nn.functional.linear(xc, weight, bias)
+        ctx.save_for_backward(binding.wht_project_tokens(xc, grid, patch, basis_idx), weight)
+        ctx.lbp = (int(patch), tuple(int(v) for v in basis_idx), bias is not None, (int(grid[0]), int(grid[1])))
+        return y
+
+    @staticmethod
+    def backward(ctx, gy):
+        x_r, weight = ctx.saved_tensors
+        patch, basis_idx, has_bias, grid = ctx.lbp
+        gy = gy.contiguous()
+        want_gx, want_gw = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
+        gx = gW = None
+        if want_gx or want_gw:
+            gx, gW = binding.lbp_wht_backward_tokens_preprojected(
+                x_r, gy, weight.detach(), grid, patch, basis_idx, want_gx=want_gx, want_gw=want_gw,
+                gw_dtype=weight.dtype)
+        gb = gy.sum(dim=(0, 1)) if has_bias and ctx.needs_input_grad[2] else None
+        return gx, gW, gb, None, None, None
+
+
+def lbp_wht_linear(x, weight, bias, patch, basis_idx, grid=None):
+    """Functional form: y = x w^T + b with the LBP-WHT backward.  x [N,H,W,Cin], or [N,T,Cin] with grid=(H,W)."""
+    if x.dim() == 3:
+        if grid is None:
+            raise ValueError("a [N, T, C] input needs grid=(H, W)")
+        return _LbpWhtLinearTokensFn.apply(x, weight, bias, patch, basis_idx, grid)
     return _LbpWhtLinearFn.apply(x, weight, bias, patch, basis_idx)
 
 
@@ -64,11 +99,8 @@ class LBPWHTLinear(torch.nn.Module):
     def forward(self, x, grid=None):
         if x.dim() == 3:
             if grid is None:
-                raise ValueError("a [N, L, C] input needs grid=(H, W)")
-            N, L, C = x.shape
-            if grid[0] * grid[1] != L:
-                raise ValueError("grid does not match the token count")
-            y = lbp_wht_linear(x.reshape(N, grid[0], grid[1], C), self.weight, self.bias, self.patch,
-                               self.basis_idx)
-            return y.reshape(N, L, self.out_features)
+                raise ValueError("a [N, T, C] input needs grid=(H, W)")
+            if grid[0] * grid[1] > x.shape[1]:
+                raise ValueError("fewer tokens than the grid holds")
+            return lbp_wht_linear(x, self.weight, self.bias, self.patch, self.basis_idx, grid)
         return lbp_wht_linear(x, self.weight, self.bias, self.patch, self.basis_idx)

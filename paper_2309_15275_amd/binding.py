@@ -19,7 +19,9 @@ _DTYPES = {torch.float32: LBP_F32, torch.bfloat16: LBP_BF16}
 # every symbol include/lbp_wht.h declares
 EXPORTS = ("lbp_wht_select_bases", "lbp_wht_select_lhe", "lbp_wht_energy", "lbp_wht_energy_workspace_bytes", "lbp_wht_backward", "lbp_wht_backward_preprojected", "lbp_wht_backward_profile", "full_bp_backward", "lbp_wht_project",
            "lbp_wht_project_pair", "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
-           "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version")
+           "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version",
+           "lbp_wht_backward_tokens", "lbp_wht_project_tokens", "lbp_wht_backward_tokens_preprojected",
+           "lbp_wht_workspace_bytes_tokens")
 
 
 class LbpShape(ctypes.Structure):
@@ -62,6 +64,11 @@ def load():
     lib.lbp_wht_project.argtypes = [vp] + [ctypes.c_int] * 6 + [i32p, ctypes.c_int, vp, vp]
     lib.lbp_wht_unproject.argtypes = [vp] + [ctypes.c_int] * 6 + [i32p, ctypes.c_int, vp, vp]
     lib.lbp_wht_project_pair.argtypes = [vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.lbp_wht_backward_tokens.argtypes = [vp, vp, vp, shp, ctypes.c_int, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.lbp_wht_backward_tokens_preprojected.argtypes = lib.lbp_wht_backward_tokens.argtypes
+    lib.lbp_wht_project_tokens.argtypes = [vp] + [ctypes.c_int] * 7 + [i32p, ctypes.c_int, vp, vp]
+    lib.lbp_wht_workspace_bytes_tokens.argtypes = [shp, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    lib.lbp_wht_workspace_bytes_tokens.restype = ctypes.c_size_t
     lib.lbp_wht_workspace_bytes.argtypes = [shp, ctypes.c_int, ctypes.c_int]
     lib.lbp_wht_workspace_bytes.restype = ctypes.c_size_t
     lib.lbp_set_workspace.argtypes = [vp, ctypes.c_size_t]
@@ -198,6 +205,76 @@ def lbp_wht_backward_preprojected(x_r, gy, w, patch, basis_idx, gx=None, gW=None
     return gx, gW
 
 
+def _token_shape(t, gy, w, grid, gw_dtype):
+    """LbpShape and the number of extra tokens of sequences t/gy [N, T, C] whose last H*W tokens are the grid."""
+    N, T = gy.shape[:2]
+    H, W = grid
+    Cout, Cin = w.shape
+    extra = T - H * W
+    if gy.dim() != 3 or extra < 0 or gy.shape[2] != Cout:
+        raise ValueError("gy must be [N, extra + H*W, Cout] with grid = (H, W)")
+    return LbpShape(N, H, W, Cin, Cout, _DTYPES[gy.dtype], _DTYPES[gw_dtype]), extra
+
+
+def lbp_wht_backward_tokens(x, gy, w, grid, patch, basis_idx, gx=None, gW=None, want_gx=True, want_gw=True,
+                            gw_dtype=torch.float32, stream=None):
+    """Algorithm 1 on token sequences x [N,T,Cin], gy [N,T,Cout] whose last H*W tokens are the
+    grid = (H, W); the T - H*W leading tokens (class token ...) are treated exactly.  Returns (gx, gW)."""
+    shape, extra = _token_shape(x, gy, w, grid, gw_dtype)
+    if tuple(x.shape) != (shape.N, gy.shape[1], shape.Cin):
+        raise ValueError("x must be [N, T, Cin]")
+    if want_gx and gx is None:
+        gx = torch.empty_like(x)
+    if want_gw and gW is None:
+        gW = torch.empty(w.shape, dtype=gw_dtype, device=w.device)
+    idx, r = _idx_array(basis_idx)
+    with torch.cuda.device(x.device):
+        _check(load().lbp_wht_backward_tokens(
+            _dev_tensor(x, "x"), _dev_tensor(gy, "gy", x.dtype), _dev_tensor(w, "w", x.dtype),
+            ctypes.byref(shape), extra, int(patch), idx, r,
+            _dev_tensor(gx, "gx", x.dtype) if gx is not None else None,
+            _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
+    return gx, gW
+
+
+def wht_project_tokens(t, grid, patch, basis_idx, out=None, stream=None):
+    """Forward-pass half for x [N,T,C]: the projected grid [P*r, C] followed by the T - H*W leading
+    tokens of every image unchanged -> [P*r + N*extra, C]."""
+    N, T, C = t.shape
+    H, W = grid
+    extra = T - H * W
+    if extra < 0:
+        raise ValueError("fewer tokens than the grid holds")
+    idx, r = _idx_array(basis_idx)
+    if out is None:
+        out = torch.empty((patch_count(N, H, W, patch) * r + N * extra, C), dtype=t.dtype, device=t.device)
+    with torch.cuda.device(t.device):
+        _check(load().lbp_wht_project_tokens(_dev_tensor(t, "t"), N, H, W, extra, C, _DTYPES[t.dtype], int(patch),
+                                             idx, r, _dev_tensor(out, "out", t.dtype), _stream_ptr(stream)))
+    return out
+
+
+def lbp_wht_backward_tokens_preprojected(x_r, gy, w, grid, patch, basis_idx, gx=None, gW=None, want_gx=True,
+                                         want_gw=True, gw_dtype=torch.float32, stream=None):
+    """lbp_wht_backward_tokens with x_r = wht_project_tokens(x) kept from the forward pass."""
+    shape, extra = _token_shape(None, gy, w, grid, gw_dtype)
+    idx, r = _idx_array(basis_idx)
+    rows = patch_count(shape.N, shape.H, shape.W, patch) * r + shape.N * extra
+    if tuple(x_r.shape) != (rows, shape.Cin):
+        raise ValueError("x_r must be [P*r + N*extra, Cin]")
+    if want_gx and gx is None:
+        gx = torch.empty((shape.N, gy.shape[1], shape.Cin), dtype=gy.dtype, device=gy.device)
+    if want_gw and gW is None:
+        gW = torch.empty(w.shape, dtype=gw_dtype, device=w.device)
+    with torch.cuda.device(gy.device):
+        _check(load().lbp_wht_backward_tokens_preprojected(
+            _dev_tensor(x_r, "x_r", gy.dtype), _dev_tensor(gy, "gy"), _dev_tensor(w, "w", gy.dtype),
+            ctypes.byref(shape), extra, int(patch), idx, r,
+            _dev_tensor(gx, "gx", gy.dtype) if gx is not None else None,
+            _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
+    return gx, gW
+
+
 def lbp_wht_backward_profile(x, gy, w, patch, basis_idx, gx, gW, stream=None):
     """lbp_wht_backward bracketed by HIP events; waits, returns the three stage times in ms:
     (projection, weight-gradient product, input-gradient product + reverse projection)."""
@@ -273,8 +350,8 @@ def wht_unproject(coef, shape, dtype, patch, basis_idx, out=None, stream=None):
     return out
 
 
-def workspace_bytes(shape, patch, r):
-    return int(load().lbp_wht_workspace_bytes(ctypes.byref(shape), int(patch), int(r)))
+def workspace_bytes(shape, patch, r, extra=0):
+    return int(load().lbp_wht_workspace_bytes_tokens(ctypes.byref(shape), int(extra), int(patch), int(r)))
 
 
 def set_workspace(buf):

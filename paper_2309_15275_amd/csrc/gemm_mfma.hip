@@ -100,8 +100,13 @@ hipError_t prepare(const GemmArgs &a, int *tile_out, mfma::Params *out, int *lp_
         for (int k = 0; k < 64; ++k) p.nat[k] = k < bp.r ? (unsigned char)bp.nat[k] : (unsigned char)0;
         p.sel.mask = bp.pooled_mask;
         for (int j = 0; j < 64; ++j) p.sel.pos[j] = bp.pooled_pos[j];
-        p.geom = make_geom(a.grid_h, a.grid_w, bp.patch);
-        p.Q = a.M / bp.r;     // = patches of the zero-padded grids
+        if (a.extra_rows < 0 || a.extra_rows > a.M || (a.extra_rows > 0 && (a.extra < 1 || a.extra_rows % a.extra)) ||
+            (a.M - a.extra_rows) % bp.r)
+            return hipErrorInvalidValue;
+        p.geom = make_geom(a.grid_h, a.grid_w, bp.patch, a.extra);
+        p.Q = (a.M - a.extra_rows) / bp.r;     // = patches of the zero-padded grids
+        p.extra_rows = a.extra_rows;
+        p.extra = a.extra > 0 ? a.extra : 1;
     }
     p.tiles_m = (a.M + p.bm_step - 1) / p.bm_step;
     *tile_out = tile;

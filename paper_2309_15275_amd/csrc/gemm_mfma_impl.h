@@ -56,6 +56,8 @@ struct Params {
     PooledSel sel;
     int r, mh, mw;
     long Q;               // number of patches
+    int extra_rows;       // rows of A after the Q*r (patch, basis) rows: tokens outside the grid, extra per image
+    int extra;            // such tokens per image; their rows of the product are stored scaled by 1/patch^2
     unsigned char nat[64];   // natural (Sylvester) index of every selected basis (matrix-core epilogue, patch 8)
     int mfma_epilogue;    // 1: the selection cannot be pooled, Eq. 7 runs on the matrix cores in the epilogue
     int store_bf16;       // EPI_PLAIN: 1 stores bf16, 0 stores fp32 (slice by slice)
@@ -91,7 +93,7 @@ __device__ __forceinline__ void unproject_tile(const float *ct, int cts, const P
         long img;
         int a0, b0;
         p.geom.origin(q, img, a0, b0);
-        uint32_t *dst = reinterpret_cast<uint32_t *>(p.C) + ((size_t)img * p.geom.HWt + (size_t)a0 * p.geom.Wt + b0) * Cd + (n0 >> 1) + cp;
+        uint32_t *dst = reinterpret_cast<uint32_t *>(p.C) + p.geom.token(img, a0, b0) * Cd + (n0 >> 1) + cp;
         const int hv = p.geom.Ht - a0, wv = p.geom.Wt - b0;     // tokens of the patch inside the grid (>= P: all)
         if (hv >= P && wv >= P) {                 // the whole patch is inside the grid
 #pragma unroll
@@ -114,6 +116,16 @@ __device__ __forceinline__ void unproject_tile(const float *ct, int cts, const P
             }
         }
     }
+}
+
+// Rows [lo, hi) of the tile that belong to tokens outside the grid (global row >= Q*r): empty
+// for all but the last tiles.
+__device__ __forceinline__ void extra_row_range(const Params &p, int m0, int &lo, int &hi)
+{
+    const long first = p.Q * p.r;
+    const long l = first - m0, h = (long)p.M - m0;
+    lo = l < 0 ? 0 : (int)(l < p.bm_step ? l : p.bm_step);
+    hi = (int)(h < p.bm_step ? h : p.bm_step);
 }
 
 // LDS layout of one stage.  A reduction-slow operand keeps its rows [k][row]; the transposing reads
@@ -405,7 +417,7 @@ __device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, co
             int a0, b0;
             p.geom.origin(q, img, a0, b0);
             unsigned short *dst = reinterpret_cast<unsigned short *>(p.C) +
-                                  ((size_t)img * p.geom.HWt + (size_t)a0 * p.geom.Wt + b0) * p.N + n0;
+                                  p.geom.token(img, a0, b0) * p.N + n0;
             const int hv = p.geom.Ht - a0, wv = p.geom.Wt - b0;     // tokens of the patch inside the grid
             for (int c = tid; c < 64 * (BN / 8); c += NT) {
                 const int tk = c >> 4, cc = c & 15, h = tk >> 3, w = tk & 7;
@@ -416,6 +428,24 @@ __device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, co
                 }
             }
             __syncthreads();                        // the staging rows are free again
+        }
+        if (p.extra_rows > 0) {       // tokens outside the grid: bf16 rows of the product times 1/64 (exact)
+            int lo, hi;
+            extra_row_range(p, m0, lo, hi);
+            for (int it = tid; it < (hi - lo) * (BN / 8); it += NT) {
+                const int lr = lo + it / (BN / 8), cc = it % (BN / 8);
+                const int col = n0 + cc * 8;
+                if (col >= p.N) continue;
+                const long j = (long)m0 + lr - p.Q * p.r;
+                const long img = j / p.extra;
+                const int e = (int)(j - img * p.extra);
+                uint4 v = *reinterpret_cast<const uint4 *>(cot + lr * S_CO + cc * 16);
+                v.x = pack_bf16x2(bf16_lo_to_f32(v.x) * inv, bf16_hi_to_f32(v.x) * inv);
+                v.y = pack_bf16x2(bf16_lo_to_f32(v.y) * inv, bf16_hi_to_f32(v.y) * inv);
+                v.z = pack_bf16x2(bf16_lo_to_f32(v.z) * inv, bf16_hi_to_f32(v.z) * inv);
+                v.w = pack_bf16x2(bf16_lo_to_f32(v.w) * inv, bf16_hi_to_f32(v.w) * inv);
+                *reinterpret_cast<uint4 *>(reinterpret_cast<unsigned short *>(p.C) + ((size_t)img * p.geom.img + e) * p.N + col) = v;
+            }
         }
     } else if constexpr (EPI == EPI_UNPROJECT) {
         constexpr int CTS = BN + 8;
@@ -447,6 +477,22 @@ __device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, co
             LBP_CASE(3, 0) LBP_CASE(3, 1) LBP_CASE(3, 2) LBP_CASE(3, 3)
 #undef LBP_CASE
             default: break;
+        }
+        if (p.extra_rows > 0) {       // tokens outside the grid: their rows are the gradient itself, scaled
+            int lo, hi;
+            extra_row_range(p, m0, lo, hi);
+            constexpr float inv = 1.0f / (float)((1 << LP) * (1 << LP));
+            constexpr int HALF = BN / 2;
+            for (int it = tid; it < (hi - lo) * HALF; it += NT) {
+                const int lr = lo + it / HALF, cp = it % HALF;
+                const int col = n0 + 2 * cp;
+                if (col >= p.N) continue;
+                const long j = (long)m0 + lr - p.Q * p.r;
+                const long img = j / p.extra;
+                const int e = (int)(j - img * p.extra);
+                uint32_t *dst = reinterpret_cast<uint32_t *>(p.C) + (((size_t)img * p.geom.img + e) * p.N + col) / 2;
+                *dst = pack_bf16x2(ct[lr * CTS + 2 * cp] * inv, ct[lr * CTS + 2 * cp + 1] * inv);
+            }
         }
     } else {
 #pragma unroll

@@ -11,27 +11,41 @@ namespace lbp {
 enum class WhtPath { kAuto = 0, kGeneric = 1, kRegister = 2, kMfma = 3 };
 enum class GemmPath { kAuto = 0, kSimple = 1 };
 
+// `extra` in the launchers below: tokens of every image in front of its grid (a class token, ...);
+// tensors are then [N][extra + H*W][C] and those tokens belong to no patch (the projections skip
+// them, see launch_gather_extra / launch_scatter_extra).
+//
 // p(.) of Eq. 6 per patch: in [N][H][W][C] -> out [P*r][C], both of `dtype`.
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
-                          const BasisPlan &plan, WhtPath path, hipStream_t stream);
+                          const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra = 0);
 
 // The same for two tensors on one token grid (gy and x of a backward call) in ONE launch where
 // the kernels allow it, so that the second, smaller tensor fills the tail of the first.
 hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
                                int N, int H, int W, int dtype, const BasisPlan &plan, WhtPath path,
-                               hipStream_t stream);
+                               hipStream_t stream, int extra = 0);
 
 // p^-1(.) of Eq. 7 per patch with the 1/p^2 factor: in fp32 [slices][P*r][C] (the slices are
-// summed first: split-K partial results) -> out [N][H][W][C] of `dtype`.
+// summed first: split-K partial results) -> out [N][H][W][C] of `dtype`.  slice_rows > 0: rows
+// of one slice when it holds more than the P*r coefficient rows.
 hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H, int W, int C,
-                            int dtype, const BasisPlan &plan, WhtPath path, hipStream_t stream);
+                            int dtype, const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra = 0,
+                            long slice_rows = 0);
+
+// Tokens outside the grid.  gather: out[n*extra + e][c] = scale * in[n][e][c] (rows appended to
+// a projected tensor so that the products treat them exactly); scatter: the reverse for the
+// input gradient, out[n][e][c] = scale * sum over slices of in[slice][n*extra + e][c] (fp32 in).
+hipError_t launch_gather_extra(const void *in, void *out, int N, int extra, long img_tokens, int C, int dtype,
+                               float scale, hipStream_t stream);
+hipError_t launch_scatter_extra(const float *in, int slices, size_t slice_stride, void *out, int N, int extra,
+                                long img_tokens, int C, int dtype, float scale, hipStream_t stream);
 
 // Matrix-core form of the two projections (bf16 tensors, any selection, any patch up to 16).
 bool wht_mfma_supported(const BasisPlan &plan, int dtype, int C);
 hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
-                               int N, int H, int W, const BasisPlan &plan, hipStream_t stream);
+                               int N, int H, int W, const BasisPlan &plan, hipStream_t stream, int extra = 0);
 hipError_t launch_unproject_mfma(const float *in, int slices, void *out, int N, int H, int W, int C,
-                                 const BasisPlan &plan, hipStream_t stream);
+                                 const BasisPlan &plan, hipStream_t stream, int extra = 0, long slice_rows = 0);
 
 // energy[j] += sum over patches q and channels of coef[q*pp + j][c]^2 for all pp = p^2 bases; `partial`
 // is scratch of pp * energy_chunks(Q) doubles.
@@ -66,6 +80,9 @@ struct GemmArgs {
     // kUnproject only: token grid of one image and the selected bases
     int grid_h = 0, grid_w = 0;
     const BasisPlan *plan = nullptr;
+    // kUnproject only: `extra` tokens per image in front of the grid; the last extra_rows rows of A
+    // are theirs (image-major) and their rows of the product go to those tokens, scaled by 1/patch^2
+    int extra = 0, extra_rows = 0;
 };
 
 // True if launch_gemm supports GemmOut::kUnproject for this selection and dtype.

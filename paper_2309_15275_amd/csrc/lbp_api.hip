@@ -123,7 +123,7 @@ lbp::WhtPath wht_path_from_env()
 
 // Pointer, alias and alignment rules common to both backward entry points.
 int validate_buffers(const void *x, const void *gy, const void *W, const lbp_shape_t *s, void *gx,
-                     void *gW, size_t x_rows = 0)
+                     void *gW, size_t x_rows = 0, int extra = 0)
 {
     if (!x || !gy || !W) return LBP_ERR_NULL;
     if (!gx && !gW) return LBP_ERR_NULL;
@@ -131,7 +131,7 @@ int validate_buffers(const void *x, const void *gy, const void *W, const lbp_sha
     int rc = lbp::validate_alignment(ptrs, 5);
     if (rc) return rc;
     size_t esz = lbp::dtype_size(s->dtype);
-    size_t M = (size_t)s->N * s->H * s->W;
+    size_t M = (size_t)s->N * ((size_t)s->H * s->W + extra);
     size_t nx = (x_rows ? x_rows : M) * s->Cin * esz, ngy = M * s->Cout * esz, nw = (size_t)s->Cout * s->Cin * esz;
     size_t ngx = M * s->Cin * esz, ngw = (size_t)s->Cout * s->Cin * lbp::dtype_size(s->gw_dtype);
     const void *ins[3] = {x, gy, W};
@@ -149,6 +149,12 @@ int validate_buffers(const void *x, const void *gy, const void *W, const lbp_sha
         hipError_t e_ = (expr);                        \
         if (e_ != hipSuccess) return hip_fail(e_);     \
     } while (0)
+
+// `extra` tokens per image in front of the grid: non-negative, and all tokens still count in 31 bits.
+bool tokens_ok(const lbp_shape_t *s, int extra)
+{
+    return extra >= 0 && (long)s->N * ((long)s->H * s->W + extra) <= 0x7fffffffL;
+}
 
 // Describes the weight-gradient product; returns true when it leaves fp32 partial sums in `part`
 // that launch_splitk_reduce still has to combine (scaled) into gW.
@@ -208,7 +214,12 @@ int lbp_wht_select_bases(int patch, int r, int order, int32_t *basis_idx)
 
 size_t lbp_wht_workspace_bytes(const lbp_shape_t *shape, int patch, int r)
 {
-    if (lbp::validate_shape(shape, patch) != LBP_OK) return 0;
+    return lbp_wht_workspace_bytes_tokens(shape, 0, patch, r);
+}
+
+size_t lbp_wht_workspace_bytes_tokens(const lbp_shape_t *shape, int extra, int patch, int r)
+{
+    if (lbp::validate_shape(shape, patch) != LBP_OK || !tokens_ok(shape, extra)) return 0;
     if (patch != 0 && (r < 1 || r > patch * patch)) return 0;
     // the split-K factors, hence the size, depend on the device's compute-unit count: use the
     // current device's if there is one, else that of an MI355X
@@ -218,11 +229,18 @@ size_t lbp_wht_workspace_bytes(const lbp_shape_t *shape, int patch, int r)
         cus = v;
     else
         (void)hipGetLastError();
-    lbp::WorkspacePlan ws;
-    if (lbp::plan_workspace(shape, patch, r, cus, false, false, &ws) != LBP_OK) return 0;
-    size_t total = ws.total;
+    // the plan of a call depends on the selection (fusable or not, pooled or not) and on whether
+    // both gradients are requested: report the largest
+    size_t total = 0;
+    for (int v = 0; v < 8; ++v) {
+        lbp::WorkspacePlan ws;
+        if (lbp::plan_workspace(shape, patch, r, cus, (v & 1) != 0, false, &ws, (v & 2) != 0, (v & 4) != 0, extra) != LBP_OK)
+            return 0;
+        if (ws.total > total) total = ws.total;
+        if (patch == 0) break;
+    }
     if (patch == 0 && shape->dtype == LBP_BF16)   // staging of gx for the plain cross-check kernels
-        total += ((size_t)shape->N * shape->H * shape->W * shape->Cin * 4 + 255) / 256 * 256;
+        total += ((size_t)shape->N * ((size_t)shape->H * shape->W + extra) * shape->Cin * 4 + 255) / 256 * 256;
     return total;
 }
 
@@ -264,9 +282,16 @@ int lbp_release_workspace(void)
 int lbp_wht_project(const void *in, int N, int H, int W, int C, int dtype, int patch,
                     const int32_t *basis_idx, int r, void *out, void *stream)
 {
+    return lbp_wht_project_tokens(in, N, H, W, 0, C, dtype, patch, basis_idx, r, out, stream);
+}
+
+int lbp_wht_project_tokens(const void *in, int N, int H, int W, int extra, int C, int dtype, int patch,
+                           const int32_t *basis_idx, int r, void *out, void *stream)
+{
     if (!in || !out || !basis_idx) return LBP_ERR_NULL;
     int rc = lbp::validate_grid(N, H, W, C, dtype, patch);
     if (rc) return rc;
+    if (extra < 0 || (long)N * ((long)H * W + extra) > 0x7fffffffL) return LBP_ERR_SHAPE;
     lbp::BasisPlan plan;
     rc = lbp::make_basis_plan(patch, basis_idx, r, &plan);
     if (rc) return rc;
@@ -274,13 +299,16 @@ int lbp_wht_project(const void *in, int N, int H, int W, int C, int dtype, int p
     rc = lbp::validate_alignment(ptrs, 2);
     if (rc) return rc;
     size_t esz = lbp::dtype_size(dtype);
-    size_t M = (size_t)N * H * W;
-    if (lbp::ranges_overlap(in, M * C * esz, out, (size_t)lbp::patch_count(N, H, W, patch) * r * C * esz)) return LBP_ERR_ALIAS;
+    size_t M = (size_t)N * ((size_t)H * W + extra);
+    const size_t Mq = (size_t)lbp::patch_count(N, H, W, patch) * r;
+    if (lbp::ranges_overlap(in, M * C * esz, out, (Mq + (size_t)N * extra) * C * esz)) return LBP_ERR_ALIAS;
     int dev;
     DeviceState *st;
     rc = current_device(&dev, &st);
     if (rc) return rc;
-    LBP_HIP(lbp::launch_project(in, out, N, H, W, C, dtype, plan, wht_path_from_env(), (hipStream_t)stream));
+    LBP_HIP(lbp::launch_project(in, out, N, H, W, C, dtype, plan, wht_path_from_env(), (hipStream_t)stream, extra));
+    LBP_HIP(lbp::launch_gather_extra(in, (char *)out + Mq * C * esz, N, extra, (long)H * W + extra, C, dtype, 1.0f,
+                                     (hipStream_t)stream));
     return LBP_OK;
 }
 
@@ -392,17 +420,20 @@ namespace {
 // x_projected: `x` already is x^ = WHT(x; I), [P*r][Cin], kept from the forward pass.
 int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_t *shape, int patch,
                   const int32_t *basis_idx, int r, void *gx, void *gW, void *stream, hipEvent_t *ev,
-                  bool x_projected = false)
+                  bool x_projected = false, int extra = 0)
 {
     if (!shape || !basis_idx) return LBP_ERR_NULL;
     if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
     int rc = lbp::validate_shape(shape, patch);
     if (rc) return rc;
+    if (!tokens_ok(shape, extra)) return LBP_ERR_SHAPE;
     lbp::BasisPlan plan;
     rc = lbp::make_basis_plan(patch, basis_idx, r, &plan);
     if (rc) return rc;
-    const size_t rows_r = (size_t)lbp::patch_count(shape->N, shape->H, shape->W, patch) * r;
-    rc = validate_buffers(x, gy, W, shape, gx, gW, x_projected ? rows_r : 0);
+    // rows of the projected tensors: (patch, basis) pairs first, then the tokens outside the grid
+    const long Mq = lbp::patch_count(shape->N, shape->H, shape->W, patch) * r;
+    const long Mr = Mq + (long)shape->N * extra;
+    rc = validate_buffers(x, gy, W, shape, gx, gW, x_projected ? (size_t)Mr : 0, extra);
     if (rc) return rc;
 
     int dev;
@@ -416,7 +447,7 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     // both gradients wanted: the two products may share one launch (not when timed stage by stage)
     const bool allow_group = gx && gW && !ev && gpath != lbp::GemmPath::kSimple && group_from_env();
     rc = lbp::plan_workspace(shape, patch, r, st->num_cus, can_fuse, fuse_env == 1, &ws,
-                             !lbp::gemm_unproject_pooled(plan), allow_group);
+                             !lbp::gemm_unproject_pooled(plan), allow_group, extra);
     if (rc) return rc;
     char *base = nullptr;
     rc = get_workspace(st, ws.total, &base);
@@ -426,7 +457,8 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     const lbp::WhtPath path = wht_path_from_env();
     const int N = shape->N, H = shape->H, Wd = shape->W, Cin = shape->Cin, Cout = shape->Cout;
     const int dt = shape->dtype;
-    const long Mr = lbp::patch_count(N, H, Wd, patch) * r;
+    const size_t esz = lbp::dtype_size(dt);
+    const long img_tokens = (long)H * Wd + extra;
     const float inv_pp = 1.0f / (float)(patch * patch);
     void *gy_r = base + ws.gy_r;
     const void *x_r = x_projected ? x : base + ws.x_r;
@@ -437,9 +469,19 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     // g^y = WHT(gy; I) is needed by both products; x^ = WHT(x; I) only by the weight gradient
     // (first two statements of Algorithm 1).  One launch covers both tensors.
     if (gW && !x_projected)
-        LBP_HIP(lbp::launch_project_pair(gy, gy_r, Cout, x, base + ws.x_r, Cin, N, H, Wd, dt, plan, path, s));
+        LBP_HIP(lbp::launch_project_pair(gy, gy_r, Cout, x, base + ws.x_r, Cin, N, H, Wd, dt, plan, path, s, extra));
     else
-        LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s));
+        LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s, extra));
+    if (extra > 0) {
+        // Tokens outside the grid join the projected tensors as they are: Eq. 2 stays exact for
+        // them.  Their g_y rows carry patch^2 (a power of two), which the 1/patch^2 of both
+        // products takes away again.
+        LBP_HIP(lbp::launch_gather_extra(gy, (char *)gy_r + (size_t)Mq * Cout * esz, N, extra, img_tokens, Cout, dt,
+                                         (float)(patch * patch), s));
+        if (gW && !x_projected)
+            LBP_HIP(lbp::launch_gather_extra(x, base + ws.x_r + (size_t)Mq * Cin * esz, N, extra, img_tokens, Cin, dt,
+                                             1.0f, s));
+    }
     if (ev) LBP_HIP(hipEventRecord(ev[1], s));
     // g~w = g^w = g^y^T x^  (with the 1/p^2 of the normalisation)
     lbp::GemmArgs gw_args, g;
@@ -462,6 +504,8 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
             g.C = gx;
             g.grid_h = H; g.grid_w = Wd;
             g.plan = &plan;
+            g.extra = extra;
+            g.extra_rows = N * extra;
         } else {
             g.splits = ws.gx.splits;
             g.out = lbp::GemmOut::kF32;
@@ -480,7 +524,11 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     if (ev) LBP_HIP(hipEventRecord(ev[2], s));
     if (gx) {
         if (!grouped) LBP_HIP(lbp::launch_gemm(g, gpath, s));
-        if (!ws.gx_fused) LBP_HIP(lbp::launch_unproject(gx_r, ws.gx.splits, gx, N, H, Wd, Cin, dt, plan, path, s));
+        if (!ws.gx_fused) {
+            LBP_HIP(lbp::launch_unproject(gx_r, ws.gx.splits, gx, N, H, Wd, Cin, dt, plan, path, s, extra, Mr));
+            LBP_HIP(lbp::launch_scatter_extra(gx_r + (size_t)Mq * Cin, ws.gx.splits, (size_t)Mr * Cin, gx, N, extra,
+                                              img_tokens, Cin, dt, inv_pp, s));
+        }
     }
     if (ev) LBP_HIP(hipEventRecord(ev[3], s));
     return LBP_OK;
@@ -501,6 +549,19 @@ int lbp_wht_backward_preprojected(const void *x_r, const void *gy, const void *W
                                   void *gx, void *gW, void *stream)
 {
     return backward_impl(x_r, gy, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr, true);
+}
+
+int lbp_wht_backward_tokens(const void *x, const void *gy, const void *W, const lbp_shape_t *shape, int extra,
+                            int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream)
+{
+    return backward_impl(x, gy, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr, false, extra);
+}
+
+int lbp_wht_backward_tokens_preprojected(const void *x_r, const void *gy, const void *W, const lbp_shape_t *shape,
+                                         int extra, int patch, const int32_t *basis_idx, int r, void *gx, void *gW,
+                                         void *stream)
+{
+    return backward_impl(x_r, gy, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr, true, extra);
 }
 
 int lbp_wht_backward_profile(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,

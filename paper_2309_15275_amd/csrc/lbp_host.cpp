@@ -219,14 +219,15 @@ long gemm_workgroups(const GemmPlan &g, long M, long N, int fused_r)
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
-                   bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group)
+                   bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group, int extra)
 {
     if (!s || !ws) return LBP_ERR_NULL;
     std::memset(ws, 0, sizeof *ws);
     if (num_cus < 1) num_cus = 256;
     const size_t esz = dtype_size(s->dtype);
     const int gw_bytes = (int)dtype_size(s->gw_dtype);
-    const long M = (long)s->N * s->H * s->W;
+    if (extra < 0) return LBP_ERR_SHAPE;
+    const long M = (long)s->N * ((long)s->H * s->W + extra);      // tokens, those outside the grid included
     size_t off = 0;
     if (patch == 0) {
         // full-rank backward: only the split-K partial sums of gW
@@ -237,7 +238,8 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
         ws->total = off;
         return LBP_OK;
     }
-    const long Mr = patch_count(s->N, s->H, s->W, patch) * r;
+    // rows of the projected tensors: (patch, basis) pairs, then the tokens outside the grid as they are
+    const long Mr = patch_count(s->N, s->H, s->W, patch) * r + (long)s->N * extra;
     ws->gw = plan_gemm(s->Cout, s->Cin, Mr, gw_bytes, true, 0, 0, num_cus);
     // gx: fused epilogue (no split, few workgroups when Mr is small) against split-K partial sums
     // that the reverse-projection kernel adds up while it reads them

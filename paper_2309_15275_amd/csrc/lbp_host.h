@@ -119,9 +119,11 @@ struct WorkspacePlan {
 // num_cus: compute units of the device (the GEMM plans depend on it); pass 256 when unknown.
 // can_fuse: the selection allows the fused reverse projection (false gives the larger workspace);
 // force_fuse: take it whenever allowed instead of comparing estimates; fused_wide: see plan_gemm;
-// allow_group: the caller wants both gradients and can launch the two products as one grid.
+// allow_group: the caller wants both gradients and can launch the two products as one grid;
+// extra: tokens per image in front of the grid (tensors are [N][extra + H*W][C]).
 int plan_workspace(const lbp_shape_t *shape, int patch, int r, int num_cus, bool can_fuse,
-                   bool force_fuse, WorkspacePlan *ws, bool fused_wide = false, bool allow_group = false);
+                   bool force_fuse, WorkspacePlan *ws, bool fused_wide = false, bool allow_group = false,
+                   int extra = 0);
 
 const char *status_string(int code);
 

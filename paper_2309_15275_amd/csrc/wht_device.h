@@ -24,6 +24,8 @@ struct GridGeom {
     int PW;        // patches per grid row, ceil(W / patch)
     int PHW;       // patches per image
     int patch;
+    int img;       // tokens one image occupies in memory: tokens in front of the grid + H*W
+    int tok0;      // tokens of an image in front of its grid (class token ...), not part of any patch
     // image n, first grid row a0 and first grid column b0 of patch q (patch numbers fit 31 bits:
     // the token count does; 32-bit divisions are several times cheaper than 64-bit ones)
     __device__ __forceinline__ void origin(long q, long &n, int &a0, int &b0) const
@@ -36,9 +38,14 @@ struct GridGeom {
         a0 = (int)(a * (unsigned)patch);
         b0 = (int)((rem - a * (unsigned)PW) * (unsigned)patch);
     }
+    // index, among all tokens of the tensor, of grid token (a0, b0) of image n
+    __device__ __forceinline__ size_t token(long n, int a0, int b0) const
+    {
+        return (size_t)n * img + tok0 + (size_t)a0 * Wt + b0;
+    }
 };
 
-inline GridGeom make_geom(int H, int W, int patch)
+inline GridGeom make_geom(int H, int W, int patch, int extra = 0)
 {
     GridGeom g;
     g.Wt = W;
@@ -47,6 +54,8 @@ inline GridGeom make_geom(int H, int W, int patch)
     g.PW = (W + patch - 1) / patch;
     g.PHW = ((H + patch - 1) / patch) * g.PW;
     g.patch = patch;
+    g.img = extra + H * W;
+    g.tok0 = extra;
     return g;
 }
 

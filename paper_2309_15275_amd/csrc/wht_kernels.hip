@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void wht_project_reg_kernel(ProjTensor t0, Pro
     long n;
     int a0, b0;
     g.origin(q, n, a0, b0);
-    const uint32_t *src = t.in + ((size_t)n * g.HWt + (size_t)a0 * g.Wt + b0) * Cd + cd;
+    const uint32_t *src = t.in + g.token(n, a0, b0) * Cd + cd;
 
     uint32_t raw[P * P];
     if (a0 + P <= g.Ht && b0 + P <= g.Wt) {
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void wht_unproject_reg_kernel(const float *__r
     long n;
     int a0, b0;
     g.origin(q, n, a0, b0);
-    uint32_t *dst = out + ((size_t)n * g.HWt + (size_t)a0 * g.Wt + b0) * Cd + cd;
+    uint32_t *dst = out + g.token(n, a0, b0) * Cd + cd;
     const int hv = g.Ht - a0, wv = g.Wt - b0;      // tokens of the patch that exist (>= P: all of them)
 
     if (BF16) {
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(128) void wht_project_generic_kernel(const uint4 *_
     long n;
     int a0, b0;
     g.origin(q, n, a0, b0);
-    const uint4 *src = in + ((size_t)n * g.HWt + (size_t)a0 * g.Wt + b0) * Cv + cv;
+    const uint4 *src = in + g.token(n, a0, b0) * Cv + cv;
     for (int k0 = 0; k0 < r; k0 += KC) {
         float acc[KC][VN];
 #pragma unroll
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(128) void wht_unproject_generic_kernel(const float 
     long n;
     int a0, b0;
     g.origin(q, n, a0, b0);
-    uint4 *dst = out + ((size_t)n * g.HWt + (size_t)a0 * g.Wt + b0) * Cv + cv;
+    uint4 *dst = out + g.token(n, a0, b0) * Cv + cv;
     for (int t0 = 0; t0 < pp; t0 += TC) {     // pp is a multiple of 4 for every legal patch
         float acc[TC][VN];
 #pragma unroll
@@ -390,7 +390,7 @@ void launch_reg_mh(int mh, int mw, const void *in, void *out, long items, int Cd
 // in2/out2/C2: optional second tensor on the same token grid (projection only).
 template <bool UNPROJECT>
 hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int dtype,
-                      const BasisPlan &plan, Slices sl, hipStream_t s, const void *in2 = nullptr,
+                      const BasisPlan &plan, Slices sl, hipStream_t s, int extra, const void *in2 = nullptr,
                       void *out2 = nullptr, int C2 = 0)
 {
     const bool bf16 = dtype == LBP_BF16;
@@ -404,7 +404,7 @@ hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int
         sec.Cd = bf16 ? C2 / 2 : C2;
         sec.items = Q * sec.Cd;
     }
-    GridGeom g = make_geom(H, W, plan.patch);
+    GridGeom g = make_geom(H, W, plan.patch, extra);
     PooledSel sel;
     sel.mask = plan.pooled_mask;
     for (int j = 0; j < 64; ++j) sel.pos[j] = plan.pooled_pos[j];
@@ -430,12 +430,12 @@ hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int
 
 template <bool UNPROJECT>
 hipError_t launch_generic(const void *in, void *out, int N, int H, int W, int C, int dtype,
-                          const BasisPlan &plan, Slices sl, hipStream_t s)
+                          const BasisPlan &plan, Slices sl, hipStream_t s, int extra)
 {
     const bool bf16 = dtype == LBP_BF16;
     const int Cv = bf16 ? C / 8 : C / 4;
     const long Q = patch_count(N, H, W, plan.patch);
-    GridGeom g = make_geom(H, W, plan.patch);
+    GridGeom g = make_geom(H, W, plan.patch, extra);
     NatTable nat;
     for (int k = 0; k < kMaxBases; ++k) nat.v[k] = plan.nat[k];
     dim3 grid((unsigned)Q, (unsigned)((Cv + 127) / 128));
@@ -477,40 +477,41 @@ bool use_mfma_path(const BasisPlan &plan, WhtPath path, int dtype, int C)
 }  // namespace
 
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
-                          const BasisPlan &plan, WhtPath path, hipStream_t stream)
+                          const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra)
 {
     if (use_mfma_path(plan, path, dtype, C))
-        return launch_project_mfma(in, out, C, nullptr, nullptr, 0, N, H, W, plan, stream);
+        return launch_project_mfma(in, out, C, nullptr, nullptr, 0, N, H, W, plan, stream, extra);
     if (use_register_path(plan, path))
-        return launch_reg<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
-    return launch_generic<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream);
+        return launch_reg<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream, extra);
+    return launch_generic<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream, extra);
 }
 
 hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
                                int N, int H, int W, int dtype, const BasisPlan &plan, WhtPath path,
-                               hipStream_t stream)
+                               hipStream_t stream, int extra)
 {
     if (use_mfma_path(plan, path, dtype, C0) && use_mfma_path(plan, path, dtype, C1))
-        return launch_project_mfma(in0, out0, C0, in1, out1, C1, N, H, W, plan, stream);
+        return launch_project_mfma(in0, out0, C0, in1, out1, C1, N, H, W, plan, stream, extra);
     if (use_register_path(plan, path))
-        return launch_reg<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream, in1, out1, C1);
-    hipError_t e = launch_generic<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream);
+        return launch_reg<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream, extra, in1, out1, C1);
+    hipError_t e = launch_generic<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream, extra);
     if (e != hipSuccess) return e;
-    return launch_generic<false>(in1, out1, N, H, W, C1, dtype, plan, Slices{}, stream);
+    return launch_generic<false>(in1, out1, N, H, W, C1, dtype, plan, Slices{}, stream, extra);
 }
 
 hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H, int W, int C,
-                            int dtype, const BasisPlan &plan, WhtPath path, hipStream_t stream)
+                            int dtype, const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra,
+                            long slice_rows)
 {
     if (slices < 1) return hipErrorInvalidValue;
     if (use_mfma_path(plan, path, dtype, C))
-        return launch_unproject_mfma(in, slices, out, N, H, W, C, plan, stream);
+        return launch_unproject_mfma(in, slices, out, N, H, W, C, plan, stream, extra, slice_rows);
     Slices sl;
     sl.count = slices;
-    sl.stride = (size_t)patch_count(N, H, W, plan.patch) * plan.r * C;
+    sl.stride = (size_t)(slice_rows > 0 ? slice_rows : patch_count(N, H, W, plan.patch) * plan.r) * C;
     if (use_register_path(plan, path))
-        return launch_reg<true>(in, out, N, H, W, C, dtype, plan, sl, stream);
-    return launch_generic<true>(in, out, N, H, W, C, dtype, plan, sl, stream);
+        return launch_reg<true>(in, out, N, H, W, C, dtype, plan, sl, stream, extra);
+    return launch_generic<true>(in, out, N, H, W, C, dtype, plan, sl, stream, extra);
 }
 
 }  // namespace lbp

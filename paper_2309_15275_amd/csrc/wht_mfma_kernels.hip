@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void wht_project_mfma_kernel(MfmaTensor t0, Mf
         long n;
         int a0, b0;
         g.origin(q, n, a0, b0);
-        const unsigned short *base = t.in + ((size_t)n * g.HWt + (size_t)a0 * g.Wt + b0) * t.C + c0;
+        const unsigned short *base = t.in + g.token(n, a0, b0) * t.C + c0;
         const int hv = g.Ht - a0, wv = g.Wt - b0;         // tokens of the patch inside the grid
         const bool chan_ok = c0 + cc8 < t.C;
         if (hv >= p && wv >= p && P2PAD == p2) {
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void wht_project_mfma_kernel(MfmaTensor t0, Mf
             long n;
             int a0, b0;
             g.origin(q, n, a0, b0);
-            const size_t tok0 = (size_t)n * g.HWt + (size_t)a0 * g.Wt + b0;
+            const size_t tok0 = g.token(n, a0, b0);
             for (int c = tid; c < P2PAD * (CB / 8); c += 256) {
                 int tk = c >> 4, cc = c & 15;
                 u32x4_t v = {0u, 0u, 0u, 0u};
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(256) void wht_unproject_mfma_kernel(const float *__
         long n;
         int a0, b0;
         g.origin(q, n, a0, b0);
-        const size_t tok0 = (size_t)n * g.HWt + (size_t)a0 * g.Wt + b0;
+        const size_t tok0 = g.token(n, a0, b0);
         __syncthreads();
         // ---- coefficients (fp32, split-K slices summed in fixed order) -> bf16 -> LDS [basis][channel]
         // lane: 4 channels (cc4) of basis rows tid/32, tid/32 + 8, ...: all loads of a slice are issued
@@ -445,10 +445,10 @@ bool wht_mfma_supported(const BasisPlan &plan, int dtype, int C)
 }
 
 hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
-                               int N, int H, int W, const BasisPlan &plan, hipStream_t stream)
+                               int N, int H, int W, const BasisPlan &plan, hipStream_t stream, int extra)
 {
     const long Q = patch_count(N, H, W, plan.patch);
-    GridGeom g = make_geom(H, W, plan.patch);
+    GridGeom g = make_geom(H, W, plan.patch, extra);
     NatTable nat = make_nat(plan);
     MfmaTensor t[2] = {};
     const void *ins[2] = {in0, in1};
@@ -487,16 +487,16 @@ hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *
 }
 
 hipError_t launch_unproject_mfma(const float *in, int slices, void *out, int N, int H, int W, int C,
-                                 const BasisPlan &plan, hipStream_t stream)
+                                 const BasisPlan &plan, hipStream_t stream, int extra, long slice_rows)
 {
     const long Q = patch_count(N, H, W, plan.patch);
-    GridGeom g = make_geom(H, W, plan.patch);
+    GridGeom g = make_geom(H, W, plan.patch, extra);
     NatTable nat = make_nat(plan);
     const int chunks = (C + CB - 1) / CB;
     const long items = Q * chunks;
     const int ipw = items_per_wg(items);
     const unsigned blocks = (unsigned)((items + ipw - 1) / ipw);
-    const size_t slice_stride = (size_t)Q * plan.r * C;
+    const size_t slice_stride = (size_t)(slice_rows > 0 ? slice_rows : Q * plan.r) * C;
     const int p2 = plan.patch * plan.patch;
     const int kpad = (plan.r + 15) / 16 * 16;
     const int rows = p2 > kpad ? p2 : kpad;

@@ -101,6 +101,23 @@ def _gelu_erf(a):
     return (0.5 * a * (1.0 + erf(a / np.sqrt(2.0)))).astype(np.float32)
 
 
+def make_token_inputs(wl, extra):
+    """Token sequences of a ViT layer: `extra` tokens (class token ...) in front of the H*W grid
+    tokens of make_inputs.  Returns dict(x=[N,extra+H*W,Cin], gy=[N,extra+H*W,Cout], w=[Cout,Cin]);
+    the extra tokens are drawn like the grid's (activations through GELU, gradients at the scale of
+    the smooth field), from a generator of their own."""
+    base = make_inputs(wl)
+    rng = np.random.default_rng(wl.seed + 7919)
+    f32 = wl.dtype == "f32"
+    xe = rng.standard_normal((wl.N, extra, wl.Cin), dtype=np.float32)
+    ge = rng.standard_normal((wl.N, extra, wl.Cout), dtype=np.float32) * np.float32(1.0 if f32 else 1e-2)
+    if not f32:
+        xe, ge = round_to_bf16(_gelu_erf(xe)), round_to_bf16(ge)
+    x = np.concatenate([xe, base["x"].reshape(wl.N, wl.H * wl.W, wl.Cin)], axis=1)
+    gy = np.concatenate([ge, base["gy"].reshape(wl.N, wl.H * wl.W, wl.Cout)], axis=1)
+    return {"x": np.ascontiguousarray(x), "gy": np.ascontiguousarray(gy), "w": base["w"]}
+
+
 def make_inputs(wl):
     """Returns dict(x=[N,H,W,Cin], gy=[N,H,W,Cout], w=[Cout,Cin]) of fp32 arrays; for a
     bf16 workload every value is exactly representable in bf16."""

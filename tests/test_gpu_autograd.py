@@ -100,3 +100,30 @@ def test_only_the_projected_activation_is_saved():
     assert torch.equal(y2.reshape(y.shape), y)
     with pytest.raises(ValueError):
         fc(x.detach().reshape(2, 256, 64))
+
+
+def test_class_token_sequences_through_autograd():
+    # [N, 1 + 14*14, C] as in ViT-B/16: with all bases kept the backward is exact on every token,
+    # class token included, so autograd through the layer equals autograd through F.linear
+    torch.manual_seed(1)
+    x = torch.randn(2, 197, 32, device="cuda", requires_grad=True)
+    w = (0.1 * torch.randn(48, 32, device="cuda")).requires_grad_(True)
+    b = torch.randn(48, device="cuda", requires_grad=True)
+    g = torch.randn(2, 197, 48, device="cuda")
+    lbp_wht_linear(x, w, b, 8, list(range(64)), grid=(14, 14)).backward(g)
+    got = [t.grad.clone() for t in (x, w, b)]
+    for t in (x, w, b):
+        t.grad = None
+    torch.nn.functional.linear(x, w, b).backward(g)
+    for a, t in zip(got, (x, w, b)):
+        assert rel_fro(to_host(a), to_host(t.grad)) <= 1e-5
+    # a low-rank selection: against the oracle, and only x^ plus the class tokens are saved
+    fc = LBPWHTLinear(32, 48, bias=False, patch=8, rank=8, device="cuda")
+    with torch.no_grad():
+        fc.weight.copy_(w)
+    x2 = x.detach().clone().requires_grad_(True)
+    y = fc(x2, grid=(14, 14))
+    assert sorted(tuple(t.shape) for t in y.grad_fn.saved_tensors) == sorted([(2 * 4 * 8 + 2, 32), (48, 32)])
+    y.backward(g)
+    gx0, gW0 = oracle.lbp_wht_backward_tokens(to_host(x), to_host(g), to_host(w), (14, 14), 8, fc.basis_idx)
+    assert rel_fro(to_host(x2.grad), gx0) <= 1e-5 and rel_fro(to_host(fc.weight.grad), gW0) <= 1e-5

@@ -1,0 +1,116 @@
+"""GPU parity for token sequences with tokens outside the grid (a class token in front of the patch
+tokens): the library's lbp_wht_backward_tokens family against the CPU oracle, element by element."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from _gpu_util import TOL, rel_fro, to_device, to_host
+from paper_2309_15275_amd import binding, workloads
+from paper_2309_15275_amd.workloads import Workload
+
+pytestmark = pytest.mark.gpu
+
+ENV = ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT", "LBP_GEMM_TILE", "LBP_GEMM_GROUP")
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    yield
+    for var in ENV:
+        os.environ.pop(var, None)
+    torch.cuda.synchronize()
+
+
+# N, H, W, extra, Cin, Cout, patch, r, order
+CASES = [
+    (3, 16, 16, 1, 72, 136, 8, 8, "l1"),       # class token, pooled selection
+    (2, 14, 14, 1, 64, 200, 8, 8, "l1"),       # ViT-B/16 at 224: 196 + 1 tokens, grid zero-padded to 16 x 16
+    (2, 14, 14, 2, 136, 72, 8, 10, "l1"),      # class + distillation token, selection that cannot be pooled
+    (5, 7, 7, 1, 264, 520, 8, 4, "l1"),        # 49-token maps, several GEMM tiles
+    (2, 8, 12, 3, 40, 24, 4, 6, "linf"),       # patch 4
+    (1, 16, 16, 1, 8, 8, 16, 5, "l1"),         # patch 16: generic / matrix-core projections
+    (4, 8, 8, 1, 64, 64, 8, 64, "l1"),         # all bases: exact on every token
+    (130, 8, 8, 1, 32, 48, 8, 8, "l1"),        # more extra rows than one GEMM tile holds
+]
+# (LBP_WHT_PATH, LBP_GEMM_PATH, LBP_FUSE_UNPROJECT, LBP_GEMM_GROUP)
+VARIANTS = [("auto", "auto", "1", "1"), ("auto", "auto", "0", "1"), ("auto", "auto", "1", "0"),
+            ("generic", "simple", "0", "1"), ("mfma", "auto", "1", "1")]
+
+
+def run_case(case, dtype, seed):
+    N, H, W, extra, Cin, Cout, patch, r, order = CASES[case]
+    wl = Workload("tokens", N, H, W, Cin, Cout, patch, (), ("l1",), dtype, seed)
+    host = workloads.make_token_inputs(wl, extra)
+    dev = {k: to_device(v, dtype) for k, v in host.items()}
+    idx = oracle.select_bases(patch, r, order)
+    return wl, extra, host, dev, idx
+
+
+@pytest.mark.parametrize("variant", range(len(VARIANTS)))
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_backward_with_tokens_outside_the_grid_matches_oracle(case, dtype, variant):
+    wht, gemm, fuse, group = VARIANTS[variant]
+    if wht == "mfma" and dtype == "f32":
+        pytest.skip("the matrix-core projections exist for bf16 tensors only")
+    os.environ["LBP_WHT_PATH"], os.environ["LBP_GEMM_PATH"] = wht, gemm
+    os.environ["LBP_FUSE_UNPROJECT"], os.environ["LBP_GEMM_GROUP"] = fuse, group
+    wl, extra, host, dev, idx = run_case(case, dtype, 600 + case)
+    T = extra + wl.H * wl.W
+    # sentinels: the outputs must be written completely
+    gx = torch.full((wl.N, T, wl.Cin), float("nan"), dtype=dev["x"].dtype, device="cuda")
+    gW = torch.full((wl.Cout, wl.Cin), float("nan"), dtype=torch.float32, device="cuda")
+    binding.lbp_wht_backward_tokens(dev["x"], dev["gy"], dev["w"], (wl.H, wl.W), wl.patch, idx, gx=gx, gW=gW)
+    gx0, gW0 = oracle.lbp_wht_backward_tokens(host["x"], host["gy"], host["w"], (wl.H, wl.W), wl.patch, idx)
+    gxh, gWh = to_host(gx), to_host(gW)
+    assert np.isfinite(gxh).all() and np.isfinite(gWh).all()
+    egx, egw = rel_fro(gxh, gx0), rel_fro(gWh, gW0)
+    assert egx <= TOL[dtype] and egw <= TOL[dtype], (egx, egw)
+    # the rows of the tokens outside the grid on their own (they are few: the total hides them)
+    ecls = rel_fro(gxh[:, :extra], gx0[:, :extra])
+    assert ecls <= TOL[dtype], ecls
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [0, 1, 2, 4])
+def test_projection_kept_from_the_forward_pass_gives_the_same_bits(case, dtype):
+    wl, extra, host, dev, idx = run_case(case, dtype, 640 + case)
+    x_r = binding.wht_project_tokens(dev["x"], (wl.H, wl.W), wl.patch, idx)
+    rows = binding.patch_count(wl.N, wl.H, wl.W, wl.patch) * len(idx)
+    # the appended rows are the extra tokens themselves
+    assert torch.equal(x_r[rows:].view(wl.N, extra, wl.Cin), dev["x"][:, :extra])
+    xg = np.ascontiguousarray(host["x"][:, extra:]).reshape(wl.N, wl.H, wl.W, wl.Cin)
+    want = oracle.project_padded(xg, wl.patch, idx)
+    assert rel_fro(to_host(x_r[:rows]), want) <= (1e-6 if dtype == "f32" else 4e-3)
+    a = binding.lbp_wht_backward_tokens(dev["x"], dev["gy"], dev["w"], (wl.H, wl.W), wl.patch, idx)
+    b = binding.lbp_wht_backward_tokens_preprojected(x_r, dev["gy"], dev["w"], (wl.H, wl.W), wl.patch, idx)
+    bits = torch.int32 if dtype == "f32" else torch.int16
+    assert torch.equal(a[0].view(bits), b[0].view(bits)) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
+
+
+def test_no_extra_tokens_is_the_grid_call():
+    wl, extra, host, dev, idx = run_case(0, "bf16", 660)
+    xg = dev["x"][:, extra:].contiguous().view(wl.N, wl.H, wl.W, wl.Cin)
+    gyg = dev["gy"][:, extra:].contiguous().view(wl.N, wl.H, wl.W, wl.Cout)
+    a = binding.lbp_wht_backward(xg, gyg, dev["w"], wl.patch, idx)
+    b = binding.lbp_wht_backward_tokens(xg.view(wl.N, -1, wl.Cin), gyg.view(wl.N, -1, wl.Cout), dev["w"],
+                                        (wl.H, wl.W), wl.patch, idx)
+    assert torch.equal(a[0].view(torch.int16).view(-1), b[0].view(torch.int16).view(-1))
+    assert torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
+
+
+def test_vitb_sequence_of_197_tokens_at_full_width():
+    # ViT-B/16 fc1 at 224 x 224: 1 + 14 x 14 tokens, 768 -> 3072, the planner's own launch configuration
+    wl = Workload("vitb197", 16, 14, 14, 768, 3072, 8, (), ("l1",), "bf16", 680)
+    host = workloads.make_token_inputs(wl, 1)
+    dev = {k: to_device(v, "bf16") for k, v in host.items()}
+    idx = oracle.select_bases(8, 8, "l1")
+    gx, gW = binding.lbp_wht_backward_tokens(dev["x"], dev["gy"], dev["w"], (14, 14), 8, idx)
+    gx0, gW0 = oracle.lbp_wht_backward_tokens(host["x"], host["gy"], host["w"], (14, 14), 8, idx)
+    assert rel_fro(to_host(gx), gx0) <= TOL["bf16"] and rel_fro(to_host(gW), gW0) <= TOL["bf16"]
+    assert rel_fro(to_host(gx)[:, :1], gx0[:, :1]) <= TOL["bf16"]

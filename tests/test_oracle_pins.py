@@ -395,6 +395,49 @@ def test_one_basis_on_a_7x7_map_is_token_sum_matmul_broadcast_over_64():
     np.testing.assert_allclose(gx, want, rtol=0, atol=1e-12)
 
 
+# ---------- tokens outside the grid (class / distillation tokens): kept exactly ----------
+
+def rand_tokens(seed, N, T, Cin, Cout):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((N, T, Cin)), rng.standard_normal((N, T, Cout)), rng.standard_normal((Cout, Cin))
+
+
+@pytest.mark.parametrize("extra,H,W,p", [(1, 4, 4, 4), (2, 7, 7, 8), (1, 14, 14, 8), (3, 2, 6, 2)])
+def test_token_sequence_with_all_bases_kept_is_exact_backprop_on_every_token(extra, H, W, p):
+    x, gy, w = rand_tokens(95, 2, extra + H * W, 3, 5)
+    gx, gW = oracle.lbp_wht_backward_tokens(x, gy, w, (H, W), p, np.arange(p * p))
+    np.testing.assert_allclose(gx.reshape(-1, 3), gy.reshape(-1, 5) @ w, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(gW, gy.reshape(-1, 5).T @ x.reshape(-1, 3), rtol=0, atol=1e-12)
+
+
+def test_tokens_outside_the_grid_are_untouched_by_the_selection_and_by_the_grid():
+    # brute force on a tiny case: the class token's row of gx and its outer product in gW are those
+    # of Eq. 2 whatever is selected; the grid rows are Algorithm 1 on the grid alone
+    x, gy, w = rand_tokens(96, 2, 1 + 16, 2, 3)
+    idx = [0, 5]
+    gx, gW = oracle.lbp_wht_backward_tokens(x, gy, w, (4, 4), 4, idx)
+    for n in range(2):
+        for ci in range(2):
+            assert abs(gx[n, 0, ci] - sum(gy[n, 0, co] * w[co, ci] for co in range(3))) < 1e-12
+    xg, gyg = x[:, 1:].reshape(2, 4, 4, 2), gy[:, 1:].reshape(2, 4, 4, 3)
+    gxg, gWg = oracle.lbp_wht_backward(xg, gyg, w, 4, idx)
+    assert np.array_equal(gx[:, 1:].reshape(2, 4, 4, 2), gxg)
+    cls = np.zeros((3, 2))
+    for n in range(2):
+        for co in range(3):
+            for ci in range(2):
+                cls[co, ci] += gy[n, 0, co] * x[n, 0, ci]
+    np.testing.assert_allclose(gW - gWg, cls, rtol=0, atol=1e-12)
+
+
+def test_no_extra_tokens_reduces_to_the_padded_grid_call():
+    x, gy, w = rand_tokens(97, 3, 35, 4, 2)
+    idx = oracle.select_bases(4, 5, "l1")
+    a = oracle.lbp_wht_backward_tokens(x, gy, w, (5, 7), 4, idx)
+    b = oracle.lbp_wht_backward_padded(x.reshape(3, 5, 7, 4), gy.reshape(3, 5, 7, 2), w, 4, idx)
+    assert np.array_equal(a[0].reshape(3, 5, 7, 4), b[0]) and np.array_equal(a[1], b[1])
+
+
 @pytest.mark.parametrize("H,W,p,r,order", [(7, 7, 8, 10, "l1"), (6, 10, 4, 4, "linf"), (9, 3, 2, 3, "l1")])
 def test_padded_projection_is_a_masked_kronecker_product(H, W, p, r, order):
     # Different algorithm: per patch, multiply the (zero-filled) patch by the Kronecker basis matrix.
