@@ -37,7 +37,7 @@ def lbp_flops(wl, r):
     """Table 1 per patch (L = patch^2 tokens), summed over the patches of the batch."""
     L = wl.patch * wl.patch
     per_patch = (wl.Cin + wl.Cout) * L * r + 4 * wl.Cin * wl.Cout * r + wl.Cin * L * r
-    return float(per_patch) * wl.patches
+    return float(per_patch) * wl.patches + 4.0 * wl.Cin * wl.Cout * wl.N * wl.extra      # tokens outside the grid: Eq. 2
 
 
 def full_bp_flops(wl):
@@ -86,7 +86,11 @@ def main():
     idx = binding.select_bases(wl.patch, r, args.order)
     esz = 4 if wl.dtype == "f32" else 2
 
-    host = workloads.make_inputs(wl)
+    # token-sequence workloads ([N, extra + H*W, C], a class token in front of the grid) go through
+    # the *_tokens entry points; the exact backward sees the same tokens as one long row of a grid
+    seq = wl.extra > 0
+    T = wl.H * wl.W + wl.extra
+    host = workloads.make_token_inputs(wl, wl.extra) if seq else workloads.make_inputs(wl)
 
     def dev(a):
         if wl.dtype == "f32":
@@ -104,19 +108,27 @@ def main():
         s["gW"] = torch.empty(s["w"].shape, dtype=torch.float32, device="cuda")
         sets.append(s)
 
+    grid = (wl.H, wl.W)
+
+    def as_grid(t):      # [N, T, C] -> [N, 1, T, C] for the entry points that take grids
+        return t.view(wl.N, 1, T, t.shape[-1]) if seq else t
+
     def lbp_step(i):
         s = sets[i % n_sets]
-        binding.lbp_wht_backward(s["x"], s["gy"], s["w"], wl.patch, idx, gx=s["gx"], gW=s["gW"])
+        if seq:
+            binding.lbp_wht_backward_tokens(s["x"], s["gy"], s["w"], grid, wl.patch, idx, gx=s["gx"], gW=s["gW"])
+        else:
+            binding.lbp_wht_backward(s["x"], s["gy"], s["w"], wl.patch, idx, gx=s["gx"], gW=s["gW"])
 
     def full_step(i):
         s = sets[i % n_sets]
-        binding.full_bp_backward(s["x"], s["gy"], s["w"], gx=s["gx"], gW=s["gW"])
+        binding.full_bp_backward(as_grid(s["x"]), as_grid(s["gy"]), s["w"], gx=as_grid(s["gx"]), gW=s["gW"])
 
     def lib_step(i):
         s = sets[i % n_sets]
         G = s["gy"].view(-1, wl.Cout)
         torch.matmul(G, s["w"], out=s["gx"].view(-1, wl.Cin))
-        torch.matmul(G.t(), s["x"].view(-1, wl.Cin))
+        torch.matmul(G.t(), s["x"].view(-1, wl.Cin))      # allocates its result: the library's habit, not timed apart
 
     def timed(fn, steps, warmup):
         for i in range(warmup):
@@ -132,15 +144,26 @@ def main():
         wall_ms = (time.perf_counter() - t0) * 1e3
         return e0.elapsed_time(e1) / steps, wall_ms / steps
 
-    proj_bufs = [binding.wht_project_pair(s["x"], s["gy"], wl.patch, idx) for s in sets]
+    if seq:      # no two-tensor entry point for sequences: one projection call per tensor
+        proj_bufs = [(binding.wht_project_tokens(s["x"], grid, wl.patch, idx),
+                      binding.wht_project_tokens(s["gy"], grid, wl.patch, idx)) for s in sets]
+    else:
+        proj_bufs = [binding.wht_project_pair(s["x"], s["gy"], wl.patch, idx) for s in sets]
 
     def proj_step(i):
         s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
-        binding.wht_project_pair(s["x"], s["gy"], wl.patch, idx, x_r=xr, gy_r=gyr)
+        if seq:
+            binding.wht_project_tokens(s["x"], grid, wl.patch, idx, out=xr)
+            binding.wht_project_tokens(s["gy"], grid, wl.patch, idx, out=gyr)
+        else:
+            binding.wht_project_pair(s["x"], s["gy"], wl.patch, idx, x_r=xr, gy_r=gyr)
 
     def pre_step(i):
         s, (xr, _) = sets[i % n_sets], proj_bufs[i % n_sets]
-        binding.lbp_wht_backward_preprojected(xr, s["gy"], s["w"], wl.patch, idx, gx=s["gx"], gW=s["gW"])
+        if seq:
+            binding.lbp_wht_backward_tokens_preprojected(xr, s["gy"], s["w"], grid, wl.patch, idx, gx=s["gx"], gW=s["gW"])
+        else:
+            binding.lbp_wht_backward_preprojected(xr, s["gy"], s["w"], wl.patch, idx, gx=s["gx"], gW=s["gW"])
 
     ms_lbp, wall_lbp = timed(lbp_step, args.steps, args.warmup)
     # the same steps recorded once into a HIP graph (one step per buffer set) and replayed: what a
@@ -167,13 +190,13 @@ def main():
     # the two products launched one after the other (the timed steps above launch them as one grid
     # where the planner groups them).  An untimed step is queued first so that the GPU is still busy
     # while the host enqueues the profiled call: the events then bracket kernels, not launch latency.
-    n_prof = max(10, min(100, args.steps))
+    n_prof = 0 if seq else max(10, min(100, args.steps))      # the profiling entry point takes grids only
     stage = np.zeros(3)
     for i in range(n_prof):
         s = sets[i % n_sets]
         lbp_step(i + 1)
         stage += np.array(binding.lbp_wht_backward_profile(s["x"], s["gy"], s["w"], wl.patch, idx, s["gx"], s["gW"]))
-    stage /= n_prof
+    stage /= max(n_prof, 1)
 
     if args.calibration_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -182,18 +205,19 @@ def main():
         torch.cuda.synchronize()
 
     flops = lbp_flops(wl, r)
-    Mr = wl.patches * r
+    Mr = wl.patches * r + wl.N * wl.extra
     # dominant kernel: the projection launch.  Algorithmic bytes: read gy and x once, write the r/p^2
-    # fraction of each.
+    # fraction of each (and the tokens outside the grid as they are).
     proj_bytes = esz * (wl.tokens + Mr) * (wl.Cout + wl.Cin)
     proj_gbs = proj_bytes / (ms_proj * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "projection of gy and x (one launch)",
+    roofline = {"bound": "hbm", "kernel": "projection of gy and x (one launch per tensor, token sequences)" if seq
+                else "projection of gy and x (one launch)",
                 "achieved": round(proj_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(proj_gbs / HBM_PEAK_GBS, 4),
                 "traffic": read_traffic(f"wht_project_{wl.name}_hbm_traffic.txt"),
                 "algorithmic_bytes": proj_bytes, "avg_launch_us": round(ms_proj * 1e3, 2)}
     gemm_flops = 2.0 * Mr * wl.Cin * wl.Cout
-    stages = {
+    stages = None if seq else {
         "projection_us": round(stage[0] * 1e3, 2),
         "gw_product_us": round(stage[1] * 1e3, 2),
         "gx_product_reverse_projection_us": round(stage[2] * 1e3, 2),
@@ -213,7 +237,10 @@ def main():
         best = 1e30
         for _ in range(2):
             t0 = time.perf_counter()
-            oracle.lbp_wht_backward_padded(sample["x"], sample["gy"], sample["w"], wl.patch, np.asarray(idx))
+            if seq:
+                oracle.lbp_wht_backward_tokens(sample["x"], sample["gy"], sample["w"], grid, wl.patch, np.asarray(idx))
+            else:
+                oracle.lbp_wht_backward_padded(sample["x"], sample["gy"], sample["w"], wl.patch, np.asarray(idx))
             best = min(best, time.perf_counter() - t0)
         cpu = {"value": round(lbp_flops(wl_s, r) / best / 1e12, 6), "unit": "TFLOP/s",
                "cores": oracle.max_threads(), "kind": "oracle",
@@ -233,7 +260,8 @@ def main():
         "vs_baseline": None,
         "dtype": wl.dtype,
         "data": "synthetic",
-        "config": {"workload": wl.name, "N": wl.N, "grid": [wl.H, wl.W], "Cin": wl.Cin, "Cout": wl.Cout,
+        "config": {"workload": wl.name, "N": wl.N, "grid": [wl.H, wl.W], "extra_tokens": wl.extra, "Cin": wl.Cin,
+                   "Cout": wl.Cout,
                    "patch": wl.patch, "r": r, "order": args.order,
                    "cache": "warm" if args.warm_cache else f"cold ({n_sets} rotating buffer sets)"},
         "lbp_flops_per_step": flops,

@@ -42,7 +42,9 @@ def main():
             line = f"{name:22s} {r:3d} {order:>5s} FAILED (exit {res.returncode})"
         else:
             j = json.loads(res.stdout.strip().splitlines()[-1])
-            st, ro = j["stages"], j["roofline"]
+            ro = j["roofline"]
+            st = j["stages"] or {"projection_us": float("nan"), "gw_product_us": float("nan"),
+                                 "gx_product_reverse_projection_us": float("nan")}      # none for token sequences
             lib = j["library_gemm_full_bp_ms"]
             line = (f"{name:22s} {r:3d} {order:>5s} {j['ms_per_step'] * 1e3:8.1f} {j['full_bp_ms'] * 1e3:8.1f} "
                     f"{lib * 1e3:8.1f} {j['speedup_vs_full_bp']:7.2f} {j['speedup_vs_library_gemm_full_bp']:6.2f} "

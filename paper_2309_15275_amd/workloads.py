@@ -35,10 +35,11 @@ class Workload:
     orders: tuple         # basis orders: "l1", "linf"
     dtype: str            # "f32" or "bf16"
     seed: int
+    extra: int = 0        # tokens per image in front of the grid (class token ...)
 
     @property
     def tokens(self):
-        return self.N * self.H * self.W
+        return self.N * (self.H * self.W + self.extra)
 
     @property
     def patches(self):
@@ -60,6 +61,9 @@ WORKLOADS = {
     # Beyond the five: the 49-token maps of Section 3.3's worked example, (Cx, Cy, L) = (3072, 768, 49);
     # a 7 x 7 grid inside one zero-padded 8 x 8 patch.
     "pad_7x7_fc2": Workload("pad_7x7_fc2", 128, 7, 7, 3072, 768, 8, (8, 36), ("l1",), "bf16", 1006),
+    # ViT-B/16 on 224 x 224 images as the layer really sees it: a class token in front of 14 x 14
+    # patch tokens (197 per image); the grid is zero-padded to 16 x 16, the class token kept exact.
+    "vitb16_197_fc1": Workload("vitb16_197_fc1", 64, 14, 14, 768, 3072, 8, (8,), ("l1",), "bf16", 1007, 1),
 }
 
 

@@ -154,3 +154,26 @@ def test_workspace_bytes_and_strerror(lib):
     for code in range(0, -12, -1):
         assert binding.strerror(code) and "unknown status" not in binding.strerror(code)
     assert "unknown status" in binding.strerror(-99)
+
+
+def test_token_sequence_entry_points_check_their_arguments(lib):
+    sh = binding.LbpShape(2, 14, 14, 64, 128, 1, 0)
+    idx = (ctypes.c_int32 * 4)(0, 1, 8, 9)
+    f = lib.lbp_wht_backward_tokens
+    args = lambda extra, x=X, gx=GX, r=4: (P(x) if x else None, P(GY), P(W_), ctypes.byref(sh), extra, 8, idx, r,
+                                           P(gx) if gx else None, P(GW), None)
+    assert f(*args(1, x=0)) == -1
+    assert f(*args(-1)) == -2
+    assert f(*args(1, r=0)) == -4
+    # gx is [N][1 + 196][Cin]: a buffer that starts inside x's 2*197*64 bf16 values overlaps it
+    assert f(*args(1, gx=X + 2 * 196 * 64 * 2)) == -7
+    assert f(*args(1, gx=X + 2 * 197 * 64 * 2)) in (0, -11)      # right behind x: no overlap
+    g = lib.lbp_wht_project_tokens
+    assert g(None, 2, 14, 14, 1, 64, 1, 8, idx, 4, P(GX), None) == -1
+    assert g(P(X), 2, 14, 14, -3, 64, 1, 8, idx, 4, P(GX), None) == -2
+    assert g(P(X), 2, 14, 14, 1, 64, 1, 8, idx, 4, P(X), None) == -7
+    h = lib.lbp_wht_backward_tokens_preprojected
+    assert h(P(X), P(GY), P(W_), ctypes.byref(sh), 1, 8, idx, 0, P(GX), P(GW), None) == -4
+    # workspace: extra tokens add rows to the projected tensors
+    assert binding.workspace_bytes(sh, 8, 4, extra=1) > binding.workspace_bytes(sh, 8, 4)
+    assert binding.workspace_bytes(sh, 8, 4, extra=-1) == 0
