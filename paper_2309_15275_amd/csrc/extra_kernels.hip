@@ -5,34 +5,15 @@
 // N * extra rows of C channels.
 #include "device_utils.h"
 #include "kernels.h"
+#include "wht_device.h"
 
 namespace lbp {
 namespace {
 
-// one thread: 16 bytes of one row (8 bf16 or 4 fp32)
 template <bool BF16>
-__global__ __launch_bounds__(256) void gather_extra_kernel(const uint4 *__restrict__ in, uint4 *__restrict__ out,
-                                                           long items, int Cv, int extra, long img_vecs, float scale)
+__global__ __launch_bounds__(256) void gather_extra_kernel(ExtraRows x)
 {
-    const long item = (long)blockIdx.x * 256 + threadIdx.x;
-    if (item >= items) return;
-    const long row = item / Cv;
-    const int cv = (int)(item - row * Cv);
-    const long n = row / extra;
-    const int e = (int)(row - n * extra);
-    uint4 v = in[(size_t)n * img_vecs + (size_t)e * Cv + cv];
-    if (BF16) {
-        v.x = pack_bf16x2(bf16_lo_to_f32(v.x) * scale, bf16_hi_to_f32(v.x) * scale);
-        v.y = pack_bf16x2(bf16_lo_to_f32(v.y) * scale, bf16_hi_to_f32(v.y) * scale);
-        v.z = pack_bf16x2(bf16_lo_to_f32(v.z) * scale, bf16_hi_to_f32(v.z) * scale);
-        v.w = pack_bf16x2(bf16_lo_to_f32(v.w) * scale, bf16_hi_to_f32(v.w) * scale);
-    } else {
-        v.x = __float_as_uint(__uint_as_float(v.x) * scale);
-        v.y = __float_as_uint(__uint_as_float(v.y) * scale);
-        v.z = __float_as_uint(__uint_as_float(v.z) * scale);
-        v.w = __float_as_uint(__uint_as_float(v.w) * scale);
-    }
-    out[item] = v;
+    copy_extra_rows<BF16>(x, blockIdx.x, threadIdx.x);
 }
 
 // one thread: 4 consecutive channels of one row, summed over the slices in a fixed order
@@ -65,16 +46,13 @@ hipError_t launch_gather_extra(const void *in, void *out, int N, int extra, long
                                float scale, hipStream_t stream)
 {
     if (extra <= 0 || N <= 0) return hipSuccess;
-    const bool bf16 = dtype == LBP_BF16;
-    const int Cv = bf16 ? C / 8 : C / 4;
-    const long items = (long)N * extra * Cv;
-    const unsigned blocks = (unsigned)((items + 255) / 256);
-    if (bf16)
-        hipLaunchKernelGGL(gather_extra_kernel<true>, dim3(blocks), dim3(256), 0, stream, (const uint4 *)in,
-                           (uint4 *)out, items, Cv, extra, img_tokens * Cv, scale);
+    ExtraRows x{};
+    set_extra_rows(x, 0, in, out, N, extra, img_tokens, C, dtype, scale);
+    set_extra_rows(x, 1, nullptr, nullptr, N, extra, img_tokens, C, dtype, scale);
+    if (dtype == LBP_BF16)
+        hipLaunchKernelGGL(gather_extra_kernel<true>, dim3(x.blocks[0]), dim3(256), 0, stream, x);
     else
-        hipLaunchKernelGGL(gather_extra_kernel<false>, dim3(blocks), dim3(256), 0, stream, (const uint4 *)in,
-                           (uint4 *)out, items, Cv, extra, img_tokens * Cv, scale);
+        hipLaunchKernelGGL(gather_extra_kernel<false>, dim3(x.blocks[0]), dim3(256), 0, stream, x);
     return hipGetLastError();
 }
 

@@ -15,15 +15,18 @@ enum class GemmPath { kAuto = 0, kSimple = 1 };
 // tensors are then [N][extra + H*W][C] and those tokens belong to no patch (the projections skip
 // them, see launch_gather_extra / launch_scatter_extra).
 //
-// p(.) of Eq. 6 per patch: in [N][H][W][C] -> out [P*r][C], both of `dtype`.
+// p(.) of Eq. 6 per patch: in [N][H][W][C] -> out [P*r][C], both of `dtype`.  With extra > 0
+// the N*extra tokens outside the grid follow as rows P*r ..., multiplied by extra_scale.
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
-                          const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra = 0);
+                          const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra = 0,
+                          float extra_scale = 1.0f);
 
 // The same for two tensors on one token grid (gy and x of a backward call) in ONE launch where
 // the kernels allow it, so that the second, smaller tensor fills the tail of the first.
 hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
                                int N, int H, int W, int dtype, const BasisPlan &plan, WhtPath path,
-                               hipStream_t stream, int extra = 0);
+                               hipStream_t stream, int extra = 0, float extra_scale0 = 1.0f,
+                               float extra_scale1 = 1.0f);
 
 // p^-1(.) of Eq. 7 per patch with the 1/p^2 factor: in fp32 [slices][P*r][C] (the slices are
 // summed first: split-K partial results) -> out [N][H][W][C] of `dtype`.  slice_rows > 0: rows
@@ -43,7 +46,8 @@ hipError_t launch_scatter_extra(const float *in, int slices, size_t slice_stride
 // Matrix-core form of the two projections (bf16 tensors, any selection, any patch up to 16).
 bool wht_mfma_supported(const BasisPlan &plan, int dtype, int C);
 hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
-                               int N, int H, int W, const BasisPlan &plan, hipStream_t stream, int extra = 0);
+                               int N, int H, int W, const BasisPlan &plan, hipStream_t stream, int extra = 0,
+                               float extra_scale0 = 1.0f, float extra_scale1 = 1.0f);
 hipError_t launch_unproject_mfma(const float *in, int slices, void *out, int N, int H, int W, int C,
                                  const BasisPlan &plan, hipStream_t stream, int extra = 0, long slice_rows = 0);
 

@@ -306,9 +306,8 @@ int lbp_wht_project_tokens(const void *in, int N, int H, int W, int extra, int C
     DeviceState *st;
     rc = current_device(&dev, &st);
     if (rc) return rc;
-    LBP_HIP(lbp::launch_project(in, out, N, H, W, C, dtype, plan, wht_path_from_env(), (hipStream_t)stream, extra));
-    LBP_HIP(lbp::launch_gather_extra(in, (char *)out + Mq * C * esz, N, extra, (long)H * W + extra, C, dtype, 1.0f,
-                                     (hipStream_t)stream));
+    LBP_HIP(lbp::launch_project(in, out, N, H, W, C, dtype, plan, wht_path_from_env(), (hipStream_t)stream, extra,
+                                1.0f));
     return LBP_OK;
 }
 
@@ -457,7 +456,6 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     const lbp::WhtPath path = wht_path_from_env();
     const int N = shape->N, H = shape->H, Wd = shape->W, Cin = shape->Cin, Cout = shape->Cout;
     const int dt = shape->dtype;
-    const size_t esz = lbp::dtype_size(dt);
     const long img_tokens = (long)H * Wd + extra;
     const float inv_pp = 1.0f / (float)(patch * patch);
     void *gy_r = base + ws.gy_r;
@@ -468,20 +466,14 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     if (ev) LBP_HIP(hipEventRecord(ev[0], s));
     // g^y = WHT(gy; I) is needed by both products; x^ = WHT(x; I) only by the weight gradient
     // (first two statements of Algorithm 1).  One launch covers both tensors.
+    // Tokens outside the grid join the projected tensors as they are (Eq. 2 stays exact for them);
+    // their g_y rows carry patch^2, a power of two, which the 1/patch^2 of both products takes away.
+    const float pp = (float)(patch * patch);
     if (gW && !x_projected)
-        LBP_HIP(lbp::launch_project_pair(gy, gy_r, Cout, x, base + ws.x_r, Cin, N, H, Wd, dt, plan, path, s, extra));
+        LBP_HIP(lbp::launch_project_pair(gy, gy_r, Cout, x, base + ws.x_r, Cin, N, H, Wd, dt, plan, path, s, extra, pp,
+                                         1.0f));
     else
-        LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s, extra));
-    if (extra > 0) {
-        // Tokens outside the grid join the projected tensors as they are: Eq. 2 stays exact for
-        // them.  Their g_y rows carry patch^2 (a power of two), which the 1/patch^2 of both
-        // products takes away again.
-        LBP_HIP(lbp::launch_gather_extra(gy, (char *)gy_r + (size_t)Mq * Cout * esz, N, extra, img_tokens, Cout, dt,
-                                         (float)(patch * patch), s));
-        if (gW && !x_projected)
-            LBP_HIP(lbp::launch_gather_extra(x, base + ws.x_r + (size_t)Mq * Cin * esz, N, extra, img_tokens, Cin, dt,
-                                             1.0f, s));
-    }
+        LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s, extra, pp));
     if (ev) LBP_HIP(hipEventRecord(ev[1], s));
     // g~w = g^w = g^y^T x^  (with the 1/p^2 of the normalisation)
     lbp::GemmArgs gw_args, g;

@@ -59,6 +59,63 @@ inline GridGeom make_geom(int H, int W, int patch, int extra = 0)
     return g;
 }
 
+// Tokens outside the grid (a class token in front of the patch tokens) belong to no patch: their
+// rows are copied, scaled, behind the projected rows of their tensor.  Up to two tensors; in a
+// projection launch the copies are done by workgroups appended to the grid (256 threads each,
+// one thread per 16 bytes), so that they cost no launch of their own.
+struct ExtraRows {
+    const uint4 *in[2];     // the token tensors
+    uint4 *out[2];          // first appended row of each projected tensor
+    long items[2];          // 16-byte pieces to copy: N * extra * Cv
+    long img_vecs[2];       // 16-byte pieces of one image: tokens per image * Cv
+    int Cv[2];              // 16-byte pieces of one token
+    float scale[2];
+    unsigned blocks[2];     // workgroups per tensor
+    int extra;              // tokens per image in front of the grid
+};
+
+template <bool BF16>
+__device__ __forceinline__ void copy_extra_rows(const ExtraRows &x, unsigned block, int tid)
+{
+    const int i = block >= x.blocks[0] ? 1 : 0;
+    const long item = (long)(block - (i ? x.blocks[0] : 0u)) * 256 + tid;
+    if (item >= x.items[i]) return;
+    const int Cv = x.Cv[i];
+    const long row = item / Cv;
+    const int cv = (int)(item - row * Cv);
+    const long n = row / x.extra;
+    const int e = (int)(row - n * x.extra);
+    const float scale = x.scale[i];
+    uint4 v = x.in[i][(size_t)n * x.img_vecs[i] + (size_t)e * Cv + cv];
+    if (BF16) {
+        v.x = pack_bf16x2(bf16_lo_to_f32(v.x) * scale, bf16_hi_to_f32(v.x) * scale);
+        v.y = pack_bf16x2(bf16_lo_to_f32(v.y) * scale, bf16_hi_to_f32(v.y) * scale);
+        v.z = pack_bf16x2(bf16_lo_to_f32(v.z) * scale, bf16_hi_to_f32(v.z) * scale);
+        v.w = pack_bf16x2(bf16_lo_to_f32(v.w) * scale, bf16_hi_to_f32(v.w) * scale);
+    } else {
+        v.x = __float_as_uint(__uint_as_float(v.x) * scale);
+        v.y = __float_as_uint(__uint_as_float(v.y) * scale);
+        v.z = __float_as_uint(__uint_as_float(v.z) * scale);
+        v.w = __float_as_uint(__uint_as_float(v.w) * scale);
+    }
+    x.out[i][item] = v;
+}
+
+// Fills one slot of an ExtraRows: tensor `in` [N][img_tokens][C] of `dtype`, rows appended at `out_rows`.
+inline void set_extra_rows(ExtraRows &x, int slot, const void *in, void *out_rows, int N, int extra, long img_tokens,
+                           int C, int dtype, float scale)
+{
+    const int Cv = dtype == LBP_BF16 ? C / 8 : C / 4;
+    x.in[slot] = (const uint4 *)in;
+    x.out[slot] = (uint4 *)out_rows;
+    x.items[slot] = in ? (long)N * extra * Cv : 0;
+    x.img_vecs[slot] = img_tokens * Cv;
+    x.Cv[slot] = Cv > 0 ? Cv : 1;
+    x.scale[slot] = scale;
+    x.blocks[slot] = (unsigned)((x.items[slot] + 255) / 256);
+    x.extra = extra > 0 ? extra : 1;
+}
+
 // Sum-pool a P x P patch over 2^MH x 2^MW token groups, then transform the pooled patch.
 template <int P, int MH, int MW>
 __device__ __forceinline__ void pooled_transform(const float (&v)[P * P],

@@ -37,10 +37,14 @@ struct ProjTensor {
 
 template <int LP, int MH, int MW, bool BF16>
 __global__ __launch_bounds__(256) void wht_project_reg_kernel(ProjTensor t0, ProjTensor t1, GridGeom g,
-                                                              PooledSel sel, int r)
+                                                              PooledSel sel, int r, ExtraRows xr)
 {
     constexpr int P = 1 << LP;
     constexpr int NC = (P >> MH) * (P >> MW);
+    if (blockIdx.x >= t0.blocks + t1.blocks) {      // appended workgroups: tokens outside the grid
+        copy_extra_rows<BF16>(xr, blockIdx.x - (t0.blocks + t1.blocks), threadIdx.x);
+        return;
+    }
     const bool second = blockIdx.x >= t0.blocks;
     const ProjTensor &t = second ? t1 : t0;
     const int Cd = t.Cd;
@@ -342,6 +346,7 @@ struct Second {
     void *out = nullptr;
     long items = 0;
     int Cd = 0;
+    ExtraRows xr{};      // tokens outside the grid, copied by workgroups appended to the launch
 };
 
 template <bool UNPROJECT, int LP, int MH, int MW, bool BF16>
@@ -353,8 +358,9 @@ void launch_reg_one(const void *in, void *out, long items, int Cd, const GridGeo
         ProjTensor t0{(const uint32_t *)in, (uint32_t *)out, items, Cd, blocks};
         ProjTensor t1{(const uint32_t *)sec.in, (uint32_t *)sec.out, sec.items, sec.Cd > 0 ? sec.Cd : 1,
                       (unsigned)((sec.items + 255) / 256)};
-        hipLaunchKernelGGL((wht_project_reg_kernel<LP, MH, MW, BF16>), dim3(t0.blocks + t1.blocks),
-                           dim3(256), 0, stream, t0, t1, g, sel, r);
+        hipLaunchKernelGGL((wht_project_reg_kernel<LP, MH, MW, BF16>),
+                           dim3(t0.blocks + t1.blocks + sec.xr.blocks[0] + sec.xr.blocks[1]), dim3(256), 0, stream, t0,
+                           t1, g, sel, r, sec.xr);
         return;
     }
     if (UNPROJECT)
@@ -391,7 +397,7 @@ void launch_reg_mh(int mh, int mw, const void *in, void *out, long items, int Cd
 template <bool UNPROJECT>
 hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int dtype,
                       const BasisPlan &plan, Slices sl, hipStream_t s, int extra, const void *in2 = nullptr,
-                      void *out2 = nullptr, int C2 = 0)
+                      void *out2 = nullptr, int C2 = 0, float extra_scale = 1.0f, float extra_scale2 = 1.0f)
 {
     const bool bf16 = dtype == LBP_BF16;
     const int Cd = bf16 ? C / 2 : C;
@@ -403,6 +409,14 @@ hipError_t launch_reg(const void *in, void *out, int N, int H, int W, int C, int
         sec.out = out2;
         sec.Cd = bf16 ? C2 / 2 : C2;
         sec.items = Q * sec.Cd;
+    }
+    if (!UNPROJECT && extra > 0) {
+        const size_t esz = dtype_size(dtype);
+        const size_t rows = (size_t)Q * plan.r;
+        const long img_tokens = (long)H * W + extra;
+        set_extra_rows(sec.xr, 0, in, (char *)out + rows * C * esz, N, extra, img_tokens, C, dtype, extra_scale);
+        set_extra_rows(sec.xr, 1, in2, in2 ? (char *)out2 + rows * C2 * esz : nullptr, N, extra, img_tokens,
+                       in2 ? C2 : C, dtype, extra_scale2);
     }
     GridGeom g = make_geom(H, W, plan.patch, extra);
     PooledSel sel;
@@ -474,29 +488,48 @@ bool use_mfma_path(const BasisPlan &plan, WhtPath path, int dtype, int C)
     return (plan.patch >> plan.mh) * (plan.patch >> plan.mw) > 16;
 }
 
+// The generic kernels have a two-dimensional grid: the tokens outside the grid get a launch of their own.
+hipError_t gather_after_generic(const void *in, void *out, int N, int H, int W, int C, int dtype, const BasisPlan &plan,
+                                int extra, float scale, hipStream_t stream)
+{
+    if (extra <= 0) return hipSuccess;
+    const size_t rows = (size_t)patch_count(N, H, W, plan.patch) * plan.r;
+    return launch_gather_extra(in, (char *)out + rows * C * dtype_size(dtype), N, extra, (long)H * W + extra, C, dtype,
+                               scale, stream);
+}
+
 }  // namespace
 
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
-                          const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra)
+                          const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra, float extra_scale)
 {
     if (use_mfma_path(plan, path, dtype, C))
-        return launch_project_mfma(in, out, C, nullptr, nullptr, 0, N, H, W, plan, stream, extra);
+        return launch_project_mfma(in, out, C, nullptr, nullptr, 0, N, H, W, plan, stream, extra, extra_scale, 1.0f);
     if (use_register_path(plan, path))
-        return launch_reg<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream, extra);
-    return launch_generic<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream, extra);
+        return launch_reg<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream, extra, nullptr, nullptr, 0,
+                                 extra_scale, 1.0f);
+    hipError_t e = launch_generic<false>(in, out, N, H, W, C, dtype, plan, Slices{}, stream, extra);
+    if (e != hipSuccess) return e;
+    return gather_after_generic(in, out, N, H, W, C, dtype, plan, extra, extra_scale, stream);
 }
 
 hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
                                int N, int H, int W, int dtype, const BasisPlan &plan, WhtPath path,
-                               hipStream_t stream, int extra)
+                               hipStream_t stream, int extra, float extra_scale0, float extra_scale1)
 {
     if (use_mfma_path(plan, path, dtype, C0) && use_mfma_path(plan, path, dtype, C1))
-        return launch_project_mfma(in0, out0, C0, in1, out1, C1, N, H, W, plan, stream, extra);
+        return launch_project_mfma(in0, out0, C0, in1, out1, C1, N, H, W, plan, stream, extra, extra_scale0,
+                                   extra_scale1);
     if (use_register_path(plan, path))
-        return launch_reg<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream, extra, in1, out1, C1);
+        return launch_reg<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream, extra, in1, out1, C1,
+                                 extra_scale0, extra_scale1);
     hipError_t e = launch_generic<false>(in0, out0, N, H, W, C0, dtype, plan, Slices{}, stream, extra);
     if (e != hipSuccess) return e;
-    return launch_generic<false>(in1, out1, N, H, W, C1, dtype, plan, Slices{}, stream, extra);
+    e = launch_generic<false>(in1, out1, N, H, W, C1, dtype, plan, Slices{}, stream, extra);
+    if (e != hipSuccess) return e;
+    e = gather_after_generic(in0, out0, N, H, W, C0, dtype, plan, extra, extra_scale0, stream);
+    if (e != hipSuccess) return e;
+    return gather_after_generic(in1, out1, N, H, W, C1, dtype, plan, extra, extra_scale1, stream);
 }
 
 hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H, int W, int C,

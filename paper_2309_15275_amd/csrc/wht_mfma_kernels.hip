@@ -90,10 +90,14 @@ __device__ __forceinline__ bf16x8_t read_b_frag(const unsigned char *tile, int k
 // ---------------------------------------------------------------------------------------------
 template <int KSTEPS, int MTILES, bool CACHE_A>
 __global__ __launch_bounds__(256) void wht_project_mfma_kernel(MfmaTensor t0, MfmaTensor t1, GridGeom g,
-                                                               NatTable nat, int r, int items_per_wg)
+                                                               NatTable nat, int r, int items_per_wg, ExtraRows xr)
 {
     constexpr int P2PAD = KSTEPS * 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    if (blockIdx.x >= t0.blocks + t1.blocks) {      // appended workgroups: tokens outside the grid
+        copy_extra_rows<true>(xr, blockIdx.x - (t0.blocks + t1.blocks), threadIdx.x);
+        return;
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int p = g.patch, p2 = p * p;
     const int li = lane & 31, kg = lane >> 5;
@@ -445,7 +449,8 @@ bool wht_mfma_supported(const BasisPlan &plan, int dtype, int C)
 }
 
 hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,
-                               int N, int H, int W, const BasisPlan &plan, hipStream_t stream, int extra)
+                               int N, int H, int W, const BasisPlan &plan, hipStream_t stream, int extra,
+                               float extra_scale0, float extra_scale1)
 {
     const long Q = patch_count(N, H, W, plan.patch);
     GridGeom g = make_geom(H, W, plan.patch, extra);
@@ -467,7 +472,15 @@ hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *
     if (t[1].chunks == 0) t[1].chunks = 1;
     const int ipw = items_per_wg(all_items);
     for (int i = 0; i < 2; ++i) t[i].blocks = (unsigned)((t[i].items + ipw - 1) / ipw);
-    const unsigned blocks = t[0].blocks + t[1].blocks;
+    ExtraRows xr{};
+    if (extra > 0) {
+        const size_t rows = (size_t)Q * plan.r;
+        const long img_tokens = (long)H * W + extra;
+        set_extra_rows(xr, 0, in0, (char *)out0 + rows * C0 * 2, N, extra, img_tokens, C0, LBP_BF16, extra_scale0);
+        set_extra_rows(xr, 1, in1, in1 ? (char *)out1 + rows * C1 * 2 : nullptr, N, extra, img_tokens, in1 ? C1 : C0,
+                       LBP_BF16, extra_scale1);
+    }
+    const unsigned blocks = t[0].blocks + t[1].blocks + xr.blocks[0] + xr.blocks[1];
     const int p2 = plan.patch * plan.patch;
     const int p2pad = p2 < 16 ? 16 : p2;
     const int lds = (p2pad > plan.r ? p2pad : plan.r) * S_IN;     // S_IN >= S_OUT: covers both uses
@@ -476,7 +489,7 @@ hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *
         auto kern = wht_project_mfma_kernel<KS, MT, CACHE>;                                         \
         hipError_t e = set_lds(kern, lds);                                                          \
         if (e != hipSuccess) return e;                                                              \
-        hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, stream, t[0], t[1], g, nat, plan.r, ipw); \
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, stream, t[0], t[1], g, nat, plan.r, ipw, xr); \
     } while (0)
     if (p2pad == 16) LBP_LAUNCH(1, 1, true);
     else if (p2pad == 64 && plan.r <= 32) LBP_LAUNCH(4, 1, true);
