@@ -16,8 +16,10 @@ reverse projection, per patch, summed over the batch) per second.  The line also
                                     as a second opinion on the comparison point,
   preprojected_x_ms_per_step        lbp_wht_backward_preprojected: x^ kept from the forward pass,
   stages                            HIP-event time of each stage inside the call,
-  roofline                          the dominant kernel (projection of gy and x, one launch, HBM
-                                    bound): algorithmic bytes / its average duration,
+  roofline                          the kernel that takes the larger share of a step: the grouped launch
+                                    of the two products (bf16 MFMA: algorithmic FLOPs / its average
+                                    duration) or the projection of gy and x (HBM: algorithmic bytes /
+                                    its average duration); roofline_second is the other one,
   cpu_baseline                      the CPU oracle timed on this machine's host cores.
 """
 import argparse
@@ -165,6 +167,10 @@ def main():
         else:
             binding.lbp_wht_backward_preprojected(xr, s["gy"], s["w"], wl.patch, idx, gx=s["gx"], gW=s["gW"])
 
+    def prod_step(i):      # the products alone, from projected tensors (grid workloads)
+        s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
+        binding.lbp_wht_products(xr, gyr, s["w"], (wl.N, wl.H, wl.W), wl.patch, idx, gx=s["gx"], gW=s["gW"])
+
     ms_lbp, wall_lbp = timed(lbp_step, args.steps, args.warmup)
     # the same steps recorded once into a HIP graph (one step per buffer set) and replayed: what a
     # training loop that captures its backward pass sees; launch gaps between the kernels shrink
@@ -181,6 +187,7 @@ def main():
     ms_pre, _ = timed(pre_step, args.steps, args.warmup)
     # the dominant kernel by itself, back to back on the launch stream (same rotation of buffers)
     ms_proj, _ = timed(proj_step, args.steps, args.warmup)
+    ms_prod = None if seq else timed(prod_step, args.steps, args.warmup)[0]
     ms_full, _ = timed(full_step, max(10, args.steps // 4), max(3, args.warmup // 4))
     ms_lib = None
     if not args.no_library_gemm:
@@ -210,13 +217,30 @@ def main():
     # fraction of each (and the tokens outside the grid as they are).
     proj_bytes = esz * (wl.tokens + Mr) * (wl.Cout + wl.Cin)
     proj_gbs = proj_bytes / (ms_proj * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "projection of gy and x (one launch per tensor, token sequences)" if seq
-                else "projection of gy and x (one launch)",
+    roof_proj = {"bound": "hbm", "kernel": "projection of gy and x (one launch per tensor, token sequences)" if seq
+                 else "projection of gy and x (one launch)",
                 "achieved": round(proj_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(proj_gbs / HBM_PEAK_GBS, 4),
                 "traffic": read_traffic(f"wht_project_{wl.name}_hbm_traffic.txt"),
                 "algorithmic_bytes": proj_bytes, "avg_launch_us": round(ms_proj * 1e3, 2)}
     gemm_flops = 2.0 * Mr * wl.Cin * wl.Cout
+    # the two products (one grouped launch where the planner groups them; with the reverse projection
+    # in the epilogue where it can be fused): 2 * M_r * Cin * Cout FLOPs each against the dense bf16
+    # (fp32: vector fp32) peak; timed back to back from projected tensors on the launch stream
+    roof_prod = None
+    if ms_prod is not None:
+        peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else 157.3
+        tf = 2.0 * gemm_flops / (ms_prod * 1e-3) / 1e12
+        roof_prod = {"bound": "mfma" if wl.dtype == "bf16" else "alu",
+                     "kernel": "the two products of a call: g^y W with Eq. 7 in the epilogue and g^y^T x^ (one grouped launch)",
+                     "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
+                     "traffic": read_traffic(f"gemm_products_{wl.name}_hbm_traffic.txt"),
+                     "algorithmic_flops": 2.0 * gemm_flops, "avg_launch_us": round(ms_prod * 1e3, 2)}
+    # `roofline` is the kernel that takes the larger share of a step, `roofline_second` the other
+    if roof_prod is not None and ms_prod > ms_proj:
+        roofline, roofline_second = roof_prod, roof_proj
+    else:
+        roofline, roofline_second = roof_proj, roof_prod
     stages = None if seq else {
         "projection_us": round(stage[0] * 1e3, 2),
         "gw_product_us": round(stage[1] * 1e3, 2),
@@ -276,6 +300,7 @@ def main():
         "host_wall_ms_per_step": round(wall_lbp, 5),
         "stages": stages,
         "roofline": roofline,
+        "roofline_second": roofline_second,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

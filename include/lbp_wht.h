@@ -138,6 +138,16 @@ int lbp_wht_backward_preprojected(const void *x_r, const void *gy, const void *W
                                   void *gx, void *gW, void *stream);
 
 /*
+ * Statements 3 to 6 of Algorithm 1 alone, from tensors that are already projected: x_r = x^ [P*r][Cin]
+ * and gy_r = g^y [P*r][Cout] (both of shape->dtype, made with the SAME basis_idx by lbp_wht_project_pair
+ * or lbp_wht_project), W [Cout][Cin].  g~w = (1/patch^2) g^y^T x^ and g~x = (1/patch^2) WHT^-1(g^y W; I)
+ * as in lbp_wht_backward, with bit-identical results.  For callers that project elsewhere (or time
+ * the products by themselves).
+ */
+int lbp_wht_products(const void *x_r, const void *gy_r, const void *W, const lbp_shape_t *shape, int patch,
+                     const int32_t *basis_idx, int r, void *gx, void *gW, void *stream);
+
+/*
  * Token sequences with tokens that are not on the grid.  A ViT layer sees, per image, `extra` tokens
  * (a class token, a distillation token) followed by the H*W patch tokens: x, gy and gx are
  * [N][extra + H*W][C] here.  Algorithm 1 is stated for the H x W map; the paper does not say what

@@ -21,7 +21,7 @@ EXPORTS = ("lbp_wht_select_bases", "lbp_wht_select_lhe", "lbp_wht_energy", "lbp_
            "lbp_wht_project_pair", "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
            "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version",
            "lbp_wht_backward_tokens", "lbp_wht_project_tokens", "lbp_wht_backward_tokens_preprojected",
-           "lbp_wht_workspace_bytes_tokens")
+           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products")
 
 
 class LbpShape(ctypes.Structure):
@@ -58,6 +58,7 @@ def load():
     lib.lbp_wht_energy_workspace_bytes.argtypes = [ctypes.c_int] * 6
     lib.lbp_wht_energy_workspace_bytes.restype = ctypes.c_size_t
     lib.lbp_wht_backward_preprojected.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.lbp_wht_products.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
     lib.lbp_wht_backward_profile.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp,
                                              ctypes.POINTER(ctypes.c_float)]
     lib.full_bp_backward.argtypes = [vp, vp, vp, shp, vp, vp, vp]
@@ -201,6 +202,30 @@ def lbp_wht_backward_preprojected(x_r, gy, w, patch, basis_idx, gx=None, gW=None
             _dev_tensor(x_r, "x_r", gy.dtype), _dev_tensor(gy, "gy"), _dev_tensor(w, "w", gy.dtype),
             ctypes.byref(shape), int(patch), idx, r,
             _dev_tensor(gx, "gx", gy.dtype) if gx is not None else None,
+            _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
+    return gx, gW
+
+
+def lbp_wht_products(x_r, gy_r, w, grid_shape, patch, basis_idx, gx=None, gW=None, want_gx=True, want_gw=True,
+                     gw_dtype=torch.float32, stream=None):
+    """Statements 3-6 of Algorithm 1 from projected tensors: x_r [P*r,Cin], gy_r [P*r,Cout] (wht_project_pair),
+    w [Cout,Cin]; grid_shape = (N, H, W) of the token grids.  Returns (gx [N,H,W,Cin], gW)."""
+    N, H, W = grid_shape
+    Cout, Cin = w.shape
+    idx, r = _idx_array(basis_idx)
+    rows = patch_count(N, H, W, patch) * r
+    if tuple(x_r.shape) != (rows, Cin) or tuple(gy_r.shape) != (rows, Cout):
+        raise ValueError("shapes must be x_r[P*r,Cin], gy_r[P*r,Cout], w[Cout,Cin]")
+    shape = LbpShape(N, H, W, Cin, Cout, _DTYPES[gy_r.dtype], _DTYPES[gw_dtype])
+    if want_gx and gx is None:
+        gx = torch.empty((N, H, W, Cin), dtype=gy_r.dtype, device=gy_r.device)
+    if want_gw and gW is None:
+        gW = torch.empty(w.shape, dtype=gw_dtype, device=w.device)
+    with torch.cuda.device(gy_r.device):
+        _check(load().lbp_wht_products(
+            _dev_tensor(x_r, "x_r", gy_r.dtype), _dev_tensor(gy_r, "gy_r"), _dev_tensor(w, "w", gy_r.dtype),
+            ctypes.byref(shape), int(patch), idx, r,
+            _dev_tensor(gx, "gx", gy_r.dtype) if gx is not None else None,
             _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
     return gx, gW
 

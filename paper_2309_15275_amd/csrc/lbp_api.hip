@@ -123,7 +123,7 @@ lbp::WhtPath wht_path_from_env()
 
 // Pointer, alias and alignment rules common to both backward entry points.
 int validate_buffers(const void *x, const void *gy, const void *W, const lbp_shape_t *s, void *gx,
-                     void *gW, size_t x_rows = 0, int extra = 0)
+                     void *gW, size_t x_rows = 0, int extra = 0, size_t gy_rows = 0)
 {
     if (!x || !gy || !W) return LBP_ERR_NULL;
     if (!gx && !gW) return LBP_ERR_NULL;
@@ -132,7 +132,8 @@ int validate_buffers(const void *x, const void *gy, const void *W, const lbp_sha
     if (rc) return rc;
     size_t esz = lbp::dtype_size(s->dtype);
     size_t M = (size_t)s->N * ((size_t)s->H * s->W + extra);
-    size_t nx = (x_rows ? x_rows : M) * s->Cin * esz, ngy = M * s->Cout * esz, nw = (size_t)s->Cout * s->Cin * esz;
+    size_t nx = (x_rows ? x_rows : M) * s->Cin * esz, ngy = (gy_rows ? gy_rows : M) * s->Cout * esz;
+    size_t nw = (size_t)s->Cout * s->Cin * esz;
     size_t ngx = M * s->Cin * esz, ngw = (size_t)s->Cout * s->Cin * lbp::dtype_size(s->gw_dtype);
     const void *ins[3] = {x, gy, W};
     size_t in_bytes[3] = {nx, ngy, nw};
@@ -417,9 +418,10 @@ namespace {
 // Algorithm 1.  `ev`, when not NULL, holds 4 events recorded on the stream before the projection,
 // after it, after the weight-gradient product and after the input-gradient product.
 // x_projected: `x` already is x^ = WHT(x; I), [P*r][Cin], kept from the forward pass.
+// gy_projected: `gy` already is g^y = WHT(gy; I) too (only with x_projected): the products alone.
 int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_t *shape, int patch,
                   const int32_t *basis_idx, int r, void *gx, void *gW, void *stream, hipEvent_t *ev,
-                  bool x_projected = false, int extra = 0)
+                  bool x_projected = false, int extra = 0, bool gy_projected = false)
 {
     if (!shape || !basis_idx) return LBP_ERR_NULL;
     if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
@@ -432,7 +434,8 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     // rows of the projected tensors: (patch, basis) pairs first, then the tokens outside the grid
     const long Mq = lbp::patch_count(shape->N, shape->H, shape->W, patch) * r;
     const long Mr = Mq + (long)shape->N * extra;
-    rc = validate_buffers(x, gy, W, shape, gx, gW, x_projected ? (size_t)Mr : 0, extra);
+    if (gy_projected && (!x_projected || extra != 0)) return LBP_ERR_SHAPE;
+    rc = validate_buffers(x, gy, W, shape, gx, gW, x_projected ? (size_t)Mr : 0, extra, gy_projected ? (size_t)Mr : 0);
     if (rc) return rc;
 
     int dev;
@@ -458,7 +461,7 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     const int dt = shape->dtype;
     const long img_tokens = (long)H * Wd + extra;
     const float inv_pp = 1.0f / (float)(patch * patch);
-    void *gy_r = base + ws.gy_r;
+    const void *gy_r = gy_projected ? gy : base + ws.gy_r;
     const void *x_r = x_projected ? x : base + ws.x_r;
     float *gx_r = (float *)(base + ws.gx_r);
     float *part = (float *)(base + ws.splitk);
@@ -469,11 +472,13 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     // Tokens outside the grid join the projected tensors as they are (Eq. 2 stays exact for them);
     // their g_y rows carry patch^2, a power of two, which the 1/patch^2 of both products takes away.
     const float pp = (float)(patch * patch);
-    if (gW && !x_projected)
-        LBP_HIP(lbp::launch_project_pair(gy, gy_r, Cout, x, base + ws.x_r, Cin, N, H, Wd, dt, plan, path, s, extra, pp,
-                                         1.0f));
+    if (gy_projected)
+        ;   // both projections were done by the caller
+    else if (gW && !x_projected)
+        LBP_HIP(lbp::launch_project_pair(gy, base + ws.gy_r, Cout, x, base + ws.x_r, Cin, N, H, Wd, dt, plan, path, s,
+                                         extra, pp, 1.0f));
     else
-        LBP_HIP(lbp::launch_project(gy, gy_r, N, H, Wd, Cout, dt, plan, path, s, extra, pp));
+        LBP_HIP(lbp::launch_project(gy, base + ws.gy_r, N, H, Wd, Cout, dt, plan, path, s, extra, pp));
     if (ev) LBP_HIP(hipEventRecord(ev[1], s));
     // g~w = g^w = g^y^T x^  (with the 1/p^2 of the normalisation)
     lbp::GemmArgs gw_args, g;
@@ -541,6 +546,12 @@ int lbp_wht_backward_preprojected(const void *x_r, const void *gy, const void *W
                                   void *gx, void *gW, void *stream)
 {
     return backward_impl(x_r, gy, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr, true);
+}
+
+int lbp_wht_products(const void *x_r, const void *gy_r, const void *W, const lbp_shape_t *shape, int patch,
+                     const int32_t *basis_idx, int r, void *gx, void *gW, void *stream)
+{
+    return backward_impl(x_r, gy_r, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr, true, 0, true);
 }
 
 int lbp_wht_backward_tokens(const void *x, const void *gy, const void *W, const lbp_shape_t *shape, int extra,

@@ -42,7 +42,7 @@ def main():
             line = f"{name:22s} {r:3d} {order:>5s} FAILED (exit {res.returncode})"
         else:
             j = json.loads(res.stdout.strip().splitlines()[-1])
-            ro = j["roofline"]
+            ro = j["roofline"] if j["roofline"]["bound"] == "hbm" else j["roofline_second"]      # the projection launch
             st = j["stages"] or {"projection_us": float("nan"), "gw_product_us": float("nan"),
                                  "gx_product_reverse_projection_us": float("nan")}      # none for token sequences
             lib = j["library_gemm_full_bp_ms"]

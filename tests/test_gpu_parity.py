@@ -337,6 +337,19 @@ def test_backward_with_x_projected_in_the_forward_pass(dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_products_from_projected_tensors_give_the_same_bits(dtype):
+    # lbp_wht_products is statements 3-6 of Algorithm 1 on tensors projected by lbp_wht_project_pair
+    wl = small("products", 3, 16, 24, 72, 136, 8, dtype, 275)
+    host, dev = device_inputs(wl)
+    for idx in (oracle.select_bases(8, 8, "l1"), oracle.select_bases(8, 21, "l1")):
+        x_r, gy_r = binding.wht_project_pair(dev["x"], dev["gy"], 8, idx)
+        a = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx)
+        b = binding.lbp_wht_products(x_r, gy_r, dev["w"], (wl.N, wl.H, wl.W), 8, idx)
+        bits = torch.int32 if dtype == "f32" else torch.int16
+        assert torch.equal(a[0].view(bits), b[0].view(bits)) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("patch", [4, 8, 16])
 def test_energy_spectrum_matches_oracle(dtype, patch):
     wl = small("energy", 3, 2 * patch, 3 * patch, 40, 72, patch, dtype, 500 + patch)

@@ -177,3 +177,15 @@ def test_token_sequence_entry_points_check_their_arguments(lib):
     # workspace: extra tokens add rows to the projected tensors
     assert binding.workspace_bytes(sh, 8, 4, extra=1) > binding.workspace_bytes(sh, 8, 4)
     assert binding.workspace_bytes(sh, 8, 4, extra=-1) == 0
+
+
+def test_products_entry_point_checks_its_arguments(lib):
+    sh = binding.LbpShape(2, 16, 16, 64, 128, 1, 0)
+    idx = (ctypes.c_int32 * 4)(0, 1, 8, 9)
+    f = lib.lbp_wht_products
+    assert f(None, P(GY), P(W_), ctypes.byref(sh), 8, idx, 4, P(GX), P(GW), None) == -1
+    assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 8, idx, 65, P(GX), P(GW), None) == -4
+    assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 5, idx, 4, P(GX), P(GW), None) == -3
+    # gy_r is only P*r = 32 rows of 128 bf16: an output right behind it does not overlap it
+    assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 8, idx, 4, P(GY + 32 * 128 * 2), P(GW), None) in (0, -11)
+    assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 8, idx, 4, P(GY + 32 * 128 * 2 - 16), P(GW), None) == -7
