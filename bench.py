@@ -15,7 +15,8 @@ reverse projection, per patch, summed over the batch) per second.  The line also
   library_gemm_full_bp_ms           the two products through torch.matmul (the vendor GEMM library)
                                     as a second opinion on the comparison point,
   preprojected_x_ms_per_step        lbp_wht_backward_preprojected: x^ kept from the forward pass,
-  stages                            HIP-event time of each stage inside the call,
+  stages                            each part of a call timed by itself, back to back (projection; the two
+                                    products as the call launches them; each product launched alone),
   roofline                          the kernel that takes the larger share of a step: the grouped launch
                                     of the two products (bf16 MFMA: algorithmic FLOPs / its average
                                     duration) or the projection of gy and x (HBM: algorithmic bytes /
@@ -193,17 +194,20 @@ def main():
     if not args.no_library_gemm:
         ms_lib, _ = timed(lib_step, max(10, args.steps // 4), max(3, args.warmup // 4))
 
-    # per-stage times inside the call: HIP events recorded by the library on the launch stream, with
-    # the two products launched one after the other (the timed steps above launch them as one grid
-    # where the planner groups them).  An untimed step is queued first so that the GPU is still busy
-    # while the host enqueues the profiled call: the events then bracket kernels, not launch latency.
-    n_prof = 0 if seq else max(10, min(100, args.steps))      # the profiling entry point takes grids only
-    stage = np.zeros(3)
-    for i in range(n_prof):
-        s = sets[i % n_sets]
-        lbp_step(i + 1)
-        stage += np.array(binding.lbp_wht_backward_profile(s["x"], s["gy"], s["w"], wl.patch, idx, s["gx"], s["gW"]))
-    stage /= max(n_prof, 1)
+    # where the time of a call goes: each part timed by itself, back to back on the launch stream
+    # (the projection loop and the products loop above; here the two products launched alone)
+    ms_gw = ms_gx = None
+    if not seq:
+        def gw_step(i):
+            s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
+            binding.lbp_wht_products(xr, gyr, s["w"], (wl.N, wl.H, wl.W), wl.patch, idx, gW=s["gW"], want_gx=False)
+
+        def gx_step(i):
+            s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
+            binding.lbp_wht_products(xr, gyr, s["w"], (wl.N, wl.H, wl.W), wl.patch, idx, gx=s["gx"], want_gw=False)
+
+        ms_gw, _ = timed(gw_step, max(20, args.steps // 2), max(5, args.warmup // 2))
+        ms_gx, _ = timed(gx_step, max(20, args.steps // 2), max(5, args.warmup // 2))
 
     if args.calibration_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -242,13 +246,12 @@ def main():
     else:
         roofline, roofline_second = roof_proj, roof_prod
     stages = None if seq else {
-        "projection_us": round(stage[0] * 1e3, 2),
-        "gw_product_us": round(stage[1] * 1e3, 2),
-        "gx_product_reverse_projection_us": round(stage[2] * 1e3, 2),
-        "gw_product_tflops": round(gemm_flops / (stage[1] * 1e-3) / 1e12, 1),
-        "gx_product_tflops": round(gemm_flops / (stage[2] * 1e-3) / 1e12, 1),
-        "gw_product_frac_of_mfma_peak": round(gemm_flops / (stage[1] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-        "gx_product_frac_of_mfma_peak": round(gemm_flops / (stage[2] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "projection_us": round(ms_proj * 1e3, 2),
+        "products_us": round(ms_prod * 1e3, 2),
+        "gw_product_alone_us": round(ms_gw * 1e3, 2),
+        "gx_product_reverse_projection_alone_us": round(ms_gx * 1e3, 2),
+        "gw_product_alone_frac_of_mfma_peak": round(gemm_flops / (ms_gw * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "gx_product_alone_frac_of_mfma_peak": round(gemm_flops / (ms_gx * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
     }
 
     cpu = None

@@ -31,7 +31,7 @@ def main():
     ap.add_argument("--out", default=None)
     args = ap.parse_args()
     head = (f"{'workload':22s} {'r':>3s} {'order':>5s} {'lbp_us':>8s} {'full_us':>8s} {'lib_us':>8s} {'speedup':>7s} "
-            f"{'vs_lib':>6s} {'pre_us':>7s} {'proj':>6s} {'gW':>6s} {'gx':>6s} {'proj GB/s':>9s} {'frac':>5s}")
+            f"{'vs_lib':>6s} {'pre_us':>7s} {'proj':>6s} {'prods':>6s} {'gW':>6s} {'gx':>6s} {'proj GB/s':>9s} {'frac':>5s}")
     lines = [head]
     print(head, flush=True)
     for name, r, order in cases():
@@ -43,13 +43,15 @@ def main():
         else:
             j = json.loads(res.stdout.strip().splitlines()[-1])
             ro = j["roofline"] if j["roofline"]["bound"] == "hbm" else j["roofline_second"]      # the projection launch
-            st = j["stages"] or {"projection_us": float("nan"), "gw_product_us": float("nan"),
-                                 "gx_product_reverse_projection_us": float("nan")}      # none for token sequences
+            nan = float("nan")
+            st = j["stages"] or {"projection_us": nan, "products_us": nan, "gw_product_alone_us": nan,
+                                 "gx_product_reverse_projection_alone_us": nan}      # none for token sequences
             lib = j["library_gemm_full_bp_ms"]
             line = (f"{name:22s} {r:3d} {order:>5s} {j['ms_per_step'] * 1e3:8.1f} {j['full_bp_ms'] * 1e3:8.1f} "
                     f"{lib * 1e3:8.1f} {j['speedup_vs_full_bp']:7.2f} {j['speedup_vs_library_gemm_full_bp']:6.2f} "
-                    f"{j['preprojected_x_ms_per_step'] * 1e3:7.1f} {st['projection_us']:6.1f} {st['gw_product_us']:6.1f} "
-                    f"{st['gx_product_reverse_projection_us']:6.1f} {ro['achieved']:9.0f} {ro['frac']:5.2f}")
+                    f"{j['preprojected_x_ms_per_step'] * 1e3:7.1f} {st['projection_us']:6.1f} {st['products_us']:6.1f} "
+                    f"{st['gw_product_alone_us']:6.1f} {st['gx_product_reverse_projection_alone_us']:6.1f} "
+                    f"{ro['achieved']:9.0f} {ro['frac']:5.2f}")
         lines.append(line)
         print(line, flush=True)
     if args.out:
