@@ -336,6 +336,21 @@ def test_backward_with_x_projected_in_the_forward_pass(dtype):
     assert torch.equal(gW2, gW)
 
 
+def test_stage_timing_entry_point_runs_the_same_backward():
+    # lbp_wht_backward_profile: the call bracketed by events, products launched one after the other
+    wl = small("profile", 4, 16, 16, 136, 264, 8, "bf16", 279)
+    host, dev = device_inputs(wl)
+    idx = oracle.select_bases(8, 8, "l1")
+    os.environ["LBP_GEMM_GROUP"] = "0"
+    gx0, gW0 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx)
+    os.environ.pop("LBP_GEMM_GROUP")
+    gx = torch.empty_like(gx0)
+    gW = torch.empty_like(gW0)
+    ms = binding.lbp_wht_backward_profile(dev["x"], dev["gy"], dev["w"], 8, idx, gx, gW)
+    assert len(ms) == 3 and all(0.0 < t < 100.0 for t in ms)
+    assert torch.equal(gx.view(torch.int16), gx0.view(torch.int16)) and torch.equal(gW.view(torch.int32), gW0.view(torch.int32))
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_products_from_projected_tensors_give_the_same_bits(dtype):
     # lbp_wht_products is statements 3-6 of Algorithm 1 on tensors projected by lbp_wht_project_pair
