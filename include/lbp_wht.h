@@ -167,7 +167,11 @@ int lbp_wht_project_tokens(const void *in, int N, int H, int W, int extra, int C
 int lbp_wht_backward_tokens_preprojected(const void *x_r, const void *gy, const void *W, const lbp_shape_t *shape,
                                          int extra, int patch, const int32_t *basis_idx, int r, void *gx, void *gW,
                                          void *stream);
-/* Workspace of the three calls above (lbp_wht_workspace_bytes with `extra` tokens per image). */
+/* lbp_wht_energy on such sequences: the spectrum of the grid tokens; the extra tokens have no
+ * coefficients and are skipped.  Same workspace as lbp_wht_energy. */
+int lbp_wht_energy_tokens(const void *in, int N, int H, int W, int extra, int C, int dtype, int patch,
+                          double *energy, void *stream);
+/* Workspace of the backward calls above (lbp_wht_workspace_bytes with `extra` tokens per image). */
 size_t lbp_wht_workspace_bytes_tokens(const lbp_shape_t *shape, int extra, int patch, int r);
 
 /*

@@ -21,7 +21,7 @@ EXPORTS = ("lbp_wht_select_bases", "lbp_wht_select_lhe", "lbp_wht_energy", "lbp_
            "lbp_wht_project_pair", "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
            "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version",
            "lbp_wht_backward_tokens", "lbp_wht_project_tokens", "lbp_wht_backward_tokens_preprojected",
-           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products")
+           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products", "lbp_wht_energy_tokens")
 
 
 class LbpShape(ctypes.Structure):
@@ -55,6 +55,7 @@ def load():
     lib.lbp_wht_backward.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
     lib.lbp_wht_select_lhe.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int, ctypes.c_int, i32p]
     lib.lbp_wht_energy.argtypes = [vp] + [ctypes.c_int] * 6 + [vp, vp]
+    lib.lbp_wht_energy_tokens.argtypes = [vp] + [ctypes.c_int] * 7 + [vp, vp]
     lib.lbp_wht_energy_workspace_bytes.argtypes = [ctypes.c_int] * 6
     lib.lbp_wht_energy_workspace_bytes.restype = ctypes.c_size_t
     lib.lbp_wht_backward_preprojected.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
@@ -128,15 +129,24 @@ def select_lhe(energy, patch, r):
     return list(out[:r])
 
 
-def wht_energy(t, patch, energy=None, stream=None):
+def wht_energy(t, patch, energy=None, stream=None, grid=None):
     """Adds the WHT energy spectrum of t [N,H,W,C] to `energy` (float64 device tensor of patch^2
-    entries, made and zeroed when not passed).  Returns it."""
-    N, H, W, C = t.shape
+    entries, made and zeroed when not passed).  Returns it.  With grid=(H, W), t is a token sequence
+    [N,T,C] whose last H*W tokens are the grid; the others are skipped."""
+    if grid is None:
+        N, H, W, C = t.shape
+        extra = 0
+    else:
+        N, T, C = t.shape
+        H, W = grid
+        extra = T - H * W
+        if extra < 0:
+            raise ValueError("fewer tokens than the grid holds")
     if energy is None:
         energy = torch.zeros(patch * patch, dtype=torch.float64, device=t.device)
     with torch.cuda.device(t.device):
-        _check(load().lbp_wht_energy(_dev_tensor(t, "t"), N, H, W, C, _DTYPES[t.dtype], int(patch),
-                                     _dev_tensor(energy, "energy", torch.float64), _stream_ptr(stream)))
+        _check(load().lbp_wht_energy_tokens(_dev_tensor(t, "t"), N, H, W, extra, C, _DTYPES[t.dtype], int(patch),
+                                            _dev_tensor(energy, "energy", torch.float64), _stream_ptr(stream)))
     return energy
 
 

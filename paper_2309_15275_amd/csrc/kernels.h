@@ -16,7 +16,8 @@ enum class GemmPath { kAuto = 0, kSimple = 1 };
 // them, see launch_gather_extra / launch_scatter_extra).
 //
 // p(.) of Eq. 6 per patch: in [N][H][W][C] -> out [P*r][C], both of `dtype`.  With extra > 0
-// the N*extra tokens outside the grid follow as rows P*r ..., multiplied by extra_scale.
+// the N*extra tokens outside the grid follow as rows P*r ..., multiplied by extra_scale (0: they are
+// skipped and nothing is appended).
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
                           const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra = 0,
                           float extra_scale = 1.0f);

@@ -358,10 +358,17 @@ size_t lbp_wht_energy_workspace_bytes(int N, int H, int W, int C, int dtype, int
 int lbp_wht_energy(const void *in, int N, int H, int W, int C, int dtype, int patch, double *energy,
                    void *stream)
 {
+    return lbp_wht_energy_tokens(in, N, H, W, 0, C, dtype, patch, energy, stream);
+}
+
+int lbp_wht_energy_tokens(const void *in, int N, int H, int W, int extra, int C, int dtype, int patch,
+                          double *energy, void *stream)
+{
     if (!in || !energy) return LBP_ERR_NULL;
     if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
     int rc = lbp::validate_grid(N, H, W, C, dtype, patch);
     if (rc) return rc;
+    if (extra < 0 || (long)N * ((long)H * W + extra) > 0x7fffffffL) return LBP_ERR_SHAPE;
     const void *ptrs[2] = {in, energy};
     rc = lbp::validate_alignment(ptrs, 2);
     if (rc) return rc;
@@ -382,7 +389,8 @@ int lbp_wht_energy(const void *in, int N, int H, int W, int C, int dtype, int pa
     const size_t coef_bytes = ((size_t)Q * pp * C * lbp::dtype_size(dtype) + 255) / 256 * 256;
     hipStream_t s = (hipStream_t)stream;
     // all p^2 coefficients of every patch (row q*p^2 + j = basis j in sequency order), then their squares
-    LBP_HIP(lbp::launch_project(in, base, N, H, W, C, dtype, plan, wht_path_from_env(), s));
+    // (tokens outside the grid have no coefficients: they are skipped)
+    LBP_HIP(lbp::launch_project(in, base, N, H, W, C, dtype, plan, wht_path_from_env(), s, extra, 0.0f));
     LBP_HIP(lbp::launch_energy(base, Q, pp, C, dtype, (double *)(base + coef_bytes), energy, s));
     return LBP_OK;
 }

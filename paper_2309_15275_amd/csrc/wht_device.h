@@ -108,7 +108,7 @@ inline void set_extra_rows(ExtraRows &x, int slot, const void *in, void *out_row
     const int Cv = dtype == LBP_BF16 ? C / 8 : C / 4;
     x.in[slot] = (const uint4 *)in;
     x.out[slot] = (uint4 *)out_rows;
-    x.items[slot] = in ? (long)N * extra * Cv : 0;
+    x.items[slot] = (in && scale != 0.0f) ? (long)N * extra * Cv : 0;      // scale 0: nothing is appended
     x.img_vecs[slot] = img_tokens * Cv;
     x.Cv[slot] = Cv > 0 ? Cv : 1;
     x.scale[slot] = scale;

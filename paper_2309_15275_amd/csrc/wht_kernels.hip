@@ -492,7 +492,7 @@ bool use_mfma_path(const BasisPlan &plan, WhtPath path, int dtype, int C)
 hipError_t gather_after_generic(const void *in, void *out, int N, int H, int W, int C, int dtype, const BasisPlan &plan,
                                 int extra, float scale, hipStream_t stream)
 {
-    if (extra <= 0) return hipSuccess;
+    if (extra <= 0 || scale == 0.0f) return hipSuccess;
     const size_t rows = (size_t)patch_count(N, H, W, plan.patch) * plan.r;
     return launch_gather_extra(in, (char *)out + rows * C * dtype_size(dtype), N, extra, (long)H * W + extra, C, dtype,
                                scale, stream);

@@ -114,3 +114,16 @@ def test_vitb_sequence_of_197_tokens_at_full_width():
     gx0, gW0 = oracle.lbp_wht_backward_tokens(host["x"], host["gy"], host["w"], (14, 14), 8, idx)
     assert rel_fro(to_host(gx), gx0) <= TOL["bf16"] and rel_fro(to_host(gW), gW0) <= TOL["bf16"]
     assert rel_fro(to_host(gx)[:, :1], gx0[:, :1]) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_energy_spectrum_of_a_token_sequence_skips_the_tokens_outside_the_grid(dtype):
+    wl, extra, host, dev, idx = run_case(1, dtype, 690)         # 1 + 14 x 14 tokens, patch 8
+    e = binding.wht_energy(dev["gy"], wl.patch, grid=(wl.H, wl.W))
+    gyg = np.ascontiguousarray(host["gy"][:, extra:]).reshape(wl.N, wl.H, wl.W, wl.Cout)
+    want = oracle.wht_energy_padded(gyg, wl.patch)
+    got = e.cpu().numpy()
+    assert np.max(np.abs(got - want)) <= (1e-5 if dtype == "f32" else 2e-2) * want.max()
+    # the same numbers as the grid handed over by itself
+    xg = dev["gy"][:, extra:].contiguous().view(wl.N, wl.H, wl.W, wl.Cout)
+    assert torch.equal(e, binding.wht_energy(xg, wl.patch))
