@@ -273,7 +273,8 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
     if (allow_group && s->dtype == LBP_BF16 && (patch == 8 || !(can_fuse && ws->gx_fused))) {
         const bool thin = s->Cin <= 64;                  // 64 x 64 tiles for both
         const int kTileW = thin ? 6 : 4, kTileX[2] = {thin ? 6 : 5, thin ? 6 : 4};       // indices into kGemmTiles
-        const bool fuse = can_fuse && patch == 8 && (ws->gx_fused || force_fuse || !fused_wide);
+        // (the matrix-core epilogue pays inside a grouped launch up to two 16-basis steps: measured)
+        const bool fuse = can_fuse && patch == 8 && (ws->gx_fused || force_fuse || !fused_wide || r <= 32);
         const GemmPlan w = plan_gemm(s->Cout, s->Cin, Mr, gw_bytes, true, 0, 0, num_cus, false, kTileW);
         const long n_w = gemm_workgroups(w, s->Cout, s->Cin, 0);
         GemmPlan x[2];
