@@ -527,18 +527,32 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
     gemm_body<BM, BN, WGM, WGN, PF, A_KFAST, EPI, LP>(p, blockIdx.x, blockIdx.y, smem);
 }
 
+// A kernel that uses more than 64 KB of dynamic LDS has to be allowed to, once per device (the
+// attribute belongs to the current device's copy of the kernel).  `configured` has one flag per
+// device; racing threads set the same value.
+constexpr int kMaxLaunchDevices = 64;
+inline hipError_t allow_dynamic_lds(const void *kern, int bytes, bool *configured)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxLaunchDevices) return hipErrorInvalidDevice;
+    if (!configured[dev]) {
+        e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e != hipSuccess) return e;
+        configured[dev] = true;
+    }
+    return hipSuccess;
+}
+
 template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
 hipError_t launch_one(const Params &p, int splits, hipStream_t stream)
 {
     constexpr int LDS = Smem<BM, BN, A_KFAST>::TOTAL;
     auto kern = gemm_kernel<BM, BN, WGM, WGN, PF, A_KFAST, EPI, LP>;
-    static bool configured = false;     // per instantiation; racing threads set the same value
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static bool configured[kMaxLaunchDevices] = {};     // per instantiation
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), LDS, configured);
+    if (e != hipSuccess) return e;
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)splits);
     hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), LDS, stream, p);
     return hipGetLastError();
@@ -581,13 +595,9 @@ hipError_t launch_pair(const Params &first, int splits_first, const Params &seco
     constexpr int L1 = Smem<BM1, BN1, KF1>::TOTAL, L2 = Smem<BM2, BN2, KF2>::TOTAL;
     constexpr int LDS = L1 > L2 ? L1 : L2;
     auto kern = gemm_pair_kernel<WGM, WGN, PF, BM1, BN1, KF1, EPI1, LP1, BM2, BN2, KF2, EPI2, LP2>;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static bool configured[kMaxLaunchDevices] = {};
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), LDS, configured);
+    if (e != hipSuccess) return e;
     PairParams pp;
     pp.first = first;
     pp.second = second;
