@@ -21,6 +21,7 @@ def _need_gpu():
         pytest.skip("no GPU")
     yield
     os.environ.pop("LBP_GEMM_GROUP", None)
+    os.environ.pop("LBP_WHT_PATH", None)
     torch.cuda.synchronize()
 
 
@@ -165,3 +166,38 @@ def test_grouped_and_separate_launches_of_the_products_agree(case):
         else:
             egx, egw = check_sampled(wl, host, gx, gW, idx, 77 + case)
         assert egx <= TOL["bf16"] and egw <= TOL["bf16"], (egx, egw)
+
+
+@pytest.mark.parametrize("path", ["auto", "mfma"])
+def test_tensors_beyond_two_to_the_31_elements(path):
+    # 2^19 tokens x 4352 channels = 2.28e9 bf16 elements (4.6 GB): element offsets no longer fit 31 bits.
+    # The tensor is made on the device (seeded); patches sampled from its whole extent, the last
+    # one included, are checked against the oracle's projection of the same values; then the
+    # reverse projection of those coefficients, again against the oracle on sampled patches.
+    os.environ["LBP_WHT_PATH"] = path
+    N, H, W, C, p = 512, 32, 32, 4352, 8
+    gen = torch.Generator(device="cuda").manual_seed(4242)
+    t = torch.randn((N, H, W, C), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    idx = oracle.select_bases(p, 4, "l1")
+    coef = binding.wht_project(t, p, idx)
+    Q, PW = N * (H // p) * (W // p), W // p
+    rng = np.random.default_rng(7)
+    qs = np.unique(np.concatenate([[0, Q - 1, Q // 2], rng.integers(0, Q, 24)]))
+    for q in qs:
+        n, rem = divmod(int(q), (H // p) * PW)
+        a, b = divmod(rem, PW)
+        patch = t[n, a * p:(a + 1) * p, b * p:(b + 1) * p, :].float().cpu().numpy()[None]       # [1, p, p, C]
+        want = oracle.project(patch, p, idx)                                                   # [4, C]
+        got = to_host(coef[q * 4:(q + 1) * 4])
+        assert rel_fro(got, want) <= 4e-3, (int(q), rel_fro(got, want))
+    del t
+    # reverse direction at the same size: fp32 coefficients -> bf16 tokens
+    back = binding.wht_unproject(coef.float(), (N, H, W, C), torch.bfloat16, p, idx)
+    for q in qs[-6:]:
+        n, rem = divmod(int(q), (H // p) * PW)
+        a, b = divmod(rem, PW)
+        c = to_host(coef[q * 4:(q + 1) * 4])
+        want = oracle.unproject(c, (1, p, p, C), p, idx)
+        got = to_host(back[n, a * p:(a + 1) * p, b * p:(b + 1) * p, :])[None]
+        assert rel_fro(got, want) <= 4e-3, int(q)
+    os.environ.pop("LBP_WHT_PATH", None)
