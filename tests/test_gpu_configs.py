@@ -201,3 +201,30 @@ def test_tensors_beyond_two_to_the_31_elements(path):
         got = to_host(back[n, a * p:(a + 1) * p, b * p:(b + 1) * p, :])[None]
         assert rel_fro(got, want) <= 4e-3, int(q)
     os.environ.pop("LBP_WHT_PATH", None)
+
+
+def test_backward_with_more_than_two_to_the_31_input_elements():
+    # x and gx have 2^19 tokens x 4352 channels (2.28e9 elements); gy is narrow.  Sampled rows of gx
+    # (the last token included) and sampled entries of gW against the oracle, which only needs the
+    # sampled channels of x for an entry of gW.
+    N, H, W, Cin, Cout, p, r = 512, 32, 32, 4352, 64, 8, 4
+    gen = torch.Generator(device="cuda").manual_seed(99)
+    x = torch.randn((N, H, W, Cin), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    gy = (0.01 * torch.randn((N, H, W, Cout), generator=gen, device="cuda")).to(torch.bfloat16)
+    w = (0.02 * torch.randn((Cout, Cin), generator=gen, device="cuda")).to(torch.bfloat16)
+    idx = oracle.select_bases(p, r, "l1")
+    gx, gW = binding.lbp_wht_backward(x, gy, w, p, idx)
+    M = N * H * W
+    rng = np.random.default_rng(5)
+    tokens = np.unique(np.concatenate([[0, M - 1, M // 2 + 17], rng.integers(0, M, 40)])).astype(np.int64)
+    gy_h, w_h = to_host(gy), to_host(w)
+    want_gx = oracle.lbp_gx_tokens(gy_h, w_h, p, idx, tokens)
+    got_gx = to_host(gx.reshape(M, Cin)[torch.from_numpy(tokens).cuda()])
+    assert rel_fro(got_gx, want_gx) <= TOL["bf16"]
+    cols = np.unique(np.concatenate([[0, Cin - 1], rng.integers(0, Cin, 6)])).astype(np.int64)
+    x_cols = to_host(x[..., torch.from_numpy(cols).cuda()].contiguous())          # [N,H,W,len(cols)]
+    co = np.repeat(np.arange(0, Cout, 9, dtype=np.int32), len(cols))
+    ci_local = np.tile(np.arange(len(cols), dtype=np.int32), len(co) // len(cols))
+    want_gw = oracle.lbp_gw_entries(x_cols, gy_h, p, idx, co, ci_local)
+    got_gw = to_host(gW[torch.from_numpy(co.astype(np.int64)).cuda(), torch.from_numpy(cols[ci_local]).cuda()])
+    assert rel_fro(got_gw, want_gw) <= TOL["bf16"]
