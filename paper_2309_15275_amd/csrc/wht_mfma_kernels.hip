@@ -88,7 +88,9 @@ __device__ __forceinline__ bf16x8_t read_b_frag(const unsigned char *tile, int k
 // forward: coefficients[k][c] = sum_t sign(nat_k, t) * tokens[t][c]
 // KSTEPS = padded tokens per patch / 16; MTILES = ceil(r / 32) upper bound for cached operands
 // ---------------------------------------------------------------------------------------------
-template <int KSTEPS, int MTILES, bool CACHE_A>
+// A_LDS: the cached sign operands live in LDS instead of registers (more than 32 bases: two
+// accumulator tiles per wavefront leave no room for them beside the prefetched item)
+template <int KSTEPS, int MTILES, bool CACHE_A, bool A_LDS = false>
 __global__ __launch_bounds__(256) void wht_project_mfma_kernel(MfmaTensor t0, MfmaTensor t1, GridGeom g,
                                                                NatTable nat, int r, int items_per_wg, ExtraRows xr)
 {
@@ -107,20 +109,31 @@ __global__ __launch_bounds__(256) void wht_project_mfma_kernel(MfmaTensor t0, Mf
     const MfmaTensor &t = second ? t1 : t0;
     const long wg = blockIdx.x - (second ? t0.blocks : 0u);
 
-    bf16x8_t afrag[CACHE_A ? MTILES : 1][CACHE_A ? KSTEPS : 1];
+    static_assert(!A_LDS || CACHE_A, "sign operands in LDS are cached operands");
+    bf16x8_t afrag[CACHE_A && !A_LDS ? MTILES : 1][CACHE_A && !A_LDS ? KSTEPS : 1];
+    // sign operands in LDS: behind the token / result rows, [m-tile][k-step][lane] 16 bytes each
+    unsigned char *const sgn = smem + (P2PAD > r ? P2PAD : r) * S_IN;
     if (CACHE_A) {
 #pragma unroll
         for (int mt = 0; mt < MTILES; ++mt) {
             int k = mt * 32 + li;
             unsigned nk = nat.v[k < r ? k : 0];
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) afrag[mt][ks] = signs_over_tokens(nk, ks * 16 + kg * 8, p2, k < r);
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                if (A_LDS) {
+                    if (((mt * KSTEPS + ks) & 3) == wave)      // the four wavefronts share the work; first barrier of the loop below
+                        *reinterpret_cast<bf16x8_t *>(sgn + ((mt * KSTEPS + ks) * 64 + lane) * 16) =
+                            signs_over_tokens(nk, ks * 16 + kg * 8, p2, k < r);
+                } else {
+                    afrag[mt][ks] = signs_over_tokens(nk, ks * 16 + kg * 8, p2, k < r);
+                }
+            }
         }
     }
 
     // The loads of the next item are issued before the current one is multiplied, so that a
     // workgroup always has one item (16 KB) on its way from HBM (not for patch 16: no registers left).
-    constexpr bool PREFETCH = KSTEPS <= 4 && MTILES == 1;
+    constexpr bool PREFETCH = KSTEPS <= 4 && (MTILES == 1 || A_LDS);
     constexpr int LOADS = P2PAD * (CB / 8) / 256 > 0 ? P2PAD * (CB / 8) / 256 : 1;      // 16-byte loads per lane per item
     static_assert(P2PAD * (CB / 8) % 256 == 0 || P2PAD * (CB / 8) < 256, "loads must divide over the lanes");
     const long item_end = min(t.items, (wg + 1) * (long)items_per_wg);
@@ -214,7 +227,9 @@ __global__ __launch_bounds__(256) void wht_project_mfma_kernel(MfmaTensor t0, Mf
             for (int mt = 0; mt < MTILES; ++mt) {
                 if (mt < mtiles) {
                     bf16x8_t a;
-                    if (CACHE_A) {
+                    if (A_LDS) {
+                        a = *reinterpret_cast<const bf16x8_t *>(sgn + ((mt * KSTEPS + ks) * 64 + lane) * 16);
+                    } else if (CACHE_A) {
                         a = afrag[mt][ks];
                     } else {
                         int k = mt * 32 + li;
@@ -484,17 +499,18 @@ hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *
     const int p2 = plan.patch * plan.patch;
     const int p2pad = p2 < 16 ? 16 : p2;
     const int lds = (p2pad > plan.r ? p2pad : plan.r) * S_IN;     // S_IN >= S_OUT: covers both uses
-#define LBP_LAUNCH(KS, MT, CACHE)                                                                   \
+#define LBP_LAUNCH(KS, MT, CACHE, ALDS)                                                             \
     do {                                                                                            \
-        auto kern = wht_project_mfma_kernel<KS, MT, CACHE>;                                         \
-        hipError_t e = set_lds(kern, lds);                                                          \
+        auto kern = wht_project_mfma_kernel<KS, MT, CACHE, ALDS>;                                   \
+        const int bytes = lds + (ALDS ? MT * KS * 64 * 16 : 0);                                     \
+        hipError_t e = set_lds(kern, bytes);                                                        \
         if (e != hipSuccess) return e;                                                              \
-        hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, stream, t[0], t[1], g, nat, plan.r, ipw, xr); \
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), bytes, stream, t[0], t[1], g, nat, plan.r, ipw, xr); \
     } while (0)
-    if (p2pad == 16) LBP_LAUNCH(1, 1, true);
-    else if (p2pad == 64 && plan.r <= 32) LBP_LAUNCH(4, 1, true);
-    else if (p2pad == 64) LBP_LAUNCH(4, 2, true);
-    else LBP_LAUNCH(16, 8, false);
+    if (p2pad == 16) LBP_LAUNCH(1, 1, true, false);
+    else if (p2pad == 64 && plan.r <= 32) LBP_LAUNCH(4, 1, true, false);
+    else if (p2pad == 64) LBP_LAUNCH(4, 2, true, true);
+    else LBP_LAUNCH(16, 8, false, false);
 #undef LBP_LAUNCH
     return hipGetLastError();
 }
