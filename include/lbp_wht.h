@@ -175,6 +175,17 @@ int lbp_wht_energy_tokens(const void *in, int N, int H, int W, int extra, int C,
 size_t lbp_wht_workspace_bytes_tokens(const lbp_shape_t *shape, int extra, int patch, int r);
 
 /*
+ * What a backward call with these arguments would launch, as one line of text (host logic only, no
+ * device work, usable without a GPU): the projection kernel, whether the two products share a
+ * launch, tile shape and split-K factor of each product, fused or separate reverse projection, and
+ * the workspace size.  num_cus <= 0 takes the current device's compute-unit count (256 if there
+ * is no device).  Writes at most len - 1 characters and a NUL to buf.  For logs and tests; the
+ * wording is not a stable interface.
+ */
+int lbp_wht_describe_plan(const lbp_shape_t *shape, int extra, int patch, const int32_t *basis_idx, int r,
+                          int want_gx, int want_gw, int num_cus, char *buf, size_t len);
+
+/*
  * For measurement, not part of the method: the same call as lbp_wht_backward, bracketed by HIP
  * events on `stream`.  It WAITS for the work to finish and returns the elapsed milliseconds of the
  * three stages in stage_ms (host, 3 floats): [0] projection of gy and x, [1] weight-gradient

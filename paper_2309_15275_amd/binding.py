@@ -21,7 +21,7 @@ EXPORTS = ("lbp_wht_select_bases", "lbp_wht_select_lhe", "lbp_wht_energy", "lbp_
            "lbp_wht_project_pair", "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
            "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version",
            "lbp_wht_backward_tokens", "lbp_wht_project_tokens", "lbp_wht_backward_tokens_preprojected",
-           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products", "lbp_wht_energy_tokens")
+           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products", "lbp_wht_energy_tokens", "lbp_wht_describe_plan")
 
 
 class LbpShape(ctypes.Structure):
@@ -59,6 +59,8 @@ def load():
     lib.lbp_wht_energy_workspace_bytes.argtypes = [ctypes.c_int] * 6
     lib.lbp_wht_energy_workspace_bytes.restype = ctypes.c_size_t
     lib.lbp_wht_backward_preprojected.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.lbp_wht_describe_plan.argtypes = [shp, ctypes.c_int, ctypes.c_int, i32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                          ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
     lib.lbp_wht_products.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
     lib.lbp_wht_backward_profile.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp,
                                              ctypes.POINTER(ctypes.c_float)]
@@ -383,6 +385,15 @@ def wht_unproject(coef, shape, dtype, patch, basis_idx, out=None, stream=None):
                                         _DTYPES[dtype], int(patch), idx, r,
                                         _dev_tensor(out, "out", dtype), _stream_ptr(stream)))
     return out
+
+
+def describe_plan(shape, patch, basis_idx, extra=0, want_gx=True, want_gw=True, num_cus=0):
+    """One line of text: what a backward call with these arguments would launch (no device work)."""
+    idx, r = _idx_array(basis_idx)
+    buf = ctypes.create_string_buffer(1024)
+    _check(load().lbp_wht_describe_plan(ctypes.byref(shape), int(extra), int(patch), idx, r, int(want_gx),
+                                        int(want_gw), int(num_cus), buf, len(buf)))
+    return buf.value.decode()
 
 
 def workspace_bytes(shape, patch, r, extra=0):

@@ -44,6 +44,10 @@ hipError_t launch_gather_extra(const void *in, void *out, int N, int extra, long
 hipError_t launch_scatter_extra(const float *in, int slices, size_t slice_stride, void *out, int N, int extra,
                                 long img_tokens, int C, int dtype, float scale, hipStream_t stream);
 
+// Which projection kernel launch_project / launch_unproject take for this selection: "register",
+// "matrix-core" or "generic" (host logic only).
+const char *projection_kernel_name(const BasisPlan &plan, WhtPath path, int dtype, int C);
+
 // Matrix-core form of the two projections (bf16 tensors, any selection, any patch up to 16).
 bool wht_mfma_supported(const BasisPlan &plan, int dtype, int C);
 hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *in1, void *out1, int C1,

@@ -3,6 +3,7 @@
 // entry point returns LBP_ERR_HIP.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -155,6 +156,19 @@ int validate_buffers(const void *x, const void *gy, const void *W, const lbp_sha
 bool tokens_ok(const lbp_shape_t *s, int extra)
 {
     return extra >= 0 && (long)s->N * ((long)s->H * s->W + extra) <= 0x7fffffffL;
+}
+
+// The launch plan of one low-rank backward call: tiles, split-K factors, fused or separate
+// reverse projection, grouped or separate products, workspace layout (host logic only).
+int plan_call(const lbp_shape_t *shape, int extra, int patch, int r, const lbp::BasisPlan &plan, int num_cus,
+              bool both_outputs, lbp::WorkspacePlan *ws)
+{
+    const lbp::GemmPath gpath = gemm_path_from_env();
+    const int fuse_env = fuse_unproject_from_env();
+    const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
+    const bool allow_group = both_outputs && gpath != lbp::GemmPath::kSimple && group_from_env();
+    return lbp::plan_workspace(shape, patch, r, num_cus, can_fuse, fuse_env == 1, ws,
+                               !lbp::gemm_unproject_pooled(plan), allow_group, extra);
 }
 
 // Describes the weight-gradient product; returns true when it leaves fp32 partial sums in `part`
@@ -451,13 +465,9 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     rc = current_device(&dev, &st);
     if (rc) return rc;
     const lbp::GemmPath gpath = gemm_path_from_env();
-    const int fuse_env = fuse_unproject_from_env();
-    const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
     lbp::WorkspacePlan ws;
     // both gradients wanted: the two products may share one launch (not when timed stage by stage)
-    const bool allow_group = gx && gW && !ev && gpath != lbp::GemmPath::kSimple && group_from_env();
-    rc = lbp::plan_workspace(shape, patch, r, st->num_cus, can_fuse, fuse_env == 1, &ws,
-                             !lbp::gemm_unproject_pooled(plan), allow_group, extra);
+    rc = plan_call(shape, extra, patch, r, plan, st->num_cus, gx && gW && !ev, &ws);
     if (rc) return rc;
     char *base = nullptr;
     rc = get_workspace(st, ws.total, &base);
@@ -554,6 +564,53 @@ int lbp_wht_backward_preprojected(const void *x_r, const void *gy, const void *W
                                   void *gx, void *gW, void *stream)
 {
     return backward_impl(x_r, gy, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr, true);
+}
+
+int lbp_wht_describe_plan(const lbp_shape_t *shape, int extra, int patch, const int32_t *basis_idx, int r,
+                          int want_gx, int want_gw, int num_cus, char *buf, size_t len)
+{
+    if (!shape || !basis_idx || !buf || len == 0) return LBP_ERR_NULL;
+    buf[0] = 0;
+    if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
+    int rc = lbp::validate_shape(shape, patch);
+    if (rc) return rc;
+    if (!tokens_ok(shape, extra)) return LBP_ERR_SHAPE;
+    if (!want_gx && !want_gw) return LBP_ERR_NULL;
+    lbp::BasisPlan plan;
+    rc = lbp::make_basis_plan(patch, basis_idx, r, &plan);
+    if (rc) return rc;
+    if (num_cus <= 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            num_cus = v;
+        else
+            (void)hipGetLastError();
+        if (num_cus <= 0) num_cus = 256;
+    }
+    lbp::WorkspacePlan ws;
+    rc = plan_call(shape, extra, patch, r, plan, num_cus, want_gx && want_gw, &ws);
+    if (rc) return rc;
+    const bool mfma = shape->dtype == LBP_BF16 && gemm_path_from_env() != lbp::GemmPath::kSimple;
+    const lbp::WhtPath path = wht_path_from_env();
+    const int pooled = (patch >> plan.mh) * (patch >> plan.mw);
+    char gw[160] = "", gxs[200] = "";
+    if (want_gw)
+        std::snprintf(gw, sizeof gw, "gW: tile %s, split-K %d%s; ", mfma ? lbp::kGemmTiles[ws.gw.tile].name : "fp32 64x64",
+                      ws.gw.splits, ws.gw.splits > 1 ? " + reduction kernel" : "");
+    if (want_gx) {
+        if (ws.gx_fused)
+            std::snprintf(gxs, sizeof gxs, "gx: tile %s, reverse projection fused (%s epilogue); ",
+                          lbp::kGemmTiles[ws.gx.tile].name, lbp::gemm_unproject_pooled(plan) ? "pooled" : "matrix-core");
+        else
+            std::snprintf(gxs, sizeof gxs, "gx: tile %s, split-K %d + %s reverse-projection kernel; ",
+                          mfma ? lbp::kGemmTiles[ws.gx.tile].name : "fp32 64x64", ws.gx.splits,
+                          lbp::projection_kernel_name(plan, path, shape->dtype, shape->Cin));
+    }
+    std::snprintf(buf, len, "projection: %s kernel (%d of %d coefficients per patch after pooling); products: %s; %s%sworkspace %zu bytes",
+                  lbp::projection_kernel_name(plan, path, shape->dtype, shape->Cout), pooled, patch * patch,
+                  ws.grouped ? "one grouped launch" : "separate launches", gw, gxs, ws.total);
+    return LBP_OK;
 }
 
 int lbp_wht_products(const void *x_r, const void *gy_r, const void *W, const lbp_shape_t *shape, int patch,

@@ -156,13 +156,13 @@ bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb)
 }
 
 const GemmTileInfo kGemmTiles[kNumGemmTiles] = {
-    {128, 128, true, 1.0, 0},
-    {64, 128, true, 1.0, 0},
-    {256, 128, false, 1.15, 0},
-    {256, 256, false, 1.4, 0},
-    {128, 128, true, 0.92, 0},    // 8 wavefronts: hides more of the LDS -> matrix-core latency
-    {64, 128, true, 0.88, 0},     // 8 wavefronts
-    {64, 64, true, 1.0, 64},      // thin layers only: on wide ones it measured 10-15 % behind 64 x 128
+    {128, 128, true, 1.0, 0, "128x128 (4 wavefronts)"},
+    {64, 128, true, 1.0, 0, "64x128 (4 wavefronts)"},
+    {256, 128, false, 1.15, 0, "256x128 (8 wavefronts)"},
+    {256, 256, false, 1.4, 0, "256x256 (8 wavefronts)"},
+    {128, 128, true, 0.92, 0, "128x128 (8 wavefronts)"},    // 8 wavefronts: hides more of the LDS -> matrix-core latency
+    {64, 128, true, 0.88, 0, "64x128 (8 wavefronts)"},      // 8 wavefronts
+    {64, 64, true, 1.0, 64, "64x64 (4 wavefronts)"},        // thin layers only: on wide ones it measured 10-15 % behind 64 x 128
 };
 
 GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split, int fused_r,

@@ -78,6 +78,7 @@ struct GemmTileInfo {
     bool fused;        // has the fused reverse-projection epilogue
     double slowdown;   // measured factor over the simple cost model below
     int max_n;         // only offered to products with at most this many columns (0: any)
+    const char *name;  // for diagnostics
 };
 constexpr int kNumGemmTiles = 7;
 extern const GemmTileInfo kGemmTiles[kNumGemmTiles];

@@ -500,6 +500,13 @@ hipError_t gather_after_generic(const void *in, void *out, int N, int H, int W, 
 
 }  // namespace
 
+const char *projection_kernel_name(const BasisPlan &plan, WhtPath path, int dtype, int C)
+{
+    if (use_mfma_path(plan, path, dtype, C)) return "matrix-core";
+    if (use_register_path(plan, path)) return "register";
+    return "generic";
+}
+
 hipError_t launch_project(const void *in, void *out, int N, int H, int W, int C, int dtype,
                           const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra, float extra_scale)
 {

@@ -189,3 +189,50 @@ def test_products_entry_point_checks_its_arguments(lib):
     # gy_r is only P*r = 32 rows of 128 bf16: an output right behind it does not overlap it
     assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 8, idx, 4, P(GY + 32 * 128 * 2), P(GW), None) in (0, -11)
     assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 8, idx, 4, P(GY + 32 * 128 * 2 - 16), P(GW), None) == -7
+
+
+def test_launch_plans_of_the_benchmark_configurations(lib, monkeypatch):
+    # host logic only: what a call would launch on a 256-unit device
+    for var in ("LBP_GEMM_GROUP", "LBP_FUSE_UNPROJECT", "LBP_GEMM_PATH", "LBP_WHT_PATH", "LBP_GEMM_TILE"):
+        monkeypatch.delenv(var, raising=False)
+    S = binding.LbpShape
+    plan = lambda sh, p, r, order="l1", **kw: binding.describe_plan(sh, p, binding.select_bases(p, r, order), num_cus=256, **kw)
+    vitb = S(64, 16, 16, 768, 3072, 1, 0)
+    t = plan(vitb, 8, 8)
+    assert "register kernel (16 of 64" in t and "one grouped launch" in t and "fused (pooled epilogue)" in t
+    assert "gW: tile 128x128 (8 wavefronts), split-K 1;" in t
+    assert int(t.rsplit("workspace ", 1)[1].split()[0]) <= binding.workspace_bytes(vitb, 8, 8)
+    t = plan(vitb, 8, 15)                               # LP_L1 r=15 cannot be pooled
+    assert "matrix-core kernel" in t and "fused (matrix-core epilogue)" in t and "one grouped launch" in t
+    t = plan(vitb, 8, 36)                               # large rank: big tiles, split-K, separate kernels
+    assert "separate launches" in t and "reverse-projection kernel" in t and "reduction kernel" in t
+    t = plan(vitb, 8, 16, "linf")                       # the 4 x 4 square of LP_Linf pools like r=8
+    assert "register kernel (16 of 64" in t and "fused (pooled epilogue)" in t
+    t = plan(vitb, 8, 4)
+    assert "register kernel (4 of 64" in t
+    t = plan(S(64, 56, 56, 48, 192, 1, 0), 8, 8)        # thin layer: 64 x 64 tiles for both products
+    assert t.count("64x64 (4 wavefronts)") == 2 and "one grouped launch" in t
+    t = plan(S(2, 8, 8, 64, 64, 0, 0), 4, 4)            # fp32: plain kernels, nothing fused or grouped
+    assert "separate launches" in t and "fp32 64x64" in t and "fused" not in t
+    t = plan(vitb, 8, 8, want_gx=False)
+    assert "separate launches" in t and "gx:" not in t and "gW:" in t
+    monkeypatch.setenv("LBP_GEMM_GROUP", "0")
+    assert "separate launches" in plan(vitb, 8, 8)
+    monkeypatch.delenv("LBP_GEMM_GROUP")
+    monkeypatch.setenv("LBP_FUSE_UNPROJECT", "0")
+    assert "fused" not in plan(vitb, 8, 8)
+
+
+def test_plan_description_checks_its_arguments(lib):
+    sh = binding.LbpShape(2, 16, 16, 64, 128, 1, 0)
+    idx = (ctypes.c_int32 * 4)(0, 1, 8, 9)
+    buf = ctypes.create_string_buffer(64)
+    f = lib.lbp_wht_describe_plan
+    assert f(None, 0, 8, idx, 4, 1, 1, 256, buf, 64) == -1
+    assert f(ctypes.byref(sh), 0, 8, idx, 4, 1, 1, 256, None, 64) == -1
+    assert f(ctypes.byref(sh), 0, 8, idx, 4, 0, 0, 256, buf, 64) == -1
+    assert f(ctypes.byref(sh), 0, 7, idx, 4, 1, 1, 256, buf, 64) == -3
+    assert f(ctypes.byref(sh), 0, 8, idx, 0, 1, 1, 256, buf, 64) == -4
+    assert f(ctypes.byref(sh), -2, 8, idx, 4, 1, 1, 256, buf, 64) == -2
+    assert f(ctypes.byref(sh), 0, 8, idx, 4, 1, 1, 256, buf, 64) == 0
+    assert len(buf.value) == 63                          # cut to the buffer, NUL-terminated
