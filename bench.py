@@ -21,7 +21,9 @@ reverse projection, per patch, summed over the batch) per second.  The line also
                                     of the two products (bf16 MFMA: algorithmic FLOPs / its average
                                     duration) or the projection of gy and x (HBM: algorithmic bytes /
                                     its average duration); roofline_second is the other one,
-  cpu_baseline                      the CPU oracle timed on this machine's host cores.
+  warm_cache_ms_per_step            the same step on one buffer set over and over (cache-warm), labelled,
+  cpu_baseline                      the CPU oracle timed on this machine's host cores (all threads; beside it one
+                                    thread, and the oracle's exact backward).
 """
 import argparse
 import json
@@ -173,6 +175,8 @@ def main():
         binding.lbp_wht_products(xr, gyr, s["w"], (wl.N, wl.H, wl.W), wl.patch, idx, gx=s["gx"], gW=s["gW"])
 
     ms_lbp, wall_lbp = timed(lbp_step, args.steps, args.warmup)
+    # the cache-warm number beside it, labelled: one buffer set over and over
+    ms_warm = None if args.warm_cache else timed(lambda i: lbp_step(0), max(20, args.steps // 2), max(5, args.warmup // 2))[0]
     # the same steps recorded once into a HIP graph (one step per buffer set) and replayed: what a
     # training loop that captures its backward pass sees; launch gaps between the kernels shrink
     ms_graph = None
@@ -240,6 +244,10 @@ def main():
                      "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
                      "traffic": read_traffic(f"gemm_products_{wl.name}_hbm_traffic.txt"),
                      "algorithmic_flops": 2.0 * gemm_flops, "avg_launch_us": round(ms_prod * 1e3, 2)}
+        # the other candidate bound: operands read once, outputs written once
+        prod_bytes = esz * (Mr * (wl.Cin + wl.Cout) + wl.Cin * wl.Cout + wl.tokens * wl.Cin) + 4 * wl.Cin * wl.Cout
+        roof_prod["algorithmic_bytes"] = prod_bytes
+        roof_prod["frac_of_hbm_peak"] = round(prod_bytes / (ms_prod * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     # `roofline` is the kernel that takes the larger share of a step, `roofline_second` the other
     if roof_prod is not None and ms_prod > ms_proj:
         roofline, roofline_second = roof_prod, roof_proj
@@ -269,10 +277,31 @@ def main():
             else:
                 oracle.lbp_wht_backward_padded(sample["x"], sample["gy"], sample["w"], wl.patch, np.asarray(idx))
             best = min(best, time.perf_counter() - t0)
+        threads = oracle.max_threads()
         cpu = {"value": round(lbp_flops(wl_s, r) / best / 1e12, 6), "unit": "TFLOP/s",
-               "cores": oracle.max_threads(), "kind": "oracle",
+               "cores": threads, "kind": "oracle",
                "sample": f"first {n_s} of {wl.N} images of the same workload, best of 2 calls, {best:.2f} s each",
                "ms_per_step_scaled_to_full": round(best * 1e3 * wl.N / n_s, 1)}
+        # beside it: the same oracle call on one thread, and the oracle's exact backward (Eq. 2) on
+        # all threads, each on a sample bounded to a few seconds, scaled to the full batch
+        n_1 = max(1, n_s // 8)
+        one = {k: (v[:n_1] if k != "w" else v) for k, v in host.items()}
+        oracle.set_threads(1)
+        t0 = time.perf_counter()
+        if seq:
+            oracle.lbp_wht_backward_tokens(one["x"], one["gy"], one["w"], grid, wl.patch, np.asarray(idx))
+        else:
+            oracle.lbp_wht_backward_padded(one["x"], one["gy"], one["w"], wl.patch, np.asarray(idx))
+        t_one = time.perf_counter() - t0
+        oracle.set_threads(threads)
+        n_f = int(max(1, min(wl.N, round(wl.N * 10e9 / max(full_bp_flops(wl), 1.0)))))
+        fb = {k: (v[:n_f].reshape(n_f, 1, -1, v.shape[-1]) if k != "w" else v) for k, v in host.items()}
+        t0 = time.perf_counter()
+        oracle.full_bp_backward(fb["x"], fb["gy"], fb["w"])
+        t_full = time.perf_counter() - t0
+        cpu["single_thread_ms_per_step_scaled_to_full"] = round(t_one * 1e3 * wl.N / n_1, 1)
+        cpu["full_bp_oracle_ms_per_step_scaled_to_full"] = round(t_full * 1e3 * wl.N / n_f, 1)
+        cpu["side_samples"] = f"one thread: first {n_1} images, {t_one:.2f} s; exact backward on {threads} threads: first {n_f} images, {t_full:.2f} s"
 
     out = {
         "metric": "lbp_wht_linear_backward_tflops",
@@ -301,6 +330,7 @@ def main():
         "preprojected_x_ms_per_step": round(ms_pre, 5),
         "graph_replay_ms_per_step": None if ms_graph is None else round(ms_graph, 5),
         "host_wall_ms_per_step": round(wall_lbp, 5),
+        "warm_cache_ms_per_step": None if ms_warm is None else round(ms_warm, 5),
         "stages": stages,
         "roofline": roofline,
         "roofline_second": roofline_second,
