@@ -236,3 +236,29 @@ def test_plan_description_checks_its_arguments(lib):
     assert f(ctypes.byref(sh), -2, 8, idx, 4, 1, 1, 256, buf, 64) == -2
     assert f(ctypes.byref(sh), 0, 8, idx, 4, 1, 1, 256, buf, 64) == 0
     assert len(buf.value) == 63                          # cut to the buffer, NUL-terminated
+
+
+def test_reported_workspace_covers_every_plan_on_random_shapes(lib, monkeypatch):
+    # lbp_wht_workspace_bytes is what a caller who brings the workspace allocates: it must cover the
+    # plan of any call with that shape, rank and kind of selection, whichever outputs are asked for
+    for var in ("LBP_GEMM_GROUP", "LBP_FUSE_UNPROJECT", "LBP_GEMM_PATH", "LBP_WHT_PATH", "LBP_GEMM_TILE"):
+        monkeypatch.delenv(var, raising=False)
+    rng = np.random.default_rng(2024)
+    for _ in range(150):
+        patch = int(rng.choice([2, 4, 8, 8, 8, 16]))
+        bf16 = bool(rng.integers(0, 2))
+        mult = 8 if bf16 else 4
+        N, H, W = int(rng.integers(1, 40)), int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        Cin, Cout = mult * int(rng.integers(1, 300)), mult * int(rng.integers(1, 300))
+        extra = int(rng.choice([0, 0, 1, 2]))
+        r = int(rng.integers(1, patch * patch + 1))
+        idx = rng.permutation(patch * patch)[:r] if rng.integers(0, 2) else oracle.select_bases(patch, r, "l1")
+        sh = binding.LbpShape(N, H, W, Cin, Cout, 1 if bf16 else 0, 0)
+        need = binding.workspace_bytes(sh, patch, r, extra=extra)
+        assert need > 0
+        for want_gx, want_gw in ((True, True), (True, False), (False, True)):
+            for cus in (256, 304, 64):
+                t = binding.describe_plan(sh, patch, idx, extra=extra, want_gx=want_gx, want_gw=want_gw, num_cus=cus)
+                used = int(t.rsplit("workspace ", 1)[1].split()[0])
+                if cus == 256:      # workspace_bytes plans for the current device, else for 256 units
+                    assert used <= need, (N, H, W, Cin, Cout, patch, r, extra, t)
