@@ -328,6 +328,7 @@ def main():
         "library_gemm_full_bp_ms": None if ms_lib is None else round(ms_lib, 5),
         "speedup_vs_library_gemm_full_bp": None if ms_lib is None else round(ms_lib / ms_lbp, 3),
         "preprojected_x_ms_per_step": round(ms_pre, 5),
+        "preprojected_x_speedup_vs_full_bp": round(ms_full / ms_pre, 3),
         "graph_replay_ms_per_step": None if ms_graph is None else round(ms_graph, 5),
         "host_wall_ms_per_step": round(wall_lbp, 5),
         "warm_cache_ms_per_step": None if ms_warm is None else round(ms_warm, 5),
