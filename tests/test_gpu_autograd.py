@@ -127,3 +127,33 @@ def test_class_token_sequences_through_autograd():
     y.backward(g)
     gx0, gW0 = oracle.lbp_wht_backward_tokens(to_host(x), to_host(g), to_host(w), (14, 14), 8, fc.basis_idx)
     assert rel_fro(to_host(x2.grad), gx0) <= 1e-5 and rel_fro(to_host(fc.weight.grad), gW0) <= 1e-5
+
+
+def test_layer_switches_to_the_profiled_selection_after_the_profiling_steps():
+    # g_y built from two planted bases per patch plus small noise: after two profiled backward passes
+    # the layer's selection is the oracle's LHE selection on the accumulated spectrum, and those
+    # two bases lead it
+    rng = np.random.default_rng(31)
+    N, H, W, Cin, Cout, p, r = 2, 16, 16, 32, 48, 8, 4
+    wal = np.array([[1 if bin(oracle_nat & t).count("1") % 2 == 0 else -1 for t in range(p)]
+                    for oracle_nat in [int(format(s ^ (s >> 1), "03b")[::-1], 2) for s in range(p)]], dtype=np.float64)
+    planted = [(3, 5), (6, 1)]
+    steps = []
+    for _ in range(2):
+        coef = rng.standard_normal((N, H // p, W // p, len(planted), Cout))
+        g = np.zeros((N, H // p, p, W // p, p, Cout))
+        for k, (u, v) in enumerate(planted):
+            g += np.einsum("h,w,nabc->nahbwc", wal[u], wal[v], coef[:, :, :, k, :])
+        g = g.reshape(N, H, W, Cout) + 0.01 * rng.standard_normal((N, H, W, Cout))
+        steps.append(g.astype(np.float32))
+    fc = LBPWHTLinear(Cin, Cout, bias=False, patch=p, rank=r, device="cuda", lhe_profile_steps=2)
+    low_pass = fc.basis_idx
+    x = torch.randn(N, H, W, Cin, device="cuda", requires_grad=True)
+    for g in steps:
+        assert fc.basis_idx == low_pass                      # still profiling: the low-pass selection is in use
+        fc(x).backward(torch.from_numpy(g).cuda())
+    want = oracle.select_lhe(sum(oracle.wht_energy(g.astype(np.float64), p) for g in steps), p, r)
+    assert list(fc.basis_idx) == [int(v) for v in want]
+    assert set(fc.basis_idx[:2]) == {u * p + v for u, v in planted}
+    fc(x).backward(torch.from_numpy(steps[0]).cuda())        # later passes run with the new selection, no more profiling
+    assert fc.lhe_energy is not None and fc.lhe_steps_left == 0
