@@ -14,6 +14,8 @@ reverse projection, per patch, summed over the batch) per second.  The line also
   full_bp_ms / speedup_vs_full_bp   the same-style exact backward (Eq. 2) from this library,
   library_gemm_full_bp_ms           the two products through torch.matmul (the vendor GEMM library)
                                     as a second opinion on the comparison point,
+  library_gemm_lowrank_products_ms  the two low-rank products through torch.matmul, to set beside
+                                    stages.products_us,
   preprojected_x_ms_per_step        lbp_wht_backward_preprojected: x^ kept from the forward pass,
   stages                            each part of a call timed by itself, back to back (projection; the two
                                     products as the call launches them; each product launched alone),
@@ -194,9 +196,20 @@ def main():
     ms_proj, _ = timed(proj_step, args.steps, args.warmup)
     ms_prod = None if seq else timed(prod_step, args.steps, args.warmup)[0]
     ms_full, _ = timed(full_step, max(10, args.steps // 4), max(3, args.warmup // 4))
-    ms_lib = None
+    ms_lib = ms_lib_lowrank = None
     if not args.no_library_gemm:
         ms_lib, _ = timed(lib_step, max(10, args.steps // 4), max(3, args.warmup // 4))
+        if not seq:
+            # the two LOW-RANK products through the vendor GEMM library, from the projected tensors
+            # (no reverse projection, no 1/p^2): what a library call costs on shapes this small
+            lr_out = [torch.empty((xr.shape[0], wl.Cin), dtype=xr.dtype, device="cuda") for xr, _ in proj_bufs]
+
+            def lib_lowrank_step(i):
+                s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
+                torch.matmul(gyr, s["w"], out=lr_out[i % n_sets])
+                torch.matmul(gyr.t(), xr)
+
+            ms_lib_lowrank, _ = timed(lib_lowrank_step, max(20, args.steps // 2), max(5, args.warmup // 2))
 
     # where the time of a call goes: each part timed by itself, back to back on the launch stream
     # (the projection loop and the products loop above; here the two products launched alone)
@@ -327,6 +340,7 @@ def main():
         "speedup_vs_full_bp": round(ms_full / ms_lbp, 3),
         "library_gemm_full_bp_ms": None if ms_lib is None else round(ms_lib, 5),
         "speedup_vs_library_gemm_full_bp": None if ms_lib is None else round(ms_lib / ms_lbp, 3),
+        "library_gemm_lowrank_products_ms": None if ms_lib_lowrank is None else round(ms_lib_lowrank, 5),
         "preprojected_x_ms_per_step": round(ms_pre, 5),
         "preprojected_x_speedup_vs_full_bp": round(ms_full / ms_pre, 3),
         "graph_replay_ms_per_step": None if ms_graph is None else round(ms_graph, 5),
