@@ -89,9 +89,13 @@ __device__ __forceinline__ bf16x8_t read_b_frag(const unsigned char *tile, int k
 // KSTEPS = padded tokens per patch / 16; MTILES = ceil(r / 32) upper bound for cached operands
 // ---------------------------------------------------------------------------------------------
 // A_LDS: the cached sign operands live in LDS instead of registers (more than 32 bases: two
-// accumulator tiles per wavefront leave no room for them beside the prefetched item)
+// accumulator tiles per wavefront leave no room for them beside the prefetched item).
+// Occupancy is asked for explicitly: a workgroup has one 16 KB item in flight, so bandwidth follows
+// the number of resident workgroups.  Left alone the compiler takes 134 registers for the A_LDS
+// form (3 wavefronts per SIMD) and 98 for the patch-8 form with up to 32 bases (4); held to 4 and
+// 5 they fit in 100 and 84 without spilling: 3.9 -> 5.0 TB/s at 36 bases, +2-3 % at 15 and 21.
 template <int KSTEPS, int MTILES, bool CACHE_A, bool A_LDS = false>
-__global__ __launch_bounds__(256) void wht_project_mfma_kernel(MfmaTensor t0, MfmaTensor t1, GridGeom g,
+__global__ __launch_bounds__(256, (A_LDS ? 4 : (KSTEPS == 4 && MTILES == 1 ? 5 : 1))) void wht_project_mfma_kernel(MfmaTensor t0, MfmaTensor t1, GridGeom g,
                                                                NatTable nat, int r, int items_per_wg, ExtraRows xr)
 {
     constexpr int P2PAD = KSTEPS * 16;
