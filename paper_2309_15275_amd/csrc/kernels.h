@@ -35,6 +35,11 @@ hipError_t launch_project_pair(const void *in0, void *out0, int C0, const void *
 hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H, int W, int C,
                             int dtype, const BasisPlan &plan, WhtPath path, hipStream_t stream, int extra = 0,
                             long slice_rows = 0);
+// The same from bf16 coefficients [P*r][C] in one piece (a product stored them, rounded once), for
+// bf16 tensors and the selections the matrix-core form takes (unproject_bf16_supported).
+bool unproject_bf16_supported(const BasisPlan &plan, WhtPath path, int dtype, int C);
+hipError_t launch_unproject_bf16(const void *in, void *out, int N, int H, int W, int C, const BasisPlan &plan,
+                                 hipStream_t stream, int extra = 0);
 
 // Tokens outside the grid.  gather: out[n*extra + e][c] = scale * in[n][e][c] (rows appended to
 // a projected tensor so that the products treat them exactly); scatter: the reverse for the
@@ -54,7 +59,8 @@ hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *
                                int N, int H, int W, const BasisPlan &plan, hipStream_t stream, int extra = 0,
                                float extra_scale0 = 1.0f, float extra_scale1 = 1.0f);
 hipError_t launch_unproject_mfma(const float *in, int slices, void *out, int N, int H, int W, int C,
-                                 const BasisPlan &plan, hipStream_t stream, int extra = 0, long slice_rows = 0);
+                                 const BasisPlan &plan, hipStream_t stream, int extra = 0, long slice_rows = 0,
+                                 bool in_bf16 = false);
 
 // energy[j] += sum over patches q and channels of coef[q*pp + j][c]^2 for all pp = p^2 bases; `partial`
 // is scratch of pp * energy_chunks(Q) doubles.

@@ -110,6 +110,18 @@ int fuse_unproject_from_env()
     return std::strcmp(s, "0") ? 1 : 0;
 }
 
+// LBP_GX_COEF: "f32" keeps the coefficients of an unfused input-gradient product in fp32 (split-K
+// slices), "bf16" stores them as bf16 wherever the kernels allow, unset lets the planner choose
+// (testing and measurement).  Returns the `coef16` argument of plan_workspace.
+int gx_coef_from_env()
+{
+    const char *s = std::getenv("LBP_GX_COEF");
+    if (!s || !*s) return 1;
+    if (!std::strcmp(s, "f32")) return 0;
+    if (!std::strcmp(s, "bf16")) return 2;
+    return 1;
+}
+
 // gW = scale * A^T-style product with split-K: direct store when one slice suffices and the
 // kernel can write the output type, otherwise fp32 partial sums and a fixed-order reduction.
 lbp::WhtPath wht_path_from_env()
@@ -167,8 +179,14 @@ int plan_call(const lbp_shape_t *shape, int extra, int patch, int r, const lbp::
     const int fuse_env = fuse_unproject_from_env();
     const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
     const bool allow_group = both_outputs && gpath != lbp::GemmPath::kSimple && group_from_env();
+    // a product that stores bf16 coefficients for the reverse projection: matrix-core products and
+    // the matrix-core form of the reverse projection only
+    int coef16 = gx_coef_from_env();
+    if (gpath == lbp::GemmPath::kSimple || shape->dtype != LBP_BF16 ||
+        !lbp::unproject_bf16_supported(plan, wht_path_from_env(), shape->dtype, shape->Cin))
+        coef16 = 0;
     return lbp::plan_workspace(shape, patch, r, num_cus, can_fuse, fuse_env == 1, ws,
-                               !lbp::gemm_unproject_pooled(plan), allow_group, extra);
+                               !lbp::gemm_unproject_pooled(plan), allow_group, extra, coef16);
 }
 
 // Describes the weight-gradient product; returns true when it leaves fp32 partial sums in `part`
@@ -247,9 +265,10 @@ size_t lbp_wht_workspace_bytes_tokens(const lbp_shape_t *shape, int extra, int p
     // the plan of a call depends on the selection (fusable or not, pooled or not) and on whether
     // both gradients are requested: report the largest
     size_t total = 0;
-    for (int v = 0; v < 8; ++v) {
+    for (int v = 0; v < 24; ++v) {
         lbp::WorkspacePlan ws;
-        if (lbp::plan_workspace(shape, patch, r, cus, (v & 1) != 0, false, &ws, (v & 2) != 0, (v & 4) != 0, extra) != LBP_OK)
+        if (lbp::plan_workspace(shape, patch, r, cus, (v & 1) != 0, false, &ws, (v & 2) != 0, (v & 4) != 0, extra,
+                                v >> 3) != LBP_OK)
             return 0;
         if (ws.total > total) total = ws.total;
         if (patch == 0) break;
@@ -521,6 +540,10 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
             g.plan = &plan;
             g.extra = extra;
             g.extra_rows = N * extra;
+        } else if (ws.gx_coef16) {
+            g.splits = 1;
+            g.out = lbp::GemmOut::kBF16;
+            g.C = gx_r;
         } else {
             g.splits = ws.gx.splits;
             g.out = lbp::GemmOut::kF32;
@@ -539,7 +562,9 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     if (ev) LBP_HIP(hipEventRecord(ev[2], s));
     if (gx) {
         if (!grouped) LBP_HIP(lbp::launch_gemm(g, gpath, s));
-        if (!ws.gx_fused) {
+        if (!ws.gx_fused && ws.gx_coef16) {
+            LBP_HIP(lbp::launch_unproject_bf16(gx_r, gx, N, H, Wd, Cin, plan, s, extra));
+        } else if (!ws.gx_fused) {
             LBP_HIP(lbp::launch_unproject(gx_r, ws.gx.splits, gx, N, H, Wd, Cin, dt, plan, path, s, extra, Mr));
             LBP_HIP(lbp::launch_scatter_extra(gx_r + (size_t)Mq * Cin, ws.gx.splits, (size_t)Mr * Cin, gx, N, extra,
                                               img_tokens, Cin, dt, inv_pp, s));
@@ -602,6 +627,10 @@ int lbp_wht_describe_plan(const lbp_shape_t *shape, int extra, int patch, const 
         if (ws.gx_fused)
             std::snprintf(gxs, sizeof gxs, "gx: tile %s, reverse projection fused (%s epilogue); ",
                           lbp::kGemmTiles[ws.gx.tile].name, lbp::gemm_unproject_pooled(plan) ? "pooled" : "matrix-core");
+        else if (ws.gx_coef16)
+            std::snprintf(gxs, sizeof gxs, "gx: tile %s, bf16 coefficients + %s reverse-projection kernel; ",
+                          lbp::kGemmTiles[ws.gx.tile].name,
+                          lbp::projection_kernel_name(plan, path, shape->dtype, shape->Cin));
         else
             std::snprintf(gxs, sizeof gxs, "gx: tile %s, split-K %d + %s reverse-projection kernel; ",
                           mfma ? lbp::kGemmTiles[ws.gx.tile].name : "fp32 64x64", ws.gx.splits,

@@ -219,7 +219,7 @@ long gemm_workgroups(const GemmPlan &g, long M, long N, int fused_r)
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
-                   bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group, int extra)
+                   bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group, int extra, int coef16)
 {
     if (!s || !ws) return LBP_ERR_NULL;
     std::memset(ws, 0, sizeof *ws);
@@ -301,12 +301,27 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
             ws->grouped = true;
         }
     }
+    // Where the reverse projection stays a kernel of its own, the product can hand it bf16
+    // coefficients in one piece instead of fp32 split-K slices: a quarter of the bytes on the way
+    // there and back, and any tile.  (Decided last, so that it only ever replaces the fp32 hand-over.)
+    if (!ws->gx_fused && coef16 > 0 && s->dtype == LBP_BF16 && extra == 0) {
+        if (ws->grouped) {
+            ws->gx_coef16 = true;       // the same tile, half the store
+        } else {
+            GemmPlan g = plan_gemm(Mr, s->Cin, s->Cout, 2, false, 0, 0, num_cus);
+            g.est_us += 8.0 + ((double)Mr * s->Cin * 2 + (double)M * s->Cin * esz) / 4.0e6;
+            if (coef16 > 1 || g.est_us < ws->gx.est_us) {
+                ws->gx = g;
+                ws->gx_coef16 = true;
+            }
+        }
+    }
     ws->gy_r = off;
     off += align_up((size_t)Mr * s->Cout * esz, 256);
     ws->x_r = off;
     off += align_up((size_t)Mr * s->Cin * esz, 256);
     ws->gx_r = off;
-    if (!ws->gx_fused) off += align_up((size_t)ws->gx.splits * Mr * s->Cin * 4, 256);
+    if (!ws->gx_fused) off += align_up((size_t)ws->gx.splits * Mr * s->Cin * (ws->gx_coef16 ? 2 : 4), 256);
     ws->splitk = off;
     off += align_up((size_t)ws->gw.splits * s->Cout * s->Cin * 4, 256);
     ws->total = off;

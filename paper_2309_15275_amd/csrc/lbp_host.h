@@ -115,16 +115,20 @@ struct WorkspacePlan {
     GemmPlan gx;                       // the input-gradient product
     bool gx_fused;                     // reverse projection fused into that product's epilogue
     bool grouped;                      // both products run in one launch (tiles chosen for that)
+    bool gx_coef16;                    // not fused: the product stores its coefficients as bf16 in one
+                                       // piece (no split-K) and the reverse projection reads those
 };
 
 // num_cus: compute units of the device (the GEMM plans depend on it); pass 256 when unknown.
 // can_fuse: the selection allows the fused reverse projection (false gives the larger workspace);
 // force_fuse: take it whenever allowed instead of comparing estimates; fused_wide: see plan_gemm;
 // allow_group: the caller wants both gradients and can launch the two products as one grid;
-// extra: tokens per image in front of the grid (tensors are [N][extra + H*W][C]).
+// extra: tokens per image in front of the grid (tensors are [N][extra + H*W][C]);
+// coef16: 1 = the caller has a reverse projection that reads bf16 coefficients (gx_coef16 may be
+// chosen), 2 = take it whenever the reverse projection is not fused, 0 = never.
 int plan_workspace(const lbp_shape_t *shape, int patch, int r, int num_cus, bool can_fuse,
                    bool force_fuse, WorkspacePlan *ws, bool fused_wide = false, bool allow_group = false,
-                   int extra = 0);
+                   int extra = 0, int coef16 = 0);
 
 const char *status_string(int code);
 

@@ -554,4 +554,16 @@ hipError_t launch_unproject(const float *in, int slices, void *out, int N, int H
     return launch_generic<true>(in, out, N, H, W, C, dtype, plan, sl, stream, extra);
 }
 
+bool unproject_bf16_supported(const BasisPlan &plan, WhtPath path, int dtype, int C)
+{
+    return use_mfma_path(plan, path, dtype, C);
+}
+
+hipError_t launch_unproject_bf16(const void *in, void *out, int N, int H, int W, int C, const BasisPlan &plan,
+                                 hipStream_t stream, int extra)
+{
+    if (!wht_mfma_supported(plan, LBP_BF16, C)) return hipErrorInvalidValue;
+    return launch_unproject_mfma((const float *)in, 1, out, N, H, W, C, plan, stream, extra, 0, true);
+}
+
 }  // namespace lbp

@@ -276,7 +276,10 @@ __global__ __launch_bounds__(256, (A_LDS ? 4 : (KSTEPS == 4 && MTILES == 1 ? 5 :
 // reverse: tokens[t][c] = (1/p^2) * sum_k sign(nat_k, t) * coefficients[k][c]
 // MTILES = padded tokens per patch / 32; KSTEPS = ceil(r / 16) upper bound
 // ---------------------------------------------------------------------------------------------
-template <int MTILES, int KSTEPS, bool CACHE_A>
+// IN_BF16: the coefficients arrive as one bf16 tensor [P*r][C] (a product that stored them itself,
+// rounded once from its fp32 accumulators: what this kernel does to fp32 input anyway) instead of
+// fp32 split-K slices; `in` is then read as bf16, 16 bytes a lane, and `slices` is ignored.
+template <int MTILES, int KSTEPS, bool CACHE_A, bool IN_BF16 = false>
 __global__ __launch_bounds__(256) void wht_unproject_mfma_kernel(const float *__restrict__ in, int slices,
                                                                  size_t slice_stride, unsigned short *out,
                                                                  int C, int chunks, long items, GridGeom g,
@@ -334,7 +337,16 @@ __global__ __launch_bounds__(256) void wht_unproject_mfma_kernel(const float *__
         // ---- coefficients (fp32, split-K slices summed in fixed order) -> bf16 -> LDS [basis][channel]
         // lane: 4 channels (cc4) of basis rows tid/32, tid/32 + 8, ...: all loads of a slice are issued
         // before any is used (patch 16 has no registers for that and keeps the plain loop)
-        if constexpr (KSTEPS > 4) {
+        if constexpr (IN_BF16) {
+            const unsigned short *inb = reinterpret_cast<const unsigned short *>(in);
+            for (int c = tid; c < ksteps * 16 * (CB / 8); c += 256) {
+                const int k = c >> 4, cc = c & 15;
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (k < r && c0 + cc * 8 < C)
+                    v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(inb + ((size_t)q * r + k) * C + c0 + cc * 8));
+                *reinterpret_cast<u32x4_t *>(smem + k * S_IN + cc * 16) = v;
+            }
+        } else if constexpr (KSTEPS > 4) {
             for (int c = tid; c < ksteps * 16 * (CB / 4); c += 256) {
                 int k = c >> 5, cc = c & 31;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -520,7 +532,7 @@ hipError_t launch_project_mfma(const void *in0, void *out0, int C0, const void *
 }
 
 hipError_t launch_unproject_mfma(const float *in, int slices, void *out, int N, int H, int W, int C,
-                                 const BasisPlan &plan, hipStream_t stream, int extra, long slice_rows)
+                                 const BasisPlan &plan, hipStream_t stream, int extra, long slice_rows, bool in_bf16)
 {
     const long Q = patch_count(N, H, W, plan.patch);
     GridGeom g = make_geom(H, W, plan.patch, extra);
@@ -534,19 +546,25 @@ hipError_t launch_unproject_mfma(const float *in, int slices, void *out, int N, 
     const int kpad = (plan.r + 15) / 16 * 16;
     const int rows = p2 > kpad ? p2 : kpad;
     const int lds = rows * S_IN;
-#define LBP_LAUNCH(MT, KS, CACHE)                                                                   \
+#define LBP_LAUNCH_T(MT, KS, CACHE, INB)                                                            \
     do {                                                                                            \
-        auto kern = wht_unproject_mfma_kernel<MT, KS, CACHE>;                                       \
+        auto kern = wht_unproject_mfma_kernel<MT, KS, CACHE, INB>;                                  \
         hipError_t e = set_lds(kern, lds);                                                          \
         if (e != hipSuccess) return e;                                                              \
         hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, stream, in, slices, slice_stride,    \
                            (unsigned short *)out, C, chunks, items, g, nat, plan.r, ipw);           \
+    } while (0)
+#define LBP_LAUNCH(MT, KS, CACHE)                       \
+    do {                                                \
+        if (in_bf16) LBP_LAUNCH_T(MT, KS, CACHE, true); \
+        else LBP_LAUNCH_T(MT, KS, CACHE, false);        \
     } while (0)
     if (p2 <= 32) LBP_LAUNCH(1, 1, true);                       // patch 2 and 4: at most 16 bases
     else if (p2 == 64 && plan.r <= 32) LBP_LAUNCH(2, 2, true);
     else if (p2 == 64) LBP_LAUNCH(2, 4, true);
     else LBP_LAUNCH(8, 16, false);
 #undef LBP_LAUNCH
+#undef LBP_LAUNCH_T
     return hipGetLastError();
 }
 

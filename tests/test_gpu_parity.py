@@ -21,7 +21,7 @@ def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     yield
-    for var in ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT", "LBP_GEMM_TILE", "LBP_GEMM_GROUP"):
+    for var in ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT", "LBP_GEMM_TILE", "LBP_GEMM_GROUP", "LBP_GX_COEF"):
         os.environ.pop(var, None)
     torch.cuda.synchronize()
 
@@ -153,6 +153,27 @@ def test_backward_matches_oracle_on_ragged_shapes(dtype, case, variant):
     idx = oracle.select_bases(patch, r, order)
     egx, egw = run_backward_case(wl, idx)
     assert egx <= TOL[dtype] and egw <= TOL[dtype], (egx, egw)
+
+
+# The reverse projection as a kernel of its own can be fed fp32 split-K slices or one bf16 tensor of
+# coefficients (the product rounds once, as the matrix-core reverse kernel does to fp32 input).
+@pytest.mark.parametrize("group", ["1", "0"])
+@pytest.mark.parametrize("coef", ["bf16", "f32"])
+@pytest.mark.parametrize("case", [(2, 16, 16, 72, 136, 8, 21), (6, 16, 32, 264, 520, 8, 36), (3, 24, 16, 136, 200, 8, 15),
+                                  (2, 7, 7, 64, 136, 8, 36), (4, 14, 14, 136, 264, 8, 64), (2, 32, 32, 40, 24, 16, 10)])
+def test_unfused_reverse_projection_from_bf16_or_fp32_coefficients(case, coef, group):
+    N, H, W, Cin, Cout, patch, r = case
+    os.environ["LBP_FUSE_UNPROJECT"], os.environ["LBP_GX_COEF"], os.environ["LBP_GEMM_GROUP"] = "0", coef, group
+    wl = small("coef", N, H, W, Cin, Cout, patch, "bf16", 900 + r)
+    idx = oracle.select_bases(patch, r, "l1")
+    shape = binding.LbpShape(N, H, W, Cin, Cout, binding.LBP_BF16, binding.LBP_F32)
+    text = binding.describe_plan(shape, patch, idx)
+    assert ("bf16 coefficients" in text) == (coef == "bf16"), text
+    host, dev = device_inputs(wl)
+    gx, gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx)
+    want_gx, want_gw = oracle.lbp_wht_backward_padded(host["x"], host["gy"], host["w"], patch, idx)
+    assert rel_fro(to_host(gx), want_gx) <= TOL["bf16"]
+    assert rel_fro(to_host(gW), want_gw) <= TOL["bf16"]
 
 
 # Grids that are not multiples of the patch: zero-padded at the bottom and right (the 49-token maps

@@ -13,7 +13,7 @@ from paper_2309_15275_amd.workloads import Workload
 
 pytestmark = pytest.mark.gpu
 
-ENV = ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT", "LBP_GEMM_TILE", "LBP_GEMM_GROUP")
+ENV = ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT", "LBP_GEMM_TILE", "LBP_GEMM_GROUP", "LBP_GX_COEF")
 
 
 @pytest.fixture(autouse=True)

@@ -193,7 +193,7 @@ def test_products_entry_point_checks_its_arguments(lib):
 
 def test_launch_plans_of_the_benchmark_configurations(lib, monkeypatch):
     # host logic only: what a call would launch on a 256-unit device
-    for var in ("LBP_GEMM_GROUP", "LBP_FUSE_UNPROJECT", "LBP_GEMM_PATH", "LBP_WHT_PATH", "LBP_GEMM_TILE"):
+    for var in ("LBP_GEMM_GROUP", "LBP_FUSE_UNPROJECT", "LBP_GEMM_PATH", "LBP_WHT_PATH", "LBP_GEMM_TILE", "LBP_GX_COEF"):
         monkeypatch.delenv(var, raising=False)
     S = binding.LbpShape
     plan = lambda sh, p, r, order="l1", **kw: binding.describe_plan(sh, p, binding.select_bases(p, r, order), num_cus=256, **kw)
@@ -241,7 +241,7 @@ def test_plan_description_checks_its_arguments(lib):
 def test_reported_workspace_covers_every_plan_on_random_shapes(lib, monkeypatch):
     # lbp_wht_workspace_bytes is what a caller who brings the workspace allocates: it must cover the
     # plan of any call with that shape, rank and kind of selection, whichever outputs are asked for
-    for var in ("LBP_GEMM_GROUP", "LBP_FUSE_UNPROJECT", "LBP_GEMM_PATH", "LBP_WHT_PATH", "LBP_GEMM_TILE"):
+    for var in ("LBP_GEMM_GROUP", "LBP_FUSE_UNPROJECT", "LBP_GEMM_PATH", "LBP_WHT_PATH", "LBP_GEMM_TILE", "LBP_GX_COEF"):
         monkeypatch.delenv(var, raising=False)
     rng = np.random.default_rng(2024)
     for _ in range(150):
