@@ -278,9 +278,13 @@ __global__ __launch_bounds__(256, (A_LDS ? 4 : (KSTEPS == 4 && MTILES == 1 ? 5 :
 // ---------------------------------------------------------------------------------------------
 // IN_BF16: the coefficients arrive as one bf16 tensor [P*r][C] (a product that stored them itself,
 // rounded once from its fp32 accumulators: what this kernel does to fp32 input anyway) instead of
-// fp32 split-K slices; `in` is then read as bf16, 16 bytes a lane, and `slices` is ignored.
+// fp32 split-K slices; `in` is then read as bf16, 16 bytes a lane, and `slices` is ignored.  That form
+// has few, short items (one patch x 128 channels per workgroup, 1536 of them at ViT-B fc1), so it is
+// bound by the length of one item's load -> LDS -> matrix core -> LDS -> store chain and gains from
+// residency: held to 5 wavefronts per SIMD (94 registers, no spills; 3 when left alone, because
+// the accumulators then go to AGPRs) it takes 14 instead of 17 us at 36 bases.
 template <int MTILES, int KSTEPS, bool CACHE_A, bool IN_BF16 = false>
-__global__ __launch_bounds__(256) void wht_unproject_mfma_kernel(const float *__restrict__ in, int slices,
+__global__ __launch_bounds__(256, (IN_BF16 && MTILES == 2 ? 5 : 1)) void wht_unproject_mfma_kernel(const float *__restrict__ in, int slices,
                                                                  size_t slice_stride, unsigned short *out,
                                                                  int C, int chunks, long items, GridGeom g,
                                                                  NatTable nat, int r, int items_per_wg)
