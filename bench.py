@@ -19,10 +19,12 @@ reverse projection, per patch, summed over the batch) per second.  The line also
   preprojected_x_ms_per_step        lbp_wht_backward_preprojected: x^ kept from the forward pass,
   stages                            each part of a call timed by itself, back to back (projection; the two
                                     products as the call launches them; each product launched alone),
-  roofline                          the kernel that takes the larger share of a step: the grouped launch
-                                    of the two products (bf16 MFMA: algorithmic FLOPs / its average
+  roofline                          the kernel that takes the larger share of a step: the two products
+                                    (one grouped launch at the default workload; `kernel` says what the
+                                    planner launches at this rank; bf16 MFMA: algorithmic FLOPs / average
                                     duration) or the projection of gy and x (HBM: algorithmic bytes /
-                                    its average duration); roofline_second is the other one,
+                                    average duration); roofline_second is the other one; `traffic` is
+                                    filled in only where profiles/ holds counters for this workload and rank,
   warm_cache_ms_per_step            the same step on one buffer set over and over (cache-warm), labelled,
   cpu_baseline                      the CPU oracle timed on this machine's host cores (all threads; beside it one
                                     thread, and the oracle's exact backward).
@@ -51,15 +53,18 @@ def full_bp_flops(wl):
     return 4.0 * wl.Cin * wl.Cout * wl.tokens
 
 
-def read_traffic(name):
-    """HBM bytes per launch of the projection kernel from the committed rocprofv3 counter summary
-    (profiles/<name>), or None."""
+def read_traffic(name, r, order):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 counter summary (profiles/<name>),
+    or None when there is none for this workload, rank and basis order."""
     path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
         return None
+    matches = False
     for line in open(path):
+        if line.startswith("measured_at"):
+            matches = line.split()[1:] == [f"rank={r}", f"order={order}"]
         if line.startswith("traffic_bytes_per_launch"):
-            return float(line.split()[1])
+            return float(line.split()[1]) if matches else None
     return None
 
 
@@ -242,9 +247,14 @@ def main():
                  else "projection of gy and x (one launch)",
                 "achieved": round(proj_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(proj_gbs / HBM_PEAK_GBS, 4),
-                "traffic": read_traffic(f"wht_project_{wl.name}_hbm_traffic.txt"),
+                "traffic": read_traffic(f"wht_project_{wl.name}_hbm_traffic.txt", r, args.order),
                 "algorithmic_bytes": proj_bytes, "avg_launch_us": round(ms_proj * 1e3, 2)}
     gemm_flops = 2.0 * Mr * wl.Cin * wl.Cout
+    # what the planner launches for the products of this call (tiles, one launch or several)
+    shape = binding.LbpShape(wl.N, wl.H, wl.W, wl.Cin, wl.Cout, binding.LBP_F32 if wl.dtype == "f32" else binding.LBP_BF16,
+                             binding.LBP_F32)
+    plan_text = binding.describe_plan(shape, wl.patch, idx, extra=wl.extra)
+    plan_products = plan_text.split("products: ", 1)[-1].split("; workspace", 1)[0]
     # the two products (one grouped launch where the planner groups them; with the reverse projection
     # in the epilogue where it can be fused): 2 * M_r * Cin * Cout FLOPs each against the dense bf16
     # (fp32: vector fp32) peak; timed back to back from projected tensors on the launch stream
@@ -253,9 +263,9 @@ def main():
         peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else 157.3
         tf = 2.0 * gemm_flops / (ms_prod * 1e-3) / 1e12
         roof_prod = {"bound": "mfma" if wl.dtype == "bf16" else "alu",
-                     "kernel": "the two products of a call: g^y W with Eq. 7 in the epilogue and g^y^T x^ (one grouped launch)",
+                     "kernel": "the two products of a call, g^y W with the reverse projection of Eq. 7 and g^y^T x^ (" + plan_products + ")",
                      "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
-                     "traffic": read_traffic(f"gemm_products_{wl.name}_hbm_traffic.txt"),
+                     "traffic": read_traffic(f"gemm_products_{wl.name}_hbm_traffic.txt", r, args.order),
                      "algorithmic_flops": 2.0 * gemm_flops, "avg_launch_us": round(ms_prod * 1e3, 2)}
         # the other candidate bound: operands read once, outputs written once
         prod_bytes = esz * (Mr * (wl.Cin + wl.Cout) + wl.Cin * wl.Cout + wl.tokens * wl.Cin) + 4 * wl.Cin * wl.Cout
