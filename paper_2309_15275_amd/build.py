@@ -14,7 +14,7 @@ LIB = os.path.join(PKG, "liblbpwht.so")
 
 SOURCES = ["lbp_host.cpp", "wht_kernels.hip", "wht_mfma_kernels.hip", "energy_kernels.hip", "extra_kernels.hip", "gemm_kernels.hip", "gemm_mfma.hip",
            "gemm_mfma_128x128.hip", "gemm_mfma_64x128.hip", "gemm_mfma_256x128.hip",
-           "gemm_mfma_256x256.hip", "gemm_mfma_128x128w8.hip", "gemm_mfma_64x128w8.hip", "gemm_mfma_64x64.hip", "gemm_mfma_pair.hip",
+           "gemm_mfma_256x256.hip", "gemm_mfma_128x128w8.hip", "gemm_mfma_64x128w8.hip", "gemm_mfma_64x64.hip", "gemm_mfma_256x192.hip", "gemm_mfma_pair.hip",
            "lbp_api.hip"]
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions on this target.

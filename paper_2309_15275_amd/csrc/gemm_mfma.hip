@@ -12,7 +12,8 @@ typedef hipError_t (*TileLaunch)(const mfma::Params &, bool, GemmOut, int, int, 
 
 // same order as kGemmTiles
 const TileLaunch kLaunch[kNumGemmTiles] = {mfma_tile_128x128, mfma_tile_64x128, mfma_tile_256x128,
-                                           mfma_tile_256x256, mfma_tile_128x128w8, mfma_tile_64x128w8, mfma_tile_64x64};
+                                           mfma_tile_256x256, mfma_tile_128x128w8, mfma_tile_64x128w8, mfma_tile_64x64,
+                                           mfma_tile_256x192};
 
 int tile_from_env()
 {

@@ -136,7 +136,7 @@ __device__ __forceinline__ void extra_row_range(const Params &p, int m0, int &lo
 template <int BM, int BN, bool A_KFAST>
 struct Smem {
     static constexpr bool A_SWZ = !A_KFAST && BM >= 128;
-    static constexpr bool B_SWZ = BN >= 128;
+    static constexpr bool B_SWZ = BN % 128 == 0;      // the permutation works on rows of whole 256-byte groups
     static constexpr int SA = A_KFAST ? (BK + 8) * 2 : (A_SWZ ? BM * 2 : BM * 2 + 64);   // row pitch of A in bytes
     static constexpr int SB = B_SWZ ? BN * 2 : BN * 2 + 64;
     static constexpr int A_BYTES = (A_KFAST ? BM : BK) * SA;
@@ -643,6 +643,7 @@ hipError_t mfma_tile_256x256(const mfma::Params &p, bool a_kfast, GemmOut out, i
 hipError_t mfma_tile_128x128w8(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
 hipError_t mfma_tile_64x128w8(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
 hipError_t mfma_tile_64x64(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
+hipError_t mfma_tile_256x192(const mfma::Params &p, bool a_kfast, GemmOut out, int lp, int splits, hipStream_t s);
 
 // Grouped launch of the input-gradient product `x` (A reduction-fast; tile 128x128 or 64x128 with 8
 // wavefronts: bm_x = 128 or 64; out_x as in launch_gemm, kUnproject needs patch 8) and the

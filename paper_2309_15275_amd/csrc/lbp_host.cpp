@@ -163,6 +163,9 @@ const GemmTileInfo kGemmTiles[kNumGemmTiles] = {
     {128, 128, true, 0.92, 0, "128x128 (8 wavefronts)"},    // 8 wavefronts: hides more of the LDS -> matrix-core latency
     {64, 128, true, 0.88, 0, "64x128 (8 wavefronts)"},      // 8 wavefronts
     {64, 64, true, 1.0, 64, "64x64 (4 wavefronts)"},        // thin layers only: on wide ones it measured 10-15 % behind 64 x 128
+    // 768 columns are four of these: the exact backward's gx at ViT-B is then 256 equal workgroups
+    // (82 us against 93-98 us for the other tiles; behind them on every split-K product measured)
+    {256, 192, false, 1.4, 0, "256x192 (8 wavefronts)", true},
 };
 
 GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split, int fused_r,
@@ -179,6 +182,7 @@ GemmPlan plan_gemm(long M, long N, long K, int out_elem_bytes, bool allow_split,
         if (only_tile >= 0 && t != only_tile) continue;
         if (fused_r > 0 && (!ti.fused || fused_r > ti.bm)) continue;
         if (ti.max_n > 0 && N > ti.max_n) continue;
+        if (ti.whole_k && allow_split) continue;
         if (fused_r > 0 && fused_wide && ti.bn != 128) continue;
         if (N <= 64 && ti.bn > 64 && !(fused_r > 0 && fused_wide)) continue;      // a thin product takes the 64-wide tile (measured)
         const long bm_step = fused_r > 0 ? ti.bm / fused_r * fused_r : ti.bm;

@@ -79,8 +79,9 @@ struct GemmTileInfo {
     double slowdown;   // measured factor over the simple cost model below
     int max_n;         // only offered to products with at most this many columns (0: any)
     const char *name;  // for diagnostics
+    bool whole_k = false;   // only offered to products the caller will not split along the reduction
 };
-constexpr int kNumGemmTiles = 7;
+constexpr int kNumGemmTiles = 8;
 extern const GemmTileInfo kGemmTiles[kNumGemmTiles];
 
 // How one matrix product is run.

@@ -261,7 +261,7 @@ def test_energy_spectrum_on_a_zero_padded_grid(dtype):
     assert np.max(np.abs(got - want)) <= tol * want.max()
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6, 7])
 @pytest.mark.parametrize("case", [0, 3, 10, 13])
 def test_every_gemm_tile_shape_matches_oracle(case, tile):
     # LBP_GEMM_TILE forces one tile shape of the matrix-core kernel for every product of the call
