@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import oracle
-from _gpu_util import TOL, device_inputs, rel_fro, to_device, to_host
+from _gpu_util import TOL, assert_matches, device_inputs, full_backward, lbp_backward, nan_outputs, rel_fro, to_device, to_host
 from paper_2309_15275_amd import binding, workloads
 from paper_2309_15275_amd.workloads import Workload
 
@@ -90,10 +90,11 @@ def test_reverse_projection_matches_oracle(dtype, path, sel):
 
 
 def run_backward_case(wl, idx, gw_dtype=torch.float32):
+    """The whole call into NaN-filled outputs against the whole oracle: norm, every row, every element."""
     host, dev = device_inputs(wl)
-    gx, gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], wl.patch, idx, gw_dtype=gw_dtype)
+    gx, gW = lbp_backward(dev, wl.patch, idx, gw_dtype=gw_dtype)
     gx0, gW0 = oracle.lbp_wht_backward(host["x"], host["gy"], host["w"], wl.patch, idx)
-    return rel_fro(to_host(gx), gx0), rel_fro(to_host(gW), gW0)
+    return assert_matches(gx, gx0, TOL[wl.dtype], "gx"), assert_matches(gW, gW0, TOL[wl.dtype], "gW")
 
 
 @pytest.mark.parametrize("r", [4, 16])
@@ -108,10 +109,10 @@ def test_cfg1_all_bases_is_exact_backprop_fp32():
     wl = workloads.WORKLOADS["cfg1_tiny"]
     host, dev = device_inputs(wl)
     idx = oracle.select_bases(wl.patch, 16, "l1")
-    gx, gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], wl.patch, idx)
+    gx, gW = lbp_backward(dev, wl.patch, idx)
     gx0, gW0 = oracle.full_bp_backward(host["x"], host["gy"], host["w"])
-    assert rel_fro(to_host(gx), gx0) <= TOL["f32"]
-    assert rel_fro(to_host(gW), gW0) <= TOL["f32"]
+    assert_matches(gx, gx0, TOL["f32"], "gx")
+    assert_matches(gW, gW0, TOL["f32"], "gW")
 
 
 RAGGED = [
@@ -170,10 +171,10 @@ def test_unfused_reverse_projection_from_bf16_or_fp32_coefficients(case, coef, g
     text = binding.describe_plan(shape, patch, idx)
     assert ("bf16 coefficients" in text) == (coef == "bf16"), text
     host, dev = device_inputs(wl)
-    gx, gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx)
+    gx, gW = lbp_backward(dev, patch, idx)
     want_gx, want_gw = oracle.lbp_wht_backward_padded(host["x"], host["gy"], host["w"], patch, idx)
-    assert rel_fro(to_host(gx), want_gx) <= TOL["bf16"]
-    assert rel_fro(to_host(gW), want_gw) <= TOL["bf16"]
+    assert_matches(gx, want_gx, TOL["bf16"], "gx")
+    assert_matches(gW, want_gw, TOL["bf16"], "gW")
 
 
 # Grids that are not multiples of the patch: zero-padded at the bottom and right (the 49-token maps
@@ -237,17 +238,21 @@ def test_backward_on_zero_padded_grids(dtype, case, variant):
     # guard rows behind gx: nothing may be written past the last real token
     gx_buf = torch.full((N * H * W + 64, Cin), 7.0, dtype=dev["x"].dtype, device="cuda")
     gx = gx_buf[:N * H * W].view(N, H, W, Cin)
-    _, gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx, gx=gx)
+    gx.fill_(float("nan"))                  # every real token must be written
+    gW = torch.full((Cout, Cin), float("nan"), dtype=torch.float32, device="cuda")
+    binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx, gx=gx, gW=gW)
     gx0, gW0 = oracle.lbp_wht_backward_padded(host["x"], host["gy"], host["w"], patch, idx)
-    egx, egw = rel_fro(to_host(gx), gx0), rel_fro(to_host(gW), gW0)
-    assert egx <= TOL[dtype] and egw <= TOL[dtype], (egx, egw)
+    assert_matches(gx, gx0, TOL[dtype], "gx")
+    assert_matches(gW, gW0, TOL[dtype], "gW")
     assert bool((gx_buf[N * H * W:] == 7.0).all())
     if len(idx) == patch * patch:
         fx, fW = oracle.full_bp_backward(host["x"], host["gy"], host["w"])
-        assert rel_fro(to_host(gx), fx) <= TOL[dtype] and rel_fro(to_host(gW), fW) <= TOL[dtype]
+        assert_matches(gx, fx, TOL[dtype], "gx against exact backprop")
+        assert_matches(gW, fW, TOL[dtype], "gW against exact backprop")
     # x projected ahead of time gives the same bits
     x_r = binding.wht_project(dev["x"], patch, idx)
-    gx2, gW2 = binding.lbp_wht_backward_preprojected(x_r, dev["gy"], dev["w"], patch, idx)
+    gx2, gW2 = nan_outputs(gx.shape, gx.dtype, gW.shape)
+    binding.lbp_wht_backward_preprojected(x_r, dev["gy"], dev["w"], patch, idx, gx=gx2, gW=gW2)
     assert torch.equal(gx2, gx) and torch.equal(gW2, gW)
 
 
@@ -269,12 +274,12 @@ def test_every_gemm_tile_shape_matches_oracle(case, tile):
     N, H, W, Cin, Cout, patch, r, order = RAGGED[case]
     wl = small("tiles", N, H, W, Cin, Cout, patch, "bf16", 400 + case)
     idx = oracle.select_bases(patch, r, order)
-    egx, egw = run_backward_case(wl, idx)
-    assert egx <= TOL["bf16"] and egw <= TOL["bf16"], (egx, egw)
+    run_backward_case(wl, idx)
     host, dev = device_inputs(wl)
-    gx, gW = binding.full_bp_backward(dev["x"], dev["gy"], dev["w"])
+    gx, gW = full_backward(dev)
     gx0, gW0 = oracle.full_bp_backward(host["x"], host["gy"], host["w"])
-    assert rel_fro(to_host(gx), gx0) <= 5e-3 and rel_fro(to_host(gW), gW0) <= 5e-3
+    assert_matches(gx, gx0, 5e-3, "exact gx")
+    assert_matches(gW, gW0, 5e-3, "exact gW")
 
 
 @pytest.mark.parametrize("tile", ["4", "6"])
@@ -289,13 +294,14 @@ def test_grouped_launch_on_ragged_shapes(case, fuse, tile):
     host, dev = device_inputs(wl)
     os.environ["LBP_GEMM_TILE"], os.environ["LBP_FUSE_UNPROJECT"] = tile, fuse
     os.environ["LBP_GEMM_GROUP"] = "0"
-    gx0, gW0 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx)
+    gx0, gW0 = lbp_backward(dev, patch, idx)
     os.environ["LBP_GEMM_GROUP"] = "1"
-    gx1, gW1 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx)
+    gx1, gW1 = lbp_backward(dev, patch, idx)
     assert torch.equal(gx0.view(torch.int16), gx1.view(torch.int16))
     assert torch.equal(gW0.view(torch.int32), gW1.view(torch.int32))
     gxo, gWo = oracle.lbp_wht_backward(host["x"], host["gy"], host["w"], patch, idx)
-    assert rel_fro(to_host(gx1), gxo) <= TOL["bf16"] and rel_fro(to_host(gW1), gWo) <= TOL["bf16"]
+    assert_matches(gx1, gxo, TOL["bf16"], "gx")
+    assert_matches(gW1, gWo, TOL["bf16"], "gW")
 
 
 def test_split_k_partial_sums_feed_the_reverse_projection():
@@ -304,15 +310,13 @@ def test_split_k_partial_sums_feed_the_reverse_projection():
     wl = small("splitgx", 1, 8, 16, 64, 4096, 8, "bf16", 450)
     for r in (4, 21):
         idx = oracle.select_bases(8, r, "l1")
-        egx, egw = run_backward_case(wl, idx)
-        assert egx <= TOL["bf16"] and egw <= TOL["bf16"], (r, egx, egw)
+        run_backward_case(wl, idx)
 
 
 def test_arbitrary_unordered_selection_backward():
     wl = small("lhe", 3, 16, 16, 72, 136, 8, "bf16", 260)
     for idx in ([9, 0, 18, 2, 16], [63, 1, 8], [0, 4, 32, 36]):
-        egx, egw = run_backward_case(wl, np.asarray(idx))
-        assert egx <= TOL["bf16"] and egw <= TOL["bf16"], (idx, egx, egw)
+        run_backward_case(wl, np.asarray(idx))
 
 
 @pytest.mark.parametrize("gemm", ["auto", "simple"])
@@ -321,10 +325,10 @@ def test_full_rank_backward_matches_oracle(dtype, gemm):
     os.environ["LBP_GEMM_PATH"] = gemm
     wl = small("full", 3, 16, 24, 72, 200, 8, dtype, 300)
     host, dev = device_inputs(wl)
-    gx, gW = binding.full_bp_backward(dev["x"], dev["gy"], dev["w"])
+    gx, gW = full_backward(dev)
     gx0, gW0 = oracle.full_bp_backward(host["x"], host["gy"], host["w"])
-    assert rel_fro(to_host(gx), gx0) <= (TOL["f32"] if dtype == "f32" else 5e-3)
-    assert rel_fro(to_host(gW), gW0) <= (TOL["f32"] if dtype == "f32" else 5e-3)
+    assert_matches(gx, gx0, TOL["f32"] if dtype == "f32" else 5e-3, "gx")
+    assert_matches(gW, gW0, TOL["f32"] if dtype == "f32" else 5e-3, "gW")
 
 
 def test_only_one_output_requested():
@@ -332,10 +336,13 @@ def test_only_one_output_requested():
     host, dev = device_inputs(wl)
     idx = oracle.select_bases(8, 8, "l1")
     gx0, gW0 = oracle.lbp_wht_backward(host["x"], host["gy"], host["w"], 8, idx)
-    gx, none = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx, want_gw=False)
-    assert none is None and rel_fro(to_host(gx), gx0) <= TOL["bf16"]
-    none, gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx, want_gx=False)
-    assert none is None and rel_fro(to_host(gW), gW0) <= TOL["bf16"]
+    gx, gW = nan_outputs(dev["x"].shape, dev["x"].dtype, dev["w"].shape)
+    _, none = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx, gx=gx, want_gw=False)
+    assert none is None
+    assert_matches(gx, gx0, TOL["bf16"], "gx alone")
+    none, _ = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx, gW=gW, want_gx=False)
+    assert none is None
+    assert_matches(gW, gW0, TOL["bf16"], "gW alone")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -347,11 +354,13 @@ def test_backward_with_x_projected_in_the_forward_pass(dtype):
     for r, order in [(8, "l1"), (21, "l1")]:
         idx = oracle.select_bases(8, r, order)
         x_r = binding.wht_project(dev["x"], 8, idx)
-        gx, gW = binding.lbp_wht_backward_preprojected(x_r, dev["gy"], dev["w"], 8, idx)
-        gx1, gW1 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx)
+        gx, gW = nan_outputs(dev["x"].shape, dev["x"].dtype, dev["w"].shape)
+        binding.lbp_wht_backward_preprojected(x_r, dev["gy"], dev["w"], 8, idx, gx=gx, gW=gW)
+        gx1, gW1 = lbp_backward(dev, 8, idx)
         assert torch.equal(gx, gx1) and torch.equal(gW, gW1)
         gx0, gW0 = oracle.lbp_wht_backward(host["x"], host["gy"], host["w"], 8, idx)
-        assert rel_fro(to_host(gx), gx0) <= TOL[dtype] and rel_fro(to_host(gW), gW0) <= TOL[dtype]
+        assert_matches(gx, gx0, TOL[dtype], "gx")
+        assert_matches(gW, gW0, TOL[dtype], "gW")
     # only gW needs x^ at all
     _, gW2 = binding.lbp_wht_backward_preprojected(x_r, dev["gy"], dev["w"], 8, idx, want_gx=False)
     assert torch.equal(gW2, gW)
@@ -365,8 +374,8 @@ def test_stage_timing_entry_point_runs_the_same_backward():
     os.environ["LBP_GEMM_GROUP"] = "0"
     gx0, gW0 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx)
     os.environ.pop("LBP_GEMM_GROUP")
-    gx = torch.empty_like(gx0)
-    gW = torch.empty_like(gW0)
+    gx = torch.full_like(gx0, float("nan"))
+    gW = torch.full_like(gW0, float("nan"))
     ms = binding.lbp_wht_backward_profile(dev["x"], dev["gy"], dev["w"], 8, idx, gx, gW)
     assert len(ms) == 3 and all(0.0 < t < 100.0 for t in ms)
     assert torch.equal(gx.view(torch.int16), gx0.view(torch.int16)) and torch.equal(gW.view(torch.int32), gW0.view(torch.int32))
@@ -379,8 +388,9 @@ def test_products_from_projected_tensors_give_the_same_bits(dtype):
     host, dev = device_inputs(wl)
     for idx in (oracle.select_bases(8, 8, "l1"), oracle.select_bases(8, 21, "l1")):
         x_r, gy_r = binding.wht_project_pair(dev["x"], dev["gy"], 8, idx)
-        a = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx)
-        b = binding.lbp_wht_products(x_r, gy_r, dev["w"], (wl.N, wl.H, wl.W), 8, idx)
+        a = lbp_backward(dev, 8, idx)
+        b = nan_outputs(dev["x"].shape, dev["x"].dtype, dev["w"].shape)
+        binding.lbp_wht_products(x_r, gy_r, dev["w"], (wl.N, wl.H, wl.W), 8, idx, gx=b[0], gW=b[1])
         bits = torch.int32 if dtype == "f32" else torch.int16
         assert torch.equal(a[0].view(bits), b[0].view(bits)) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
 
@@ -413,15 +423,13 @@ def test_lhe_selection_end_to_end():
     # the selection is unique only up to near-ties: the energy the chosen set keeps must match
     assert E0[idx].sum() >= (1 - 1e-3) * E0[idx0].sum()
     assert len(set(idx)) == 10 and idx[0] == 0
-    egx, egw = run_backward_case(wl, np.asarray(idx))
-    assert egx <= TOL["bf16"] and egw <= TOL["bf16"]
+    run_backward_case(wl, np.asarray(idx))
 
 
 def test_bf16_weight_gradient_output():
     wl = small("gwbf16", 2, 16, 16, 64, 128, 8, "bf16", 320)
     idx = oracle.select_bases(8, 8, "l1")
-    egx, egw = run_backward_case(wl, idx, gw_dtype=torch.bfloat16)
-    assert egx <= TOL["bf16"] and egw <= TOL["bf16"]
+    run_backward_case(wl, idx, gw_dtype=torch.bfloat16)
 
 
 def test_outputs_are_overwritten_and_repeatable():
