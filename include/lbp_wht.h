@@ -127,6 +127,24 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
                      int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream);
 
 /*
+ * lbp_wht_backward for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same bits
+ * as lbp_wht_backward, but the projected tensors, split-K partial sums and unfused coefficients
+ * live in a fixed array of LBP_STATIC_SCRATCH_BYTES that is part of the library's device image
+ * (every GPU the library runs on holds its own copy until the process ends) instead of the
+ * workspace.  The call makes no hipMalloc / hipFree and ignores lbp_set_workspace.
+ *   LBP_ERR_WORKSPACE  the call would need more scratch than the array holds (the need is what
+ *                      lbp_wht_workspace_bytes reports at most; ViT-B fc1, N = 64, r = 8 needs
+ *                      15.7 MB); nothing is launched.
+ * All calls on one GPU share that GPU's array, whatever their streams: two calls that overlap in
+ * time on one GPU race.  Calls ordered by one stream are safe; nothing in the array has to
+ * start at zero (every region is written before it is read within a call).
+ */
+#define LBP_STATIC_SCRATCH_BYTES (32u << 20)
+int lbp_wht_backward_static(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
+                            int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream);
+
+/*
  * Algorithm 1 with its first statement hoisted out: x^ = WHT(x; I) depends only on the layer's input
  * and the index set, so the forward pass can compute it once (lbp_wht_project on x) and keep it
  * instead of x, which is patch^2/r times larger.  x_r is that tensor, [P*r][Cin] of shape->dtype,

@@ -21,7 +21,7 @@ EXPORTS = ("lbp_wht_select_bases", "lbp_wht_select_lhe", "lbp_wht_energy", "lbp_
            "lbp_wht_project_pair", "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
            "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version",
            "lbp_wht_backward_tokens", "lbp_wht_project_tokens", "lbp_wht_backward_tokens_preprojected",
-           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products", "lbp_wht_energy_tokens", "lbp_wht_describe_plan")
+           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products", "lbp_wht_energy_tokens", "lbp_wht_describe_plan", "lbp_wht_backward_static")
 
 
 class LbpShape(ctypes.Structure):
@@ -53,6 +53,7 @@ def load():
     shp = ctypes.POINTER(LbpShape)
     lib.lbp_wht_select_bases.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p]
     lib.lbp_wht_backward.argtypes = [vp, vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.lbp_wht_backward_static.argtypes = lib.lbp_wht_backward.argtypes
     lib.lbp_wht_select_lhe.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int, ctypes.c_int, i32p]
     lib.lbp_wht_energy.argtypes = [vp] + [ctypes.c_int] * 6 + [vp, vp]
     lib.lbp_wht_energy_tokens.argtypes = [vp] + [ctypes.c_int] * 7 + [vp, vp]
@@ -188,6 +189,24 @@ def lbp_wht_backward(x, gy, w, patch, basis_idx, gx=None, gW=None, want_gx=True,
     idx, r = _idx_array(basis_idx)
     with torch.cuda.device(x.device):
         _check(load().lbp_wht_backward(
+            _dev_tensor(x, "x"), _dev_tensor(gy, "gy", x.dtype), _dev_tensor(w, "w", x.dtype),
+            ctypes.byref(shape), int(patch), idx, r,
+            _dev_tensor(gx, "gx", x.dtype) if gx is not None else None,
+            _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
+    return gx, gW
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def lbp_wht_backward_static(x, gy, w, patch, basis_idx, gx, gW, stream=None):
+    """lbp_wht_backward through the library's fixed scratch array: the library allocates nothing.
+    The caller brings both outputs (either may be None to skip it)."""
+    gw_dtype = gW.dtype if gW is not None else torch.float32
+    shape = make_shape(x, gy, w, gw_dtype)
+    idx, r = _idx_array(basis_idx)
+    with torch.cuda.device(x.device):
+        _check(load().lbp_wht_backward_static(
             _dev_tensor(x, "x"), _dev_tensor(gy, "gy", x.dtype), _dev_tensor(w, "w", x.dtype),
             ctypes.byref(shape), int(patch), idx, r,
             _dev_tensor(gx, "gx", x.dtype) if gx is not None else None,

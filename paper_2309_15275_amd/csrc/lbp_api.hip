@@ -24,12 +24,19 @@ int hip_fail(hipError_t e)
 
 constexpr int kMaxDevices = 64;
 
+// Scratch of lbp_wht_backward_static, the entry point that allocates nothing.  Part of the device
+// image: every GPU holds its own copy at its own address.  On the host this name is only a handle
+// for hipGetSymbolAddress; the address kernels get is DeviceState::static_ws.
+constexpr size_t kStaticScratchBytes = LBP_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 struct DeviceState {
     void *internal_ws = nullptr;
     size_t internal_bytes = 0;
     void *user_ws = nullptr;
     size_t user_bytes = 0;
     int num_cus = 0;
+    char *static_ws = nullptr;      // device address of `scratch` on this device
 };
 
 std::mutex g_mutex;
@@ -47,6 +54,12 @@ int current_device(int *dev, DeviceState **st)
         int cus = 0;
         e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d);
         if (e != hipSuccess) return hip_fail(e);
+        // first call on this device, which is current: its copy of the static scratch array
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255u)) return hip_fail(hipErrorInvalidSymbol);
+        g_dev[d].static_ws = static_cast<char *>(ptr);
         g_dev[d].num_cus = cus > 0 ? cus : 256;
     }
     *dev = d;
@@ -462,7 +475,7 @@ namespace {
 // gy_projected: `gy` already is g^y = WHT(gy; I) too (only with x_projected): the products alone.
 int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_t *shape, int patch,
                   const int32_t *basis_idx, int r, void *gx, void *gW, void *stream, hipEvent_t *ev,
-                  bool x_projected = false, int extra = 0, bool gy_projected = false)
+                  bool x_projected = false, int extra = 0, bool gy_projected = false, bool static_scratch = false)
 {
     if (!shape || !basis_idx) return LBP_ERR_NULL;
     if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
@@ -489,8 +502,13 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     rc = plan_call(shape, extra, patch, r, plan, st->num_cus, gx && gW && !ev, &ws);
     if (rc) return rc;
     char *base = nullptr;
-    rc = get_workspace(st, ws.total, &base);
-    if (rc) return rc;
+    if (static_scratch) {       // no allocation on this path: the fixed array or an error
+        if (ws.total > kStaticScratchBytes) return LBP_ERR_WORKSPACE;
+        base = st->static_ws;
+    } else {
+        rc = get_workspace(st, ws.total, &base);
+        if (rc) return rc;
+    }
 
     hipStream_t s = (hipStream_t)stream;
     const lbp::WhtPath path = wht_path_from_env();
@@ -582,6 +600,12 @@ int lbp_wht_backward(const void *x, const void *gy, const void *W, const lbp_sha
                      int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream)
 {
     return backward_impl(x, gy, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr);
+}
+
+int lbp_wht_backward_static(const void *x, const void *gy, const void *W, const lbp_shape_t *shape,
+                            int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream)
+{
+    return backward_impl(x, gy, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr, false, 0, false, true);
 }
 
 int lbp_wht_backward_preprojected(const void *x_r, const void *gy, const void *W,
