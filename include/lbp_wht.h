@@ -72,8 +72,9 @@ typedef enum {
                               fp32)                                                            */
     LBP_ERR_ORDER = -9,    /* order is neither LBP_ORDER_L1 nor LBP_ORDER_LINF                 */
     LBP_ERR_WORKSPACE = -10, /* caller-provided workspace too small                            */
-    LBP_ERR_HIP = -11      /* a HIP call failed (no device, allocation, launch); the HIP error
+    LBP_ERR_HIP = -11,     /* a HIP call failed (no device, allocation, launch); the HIP error
                               code is kept and returned by lbp_last_hip_error()                */
+    LBP_ERR_OPTION = -12   /* lbp_set_option: unknown name or a value it does not take         */
 } lbp_status_t;
 
 typedef struct {
@@ -262,6 +263,20 @@ int lbp_set_workspace(void *dev_ptr, size_t bytes);
 
 /* Frees the internal workspaces of all devices (synchronises each device first). */
 int lbp_release_workspace(void);
+
+/*
+ * Kernel-choice switches, for tests and measurement only (normal use never needs them: the
+ * planner chooses).  Process-wide; the value NULL puts a switch back to its default.  The first
+ * use of the switches also reads environment variables of the same names, once per process.
+ *   "LBP_WHT_PATH"        "generic" | "register" | "mfma"   projection kernels (default: chosen per selection)
+ *   "LBP_GEMM_PATH"       "simple"                          plain cross-check products
+ *   "LBP_GEMM_TILE"       "0" .. "7"                        one tile shape for every product
+ *   "LBP_FUSE_UNPROJECT"  "0" | "1"                         reverse projection never / always fused where possible
+ *   "LBP_GEMM_GROUP"      "0" | "1"                         the two products in separate launches / grouped where possible
+ *   "LBP_GX_COEF"         "f32" | "bf16"                    coefficients handed to an unfused reverse projection
+ * Returns LBP_ERR_NULL (name is NULL) or LBP_ERR_OPTION (unknown name or value).  No HIP call.
+ */
+int lbp_set_option(const char *name, const char *value);
 
 /* Static description of a status code. */
 const char *lbp_strerror(int code);

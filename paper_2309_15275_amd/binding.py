@@ -21,7 +21,7 @@ EXPORTS = ("lbp_wht_select_bases", "lbp_wht_select_lhe", "lbp_wht_energy", "lbp_
            "lbp_wht_project_pair", "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
            "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version",
            "lbp_wht_backward_tokens", "lbp_wht_project_tokens", "lbp_wht_backward_tokens_preprojected",
-           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products", "lbp_wht_energy_tokens", "lbp_wht_describe_plan", "lbp_wht_backward_static")
+           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products", "lbp_wht_energy_tokens", "lbp_wht_describe_plan", "lbp_wht_backward_static", "lbp_set_option")
 
 
 class LbpShape(ctypes.Structure):
@@ -78,6 +78,7 @@ def load():
     lib.lbp_wht_workspace_bytes.restype = ctypes.c_size_t
     lib.lbp_set_workspace.argtypes = [vp, ctypes.c_size_t]
     lib.lbp_release_workspace.argtypes = []
+    lib.lbp_set_option.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
     lib.lbp_strerror.argtypes = [ctypes.c_int]
     lib.lbp_strerror.restype = ctypes.c_char_p
     lib.lbp_last_hip_error.argtypes = []
@@ -100,6 +101,19 @@ def strerror(code):
 
 def version():
     return int(load().lbp_version())
+
+
+OPTIONS = ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_GEMM_TILE", "LBP_FUSE_UNPROJECT", "LBP_GEMM_GROUP", "LBP_GX_COEF")
+
+
+def set_option(name, value):
+    """A kernel-choice switch of the library (tests and measurement); value None restores the default."""
+    _check(load().lbp_set_option(name.encode(), None if value is None else str(value).encode()))
+
+
+def reset_options():
+    for name in OPTIONS:
+        set_option(name, None)
 
 
 def _idx_array(basis_idx):

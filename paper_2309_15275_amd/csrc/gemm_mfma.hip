@@ -15,14 +15,6 @@ const TileLaunch kLaunch[kNumGemmTiles] = {mfma_tile_128x128, mfma_tile_64x128, 
                                            mfma_tile_256x256, mfma_tile_128x128w8, mfma_tile_64x128w8, mfma_tile_64x64,
                                            mfma_tile_256x192};
 
-int tile_from_env()
-{
-    const char *s = std::getenv("LBP_GEMM_TILE");
-    if (!s || !*s) return -1;
-    int v = std::atoi(s);
-    return v >= 0 && v < kNumGemmTiles ? v : -1;
-}
-
 int device_cus()
 {
     static int cus = 0;
@@ -64,7 +56,7 @@ hipError_t prepare(const GemmArgs &a, int *tile_out, mfma::Params *out, int *lp_
     if (a.M < (a.a_kfast ? 1 : 8) || a.N < 8 || a.K < 1) return hipErrorInvalidValue;
     if (a.N % 8 || a.ldb % 8 || a.lda % 8 || (a.a_kfast ? a.K % 8 : a.M % 8)) return hipErrorInvalidValue;
     if (a.out != GemmOut::kF32 && a.splits != 1) return hipErrorInvalidValue;
-    int tile = tile_from_env();     // testing: force one tile shape for every product
+    int tile = options().gemm_tile;     // testing: force one tile shape for every product
     if (tile >= 0 && a.out == GemmOut::kUnproject &&
         (!kGemmTiles[tile].fused || (a.plan && !gemm_unproject_pooled(*a.plan) && kGemmTiles[tile].bn != 128)))
         tile = -1;

@@ -99,53 +99,9 @@ int get_workspace(DeviceState *st, size_t bytes, char **out)
     return LBP_OK;
 }
 
-lbp::GemmPath gemm_path_from_env()
-{
-    const char *s = std::getenv("LBP_GEMM_PATH");
-    if (s && !std::strcmp(s, "simple")) return lbp::GemmPath::kSimple;
-    return lbp::GemmPath::kAuto;
-}
-
-// LBP_GEMM_GROUP=0 keeps the two products of a backward call in separate launches (testing).
-bool group_from_env()
-{
-    const char *s = std::getenv("LBP_GEMM_GROUP");
-    return !(s && s[0] == '0' && s[1] == 0);
-}
-
-// LBP_FUSE_UNPROJECT: "0" keeps the reverse projection a kernel of its own, "1" fuses it into the
-// input-gradient product whenever the kernel supports the selection, unset lets the planner choose
-// (for testing and measurement).  Returns -1 when unset.
-int fuse_unproject_from_env()
-{
-    const char *s = std::getenv("LBP_FUSE_UNPROJECT");
-    if (!s || !*s) return -1;
-    return std::strcmp(s, "0") ? 1 : 0;
-}
-
-// LBP_GX_COEF: "f32" keeps the coefficients of an unfused input-gradient product in fp32 (split-K
-// slices), "bf16" stores them as bf16 wherever the kernels allow, unset lets the planner choose
-// (testing and measurement).  Returns the `coef16` argument of plan_workspace.
-int gx_coef_from_env()
-{
-    const char *s = std::getenv("LBP_GX_COEF");
-    if (!s || !*s) return 1;
-    if (!std::strcmp(s, "f32")) return 0;
-    if (!std::strcmp(s, "bf16")) return 2;
-    return 1;
-}
-
-// gW = scale * A^T-style product with split-K: direct store when one slice suffices and the
-// kernel can write the output type, otherwise fp32 partial sums and a fixed-order reduction.
-lbp::WhtPath wht_path_from_env()
-{
-    const char *s = std::getenv("LBP_WHT_PATH");
-    if (!s) return lbp::WhtPath::kAuto;
-    if (!std::strcmp(s, "generic")) return lbp::WhtPath::kGeneric;
-    if (!std::strcmp(s, "register")) return lbp::WhtPath::kRegister;
-    if (!std::strcmp(s, "mfma")) return lbp::WhtPath::kMfma;
-    return lbp::WhtPath::kAuto;
-}
+// The kernel-choice switches (lbp_set_option) in the kernels' own types.
+lbp::GemmPath gemm_path_option() { return lbp::options().gemm_simple ? lbp::GemmPath::kSimple : lbp::GemmPath::kAuto; }
+lbp::WhtPath wht_path_option() { return static_cast<lbp::WhtPath>(lbp::options().wht_path); }
 
 // Pointer, alias and alignment rules common to both backward entry points.
 int validate_buffers(const void *x, const void *gy, const void *W, const lbp_shape_t *s, void *gx,
@@ -188,15 +144,16 @@ bool tokens_ok(const lbp_shape_t *s, int extra)
 int plan_call(const lbp_shape_t *shape, int extra, int patch, int r, const lbp::BasisPlan &plan, int num_cus,
               bool both_outputs, lbp::WorkspacePlan *ws)
 {
-    const lbp::GemmPath gpath = gemm_path_from_env();
-    const int fuse_env = fuse_unproject_from_env();
+    const lbp::Options opt = lbp::options();
+    const lbp::GemmPath gpath = opt.gemm_simple ? lbp::GemmPath::kSimple : lbp::GemmPath::kAuto;
+    const int fuse_env = opt.fuse_unproject;
     const bool can_fuse = fuse_env != 0 && lbp::gemm_can_fuse_unproject(plan, shape->dtype, gpath);
-    const bool allow_group = both_outputs && gpath != lbp::GemmPath::kSimple && group_from_env();
+    const bool allow_group = both_outputs && gpath != lbp::GemmPath::kSimple && opt.gemm_group != 0;
     // a product that stores bf16 coefficients for the reverse projection: matrix-core products and
     // the matrix-core form of the reverse projection only
-    int coef16 = gx_coef_from_env();
+    int coef16 = opt.gx_coef;
     if (gpath == lbp::GemmPath::kSimple || shape->dtype != LBP_BF16 ||
-        !lbp::unproject_bf16_supported(plan, wht_path_from_env(), shape->dtype, shape->Cin))
+        !lbp::unproject_bf16_supported(plan, static_cast<lbp::WhtPath>(opt.wht_path), shape->dtype, shape->Cin))
         coef16 = 0;
     return lbp::plan_workspace(shape, patch, r, num_cus, can_fuse, fuse_env == 1, ws,
                                !lbp::gemm_unproject_pooled(plan), allow_group, extra, coef16);
@@ -252,6 +209,8 @@ int lbp_version(void) { return 100; }
 const char *lbp_strerror(int code) { return lbp::status_string(code); }
 
 int lbp_last_hip_error(void) { return t_last_hip_error; }
+
+int lbp_set_option(const char *name, const char *value) { return lbp::set_option(name, value); }
 
 int lbp_wht_select_bases(int patch, int r, int order, int32_t *basis_idx)
 {
@@ -353,7 +312,7 @@ int lbp_wht_project_tokens(const void *in, int N, int H, int W, int extra, int C
     DeviceState *st;
     rc = current_device(&dev, &st);
     if (rc) return rc;
-    LBP_HIP(lbp::launch_project(in, out, N, H, W, C, dtype, plan, wht_path_from_env(), (hipStream_t)stream, extra,
+    LBP_HIP(lbp::launch_project(in, out, N, H, W, C, dtype, plan, wht_path_option(), (hipStream_t)stream, extra,
                                 1.0f));
     return LBP_OK;
 }
@@ -384,7 +343,7 @@ int lbp_wht_project_pair(const void *x, const void *gy, const lbp_shape_t *shape
     rc = current_device(&dev, &st);
     if (rc) return rc;
     LBP_HIP(lbp::launch_project_pair(gy, gy_r, shape->Cout, x, x_r, shape->Cin, shape->N, shape->H, shape->W,
-                                     shape->dtype, plan, wht_path_from_env(), (hipStream_t)stream));
+                                     shape->dtype, plan, wht_path_option(), (hipStream_t)stream));
     return LBP_OK;
 }
 
@@ -436,7 +395,7 @@ int lbp_wht_energy_tokens(const void *in, int N, int H, int W, int extra, int C,
     hipStream_t s = (hipStream_t)stream;
     // all p^2 coefficients of every patch (row q*p^2 + j = basis j in sequency order), then their squares
     // (tokens outside the grid have no coefficients: they are skipped)
-    LBP_HIP(lbp::launch_project(in, base, N, H, W, C, dtype, plan, wht_path_from_env(), s, extra, 0.0f));
+    LBP_HIP(lbp::launch_project(in, base, N, H, W, C, dtype, plan, wht_path_option(), s, extra, 0.0f));
     LBP_HIP(lbp::launch_energy(base, Q, pp, C, dtype, (double *)(base + coef_bytes), energy, s));
     return LBP_OK;
 }
@@ -460,7 +419,7 @@ int lbp_wht_unproject(const void *in, int N, int H, int W, int C, int dtype, int
     DeviceState *st;
     rc = current_device(&dev, &st);
     if (rc) return rc;
-    LBP_HIP(lbp::launch_unproject((const float *)in, 1, out, N, H, W, C, dtype, plan, wht_path_from_env(),
+    LBP_HIP(lbp::launch_unproject((const float *)in, 1, out, N, H, W, C, dtype, plan, wht_path_option(),
                                   (hipStream_t)stream));
     return LBP_OK;
 }
@@ -496,7 +455,7 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     DeviceState *st;
     rc = current_device(&dev, &st);
     if (rc) return rc;
-    const lbp::GemmPath gpath = gemm_path_from_env();
+    const lbp::GemmPath gpath = gemm_path_option();
     lbp::WorkspacePlan ws;
     // both gradients wanted: the two products may share one launch (not when timed stage by stage)
     rc = plan_call(shape, extra, patch, r, plan, st->num_cus, gx && gW && !ev, &ws);
@@ -511,7 +470,7 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     }
 
     hipStream_t s = (hipStream_t)stream;
-    const lbp::WhtPath path = wht_path_from_env();
+    const lbp::WhtPath path = wht_path_option();
     const int N = shape->N, H = shape->H, Wd = shape->W, Cin = shape->Cin, Cout = shape->Cout;
     const int dt = shape->dtype;
     const long img_tokens = (long)H * Wd + extra;
@@ -640,8 +599,8 @@ int lbp_wht_describe_plan(const lbp_shape_t *shape, int extra, int patch, const 
     lbp::WorkspacePlan ws;
     rc = plan_call(shape, extra, patch, r, plan, num_cus, want_gx && want_gw, &ws);
     if (rc) return rc;
-    const bool mfma = shape->dtype == LBP_BF16 && gemm_path_from_env() != lbp::GemmPath::kSimple;
-    const lbp::WhtPath path = wht_path_from_env();
+    const bool mfma = shape->dtype == LBP_BF16 && gemm_path_option() != lbp::GemmPath::kSimple;
+    const lbp::WhtPath path = wht_path_option();
     const int pooled = (patch >> plan.mh) * (patch >> plan.mw);
     char gw[160] = "", gxs[200] = "";
     if (want_gw)
@@ -723,7 +682,7 @@ int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_sha
     rc = lbp::plan_workspace(shape, 0, 0, st->num_cus, false, false, &ws);
     if (rc) return rc;
     // the plain bf16 kernel needs an fp32 staging buffer of M x Cin for gx
-    size_t gx_stage = gx && dt == LBP_BF16 && gemm_path_from_env() == lbp::GemmPath::kSimple
+    size_t gx_stage = gx && dt == LBP_BF16 && gemm_path_option() == lbp::GemmPath::kSimple
                           ? ((size_t)M * Cin * 4 + 255) / 256 * 256 : 0;
     char *base = nullptr;
     rc = get_workspace(st, ws.total + gx_stage, &base);
@@ -731,7 +690,7 @@ int full_bp_backward(const void *x, const void *gy, const void *W, const lbp_sha
     hipStream_t s = (hipStream_t)stream;
     float *part = (float *)(base + ws.splitk);
 
-    const lbp::GemmPath gpath = gemm_path_from_env();
+    const lbp::GemmPath gpath = gemm_path_option();
     if (gW) {   // gW = gy^T x  (Eq. 2)
         rc = weight_gradient(gy, x, Cout, Cin, M, dt, shape->gw_dtype, ws.gw, 1.0f, part, gW, gpath, s);
         if (rc) return rc;

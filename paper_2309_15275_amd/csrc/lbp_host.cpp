@@ -3,7 +3,9 @@
 #include "lbp_host.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <tuple>
 #include <vector>
 
@@ -222,10 +224,10 @@ long gemm_workgroups(const GemmPlan &g, long M, long N, int fused_r)
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
-                   bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group, int extra, int coef16)
+static int plan_workspace_uncached(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
+                                   bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group, int extra,
+                                   int coef16)
 {
-    if (!s || !ws) return LBP_ERR_NULL;
     std::memset(ws, 0, sizeof *ws);
     if (num_cus < 1) num_cus = 256;
     const size_t esz = dtype_size(s->dtype);
@@ -332,6 +334,130 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
     return LBP_OK;
 }
 
+// The plan is a pure function of its arguments and costs dozens of sweeps over tiles and split
+// factors; a training loop calls with the same few layers over and over, so the last plans are kept.
+namespace {
+struct PlanKey {
+    int32_t v[16];
+    bool operator==(const PlanKey &o) const { return std::memcmp(v, o.v, sizeof v) == 0; }
+};
+struct PlanSlot {
+    bool used = false;
+    PlanKey key;
+    WorkspacePlan plan;
+};
+constexpr int kPlanSlots = 32;
+std::mutex g_plan_mutex;
+PlanSlot g_plan_cache[kPlanSlots];
+unsigned g_plan_next = 0;
+}  // namespace
+
+int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
+                   bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group, int extra, int coef16)
+{
+    if (!s || !ws) return LBP_ERR_NULL;
+    const PlanKey key{{s->N, s->H, s->W, s->Cin, s->Cout, s->dtype, s->gw_dtype, patch, r, num_cus, can_fuse,
+                       force_fuse, fused_wide, allow_group, extra, coef16}};
+    {
+        std::lock_guard<std::mutex> lock(g_plan_mutex);
+        for (const PlanSlot &slot : g_plan_cache)
+            if (slot.used && slot.key == key) {
+                *ws = slot.plan;
+                return LBP_OK;
+            }
+    }
+    const int rc = plan_workspace_uncached(s, patch, r, num_cus, can_fuse, force_fuse, ws, fused_wide, allow_group,
+                                           extra, coef16);
+    if (rc != LBP_OK) return rc;
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    PlanSlot &slot = g_plan_cache[g_plan_next++ % kPlanSlots];
+    slot.used = true;
+    slot.key = key;
+    slot.plan = *ws;
+    return LBP_OK;
+}
+
+namespace {
+
+std::mutex g_opt_mutex;
+Options g_opt;
+bool g_opt_env_read = false;
+
+const char *const kOptionNames[] = {"LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_GEMM_TILE", "LBP_FUSE_UNPROJECT",
+                                    "LBP_GEMM_GROUP", "LBP_GX_COEF"};
+
+// Applies one switch to `o`; value NULL or "" restores the default.
+int apply_option(Options *o, const char *name, const char *value)
+{
+    const Options def;
+    const bool reset = !value || !*value;
+    auto is = [&](const char *v) { return !reset && !std::strcmp(value, v); };
+    if (!std::strcmp(name, "LBP_WHT_PATH")) {
+        if (reset || is("auto")) o->wht_path = def.wht_path;
+        else if (is("generic")) o->wht_path = 1;
+        else if (is("register")) o->wht_path = 2;
+        else if (is("mfma")) o->wht_path = 3;
+        else return LBP_ERR_OPTION;
+    } else if (!std::strcmp(name, "LBP_GEMM_PATH")) {
+        if (reset || is("auto")) o->gemm_simple = 0;
+        else if (is("simple")) o->gemm_simple = 1;
+        else return LBP_ERR_OPTION;
+    } else if (!std::strcmp(name, "LBP_GEMM_TILE")) {
+        if (reset) {
+            o->gemm_tile = def.gemm_tile;
+            return LBP_OK;
+        }
+        char *end = nullptr;
+        const long v = std::strtol(value, &end, 10);
+        if (*end || v < 0 || v >= kNumGemmTiles) return LBP_ERR_OPTION;
+        o->gemm_tile = (int)v;
+    } else if (!std::strcmp(name, "LBP_FUSE_UNPROJECT")) {
+        if (reset) o->fuse_unproject = def.fuse_unproject;
+        else if (is("0")) o->fuse_unproject = 0;
+        else if (is("1")) o->fuse_unproject = 1;
+        else return LBP_ERR_OPTION;
+    } else if (!std::strcmp(name, "LBP_GEMM_GROUP")) {
+        if (reset || is("1")) o->gemm_group = 1;
+        else if (is("0")) o->gemm_group = 0;
+        else return LBP_ERR_OPTION;
+    } else if (!std::strcmp(name, "LBP_GX_COEF")) {
+        if (reset) o->gx_coef = def.gx_coef;
+        else if (is("f32")) o->gx_coef = 0;
+        else if (is("bf16")) o->gx_coef = 2;
+        else return LBP_ERR_OPTION;
+    } else {
+        return LBP_ERR_OPTION;
+    }
+    return LBP_OK;
+}
+
+// The only place the environment is read: once per process (g_opt_mutex held).  A value a switch
+// does not take is ignored.
+void read_env_once()
+{
+    if (g_opt_env_read) return;
+    g_opt_env_read = true;
+    for (const char *name : kOptionNames)
+        if (const char *v = std::getenv(name)) (void)apply_option(&g_opt, name, v);
+}
+
+}  // namespace
+
+Options options()
+{
+    std::lock_guard<std::mutex> lock(g_opt_mutex);
+    read_env_once();
+    return g_opt;
+}
+
+int set_option(const char *name, const char *value)
+{
+    if (!name) return LBP_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_opt_mutex);
+    read_env_once();
+    return apply_option(&g_opt, name, value);
+}
+
 const char *status_string(int code)
 {
     switch (code) {
@@ -347,6 +473,7 @@ const char *status_string(int code)
         case LBP_ERR_ORDER: return "order must be LBP_ORDER_L1 or LBP_ORDER_LINF";
         case LBP_ERR_WORKSPACE: return "caller-provided workspace is too small";
         case LBP_ERR_HIP: return "a HIP call failed (see lbp_last_hip_error)";
+        case LBP_ERR_OPTION: return "unknown option name or value";
         default: return "unknown status code";
     }
 }

@@ -133,4 +133,18 @@ int plan_workspace(const lbp_shape_t *shape, int patch, int r, int num_cus, bool
 
 const char *status_string(int code);
 
+// Kernel-choice switches (tests and measurement; see lbp_set_option in the public header).
+struct Options {
+    int wht_path = 0;          // 0 chosen per selection, 1 generic, 2 register, 3 matrix-core
+    int gemm_simple = 0;       // 1: plain cross-check products
+    int gemm_tile = -1;        // >= 0: one tile shape for every product
+    int fuse_unproject = -1;   // -1 planner, 0 never, 1 wherever the kernel supports the selection
+    int gemm_group = 1;        // 0: the two products of a call in separate launches
+    int gx_coef = 1;           // 1 planner, 0 fp32 slices, 2 bf16 wherever the kernels allow
+};
+// The current switches; the first call reads the LBP_* environment variables, once per process.
+Options options();
+// One switch by name; value NULL restores the default.  LBP_OK, LBP_ERR_NULL or LBP_ERR_OPTION.
+int set_option(const char *name, const char *value);
+
 }  // namespace lbp

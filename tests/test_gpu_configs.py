@@ -21,8 +21,7 @@ def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     yield
-    os.environ.pop("LBP_GEMM_GROUP", None)
-    os.environ.pop("LBP_WHT_PATH", None)
+    binding.reset_options()
     torch.cuda.synchronize()
 
 
@@ -136,9 +135,9 @@ def test_grouped_and_separate_launches_of_the_products_agree(case):
     wl = workloads.WORKLOADS[name]
     host, dev = device_inputs(wl)
     idx = oracle.select_bases(wl.patch, r, order)
-    os.environ["LBP_GEMM_GROUP"] = "0"
+    binding.set_option("LBP_GEMM_GROUP", "0")
     gx0, gW0 = lbp_backward(dev, wl.patch, idx)
-    os.environ.pop("LBP_GEMM_GROUP")
+    binding.set_option("LBP_GEMM_GROUP", None)
     gx1, gW1 = lbp_backward(dev, wl.patch, idx)
     assert rel_fro(to_host(gx1), to_host(gx0)) <= TOL["bf16"] and rel_fro(to_host(gW1), to_host(gW0)) <= 1e-5
     fn = oracle.lbp_wht_backward_padded if (wl.H % wl.patch or wl.W % wl.patch) else oracle.lbp_wht_backward
@@ -154,7 +153,7 @@ def test_tensors_beyond_two_to_the_31_elements(path):
     # The tensor is made on the device (seeded); patches sampled from its whole extent, the last
     # one included, are checked against the oracle's projection of the same values; then the
     # reverse projection of those coefficients, again against the oracle on sampled patches.
-    os.environ["LBP_WHT_PATH"] = path
+    binding.set_option("LBP_WHT_PATH", path)
     N, H, W, C, p = 512, 32, 32, 4352, 8
     gen = torch.Generator(device="cuda").manual_seed(4242)
     t = torch.randn((N, H, W, C), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
@@ -180,7 +179,7 @@ def test_tensors_beyond_two_to_the_31_elements(path):
         want = oracle.unproject(c, (1, p, p, C), p, idx)
         got = to_host(back[n, a * p:(a + 1) * p, b * p:(b + 1) * p, :])[None]
         assert rel_fro(got, want) <= 4e-3, int(q)
-    os.environ.pop("LBP_WHT_PATH", None)
+    binding.set_option("LBP_WHT_PATH", None)
 
 
 def test_backward_with_more_than_two_to_the_31_input_elements():

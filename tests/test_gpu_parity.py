@@ -21,8 +21,7 @@ def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     yield
-    for var in ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT", "LBP_GEMM_TILE", "LBP_GEMM_GROUP", "LBP_GX_COEF"):
-        os.environ.pop(var, None)
+    binding.reset_options()
     torch.cuda.synchronize()
 
 
@@ -58,7 +57,7 @@ def test_projection_matches_oracle(dtype, path, sel):
         pytest.skip("the matrix-core form exists for bf16 tensors only")
     patch, mk = SELECTIONS[sel]
     idx = np.asarray(mk())
-    os.environ["LBP_WHT_PATH"] = path
+    binding.set_option("LBP_WHT_PATH", path)
     # ragged: 3 images, non-square grid, channel count that is not a multiple of 64 lanes
     wl = small("proj", 3, 2 * patch, 3 * patch, 40, 72, patch, dtype, 7 + sel)
     host, dev = device_inputs(wl)
@@ -77,7 +76,7 @@ def test_reverse_projection_matches_oracle(dtype, path, sel):
         pytest.skip("the matrix-core form exists for bf16 tensors only")
     patch, mk = SELECTIONS[sel]
     idx = np.asarray(mk())
-    os.environ["LBP_WHT_PATH"] = path
+    binding.set_option("LBP_WHT_PATH", path)
     N, H, W, C = 2, 3 * patch, 2 * patch, 56
     rng = np.random.default_rng(100 + sel)
     coef = rng.standard_normal((N * H * W // (patch * patch) * len(idx), C)).astype(np.float32)
@@ -147,8 +146,9 @@ def test_backward_matches_oracle_on_ragged_shapes(dtype, case, variant):
     gemm, fuse = VARIANTS[variant]
     if gemm.endswith("+mfma-wht"):          # both projections in their matrix-core form, nothing fused
         gemm = "auto"
-        os.environ["LBP_WHT_PATH"] = "mfma"
-    os.environ["LBP_GEMM_PATH"], os.environ["LBP_FUSE_UNPROJECT"] = gemm, fuse
+        binding.set_option("LBP_WHT_PATH", "mfma")
+    binding.set_option("LBP_GEMM_PATH", gemm)
+    binding.set_option("LBP_FUSE_UNPROJECT", fuse)
     N, H, W, Cin, Cout, patch, r, order = RAGGED[case]
     wl = small("ragged", N, H, W, Cin, Cout, patch, dtype, 200 + case)
     idx = oracle.select_bases(patch, r, order)
@@ -164,7 +164,9 @@ def test_backward_matches_oracle_on_ragged_shapes(dtype, case, variant):
                                   (2, 7, 7, 64, 136, 8, 36), (4, 14, 14, 136, 264, 8, 64), (2, 32, 32, 40, 24, 16, 10)])
 def test_unfused_reverse_projection_from_bf16_or_fp32_coefficients(case, coef, group):
     N, H, W, Cin, Cout, patch, r = case
-    os.environ["LBP_FUSE_UNPROJECT"], os.environ["LBP_GX_COEF"], os.environ["LBP_GEMM_GROUP"] = "0", coef, group
+    binding.set_option("LBP_FUSE_UNPROJECT", "0")
+    binding.set_option("LBP_GX_COEF", coef)
+    binding.set_option("LBP_GEMM_GROUP", group)
     wl = small("coef", N, H, W, Cin, Cout, patch, "bf16", 900 + r)
     idx = oracle.select_bases(patch, r, "l1")
     shape = binding.LbpShape(N, H, W, Cin, Cout, binding.LBP_BF16, binding.LBP_F32)
@@ -200,7 +202,7 @@ def test_projections_on_zero_padded_grids(dtype, case, path):
         pytest.skip("the matrix-core form exists for bf16 tensors only")
     N, H, W, Cin, Cout, patch, mk = PADDED[case]
     idx = np.asarray(mk())
-    os.environ["LBP_WHT_PATH"] = path
+    binding.set_option("LBP_WHT_PATH", path)
     wl = small("padded", N, H, W, Cin, Cout, patch, dtype, 300 + case)
     host, dev = device_inputs(wl)
     for name in ("x", "gy"):
@@ -229,8 +231,8 @@ def test_backward_on_zero_padded_grids(dtype, case, variant):
     gemm, fuse = variant
     if dtype == "f32" and variant != ("auto", "1"):
         pytest.skip("the fp32 path has one implementation")
-    os.environ["LBP_GEMM_PATH"] = gemm
-    os.environ["LBP_FUSE_UNPROJECT"] = fuse
+    binding.set_option("LBP_GEMM_PATH", gemm)
+    binding.set_option("LBP_FUSE_UNPROJECT", fuse)
     N, H, W, Cin, Cout, patch, mk = PADDED[case]
     idx = np.asarray(mk())
     wl = small("padded", N, H, W, Cin, Cout, patch, dtype, 500 + case)
@@ -270,7 +272,7 @@ def test_energy_spectrum_on_a_zero_padded_grid(dtype):
 @pytest.mark.parametrize("case", [0, 3, 10, 13])
 def test_every_gemm_tile_shape_matches_oracle(case, tile):
     # LBP_GEMM_TILE forces one tile shape of the matrix-core kernel for every product of the call
-    os.environ["LBP_GEMM_TILE"] = str(tile)
+    binding.set_option("LBP_GEMM_TILE", str(tile))
     N, H, W, Cin, Cout, patch, r, order = RAGGED[case]
     wl = small("tiles", N, H, W, Cin, Cout, patch, "bf16", 400 + case)
     idx = oracle.select_bases(patch, r, order)
@@ -292,10 +294,11 @@ def test_grouped_launch_on_ragged_shapes(case, fuse, tile):
     wl = small("group", N, H, W, Cin, Cout, patch, "bf16", 430 + case)
     idx = oracle.select_bases(patch, r, order)
     host, dev = device_inputs(wl)
-    os.environ["LBP_GEMM_TILE"], os.environ["LBP_FUSE_UNPROJECT"] = tile, fuse
-    os.environ["LBP_GEMM_GROUP"] = "0"
+    binding.set_option("LBP_GEMM_TILE", tile)
+    binding.set_option("LBP_FUSE_UNPROJECT", fuse)
+    binding.set_option("LBP_GEMM_GROUP", "0")
     gx0, gW0 = lbp_backward(dev, patch, idx)
-    os.environ["LBP_GEMM_GROUP"] = "1"
+    binding.set_option("LBP_GEMM_GROUP", "1")
     gx1, gW1 = lbp_backward(dev, patch, idx)
     assert torch.equal(gx0.view(torch.int16), gx1.view(torch.int16))
     assert torch.equal(gW0.view(torch.int32), gW1.view(torch.int32))
@@ -322,7 +325,7 @@ def test_arbitrary_unordered_selection_backward():
 @pytest.mark.parametrize("gemm", ["auto", "simple"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_full_rank_backward_matches_oracle(dtype, gemm):
-    os.environ["LBP_GEMM_PATH"] = gemm
+    binding.set_option("LBP_GEMM_PATH", gemm)
     wl = small("full", 3, 16, 24, 72, 200, 8, dtype, 300)
     host, dev = device_inputs(wl)
     gx, gW = full_backward(dev)
@@ -371,9 +374,9 @@ def test_stage_timing_entry_point_runs_the_same_backward():
     wl = small("profile", 4, 16, 16, 136, 264, 8, "bf16", 279)
     host, dev = device_inputs(wl)
     idx = oracle.select_bases(8, 8, "l1")
-    os.environ["LBP_GEMM_GROUP"] = "0"
+    binding.set_option("LBP_GEMM_GROUP", "0")
     gx0, gW0 = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], 8, idx)
-    os.environ.pop("LBP_GEMM_GROUP")
+    binding.set_option("LBP_GEMM_GROUP", None)
     gx = torch.full_like(gx0, float("nan"))
     gW = torch.full_like(gW0, float("nan"))
     ms = binding.lbp_wht_backward_profile(dev["x"], dev["gy"], dev["w"], 8, idx, gx, gW)

@@ -13,16 +13,12 @@ from paper_2309_15275_amd.workloads import Workload
 
 pytestmark = pytest.mark.gpu
 
-ENV = ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_FUSE_UNPROJECT", "LBP_GEMM_TILE", "LBP_GEMM_GROUP", "LBP_GX_COEF")
-
-
 @pytest.fixture(autouse=True)
 def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     yield
-    for var in ENV:
-        os.environ.pop(var, None)
+    binding.reset_options()
     torch.cuda.synchronize()
 
 
@@ -58,8 +54,10 @@ def test_backward_with_tokens_outside_the_grid_matches_oracle(case, dtype, varia
     wht, gemm, fuse, group = VARIANTS[variant]
     if wht == "mfma" and dtype == "f32":
         pytest.skip("the matrix-core projections exist for bf16 tensors only")
-    os.environ["LBP_WHT_PATH"], os.environ["LBP_GEMM_PATH"] = wht, gemm
-    os.environ["LBP_FUSE_UNPROJECT"], os.environ["LBP_GEMM_GROUP"] = fuse, group
+    binding.set_option("LBP_WHT_PATH", wht)
+    binding.set_option("LBP_GEMM_PATH", gemm)
+    binding.set_option("LBP_FUSE_UNPROJECT", fuse)
+    binding.set_option("LBP_GEMM_GROUP", group)
     wl, extra, host, dev, idx = run_case(case, dtype, 600 + case)
     T = extra + wl.H * wl.W
     # sentinels: the outputs must be written completely

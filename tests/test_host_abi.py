@@ -191,10 +191,9 @@ def test_products_entry_point_checks_its_arguments(lib):
     assert f(P(X), P(GY), P(W_), ctypes.byref(sh), 8, idx, 4, P(GY + 32 * 128 * 2 - 16), P(GW), None) == -7
 
 
-def test_launch_plans_of_the_benchmark_configurations(lib, monkeypatch):
+def test_launch_plans_of_the_benchmark_configurations(lib):
     # host logic only: what a call would launch on a 256-unit device
-    for var in ("LBP_GEMM_GROUP", "LBP_FUSE_UNPROJECT", "LBP_GEMM_PATH", "LBP_WHT_PATH", "LBP_GEMM_TILE", "LBP_GX_COEF"):
-        monkeypatch.delenv(var, raising=False)
+    binding.reset_options()
     S = binding.LbpShape
     plan = lambda sh, p, r, order="l1", **kw: binding.describe_plan(sh, p, binding.select_bases(p, r, order), num_cus=256, **kw)
     vitb = S(64, 16, 16, 768, 3072, 1, 0)
@@ -216,11 +215,32 @@ def test_launch_plans_of_the_benchmark_configurations(lib, monkeypatch):
     assert "separate launches" in t and "fp32 64x64" in t and "fused" not in t
     t = plan(vitb, 8, 8, want_gx=False)
     assert "separate launches" in t and "gx:" not in t and "gW:" in t
-    monkeypatch.setenv("LBP_GEMM_GROUP", "0")
+    # the switches change the plan at once (the plan cache is keyed on what they decide)
+    grouped = plan(vitb, 8, 8)
+    binding.set_option("LBP_GEMM_GROUP", "0")
     assert "separate launches" in plan(vitb, 8, 8)
-    monkeypatch.delenv("LBP_GEMM_GROUP")
-    monkeypatch.setenv("LBP_FUSE_UNPROJECT", "0")
+    binding.set_option("LBP_GEMM_GROUP", None)
+    assert plan(vitb, 8, 8) == grouped
+    binding.set_option("LBP_FUSE_UNPROJECT", "0")
     assert "fused" not in plan(vitb, 8, 8)
+    binding.reset_options()
+    assert plan(vitb, 8, 8) == grouped
+
+
+def test_option_switches_check_their_arguments(lib):
+    f = lib.lbp_set_option
+    assert f(None, b"0") == -1
+    assert f(b"LBP_NO_SUCH_SWITCH", b"0") == -12
+    assert f(b"LBP_GEMM_TILE", b"8") == -12 and f(b"LBP_GEMM_TILE", b"x") == -12 and f(b"LBP_GEMM_TILE", b"-1") == -12
+    assert f(b"LBP_WHT_PATH", b"fast") == -12 and f(b"LBP_GX_COEF", b"f16") == -12
+    assert f(b"LBP_FUSE_UNPROJECT", b"2") == -12 and f(b"LBP_GEMM_GROUP", b"yes") == -12
+    for name, values in (("LBP_WHT_PATH", ("generic", "register", "mfma", "auto")), ("LBP_GEMM_PATH", ("simple", "auto")),
+                         ("LBP_GEMM_TILE", tuple(str(i) for i in range(8))), ("LBP_FUSE_UNPROJECT", ("0", "1")),
+                         ("LBP_GEMM_GROUP", ("0", "1")), ("LBP_GX_COEF", ("f32", "bf16"))):
+        for v in values:
+            assert f(name.encode(), v.encode()) == 0, (name, v)
+        assert f(name.encode(), None) == 0
+    assert "option" in binding.strerror(-12)
 
 
 def test_plan_description_checks_its_arguments(lib):
@@ -238,11 +258,10 @@ def test_plan_description_checks_its_arguments(lib):
     assert len(buf.value) == 63                          # cut to the buffer, NUL-terminated
 
 
-def test_reported_workspace_covers_every_plan_on_random_shapes(lib, monkeypatch):
+def test_reported_workspace_covers_every_plan_on_random_shapes(lib):
     # lbp_wht_workspace_bytes is what a caller who brings the workspace allocates: it must cover the
     # plan of any call with that shape, rank and kind of selection, whichever outputs are asked for
-    for var in ("LBP_GEMM_GROUP", "LBP_FUSE_UNPROJECT", "LBP_GEMM_PATH", "LBP_WHT_PATH", "LBP_GEMM_TILE", "LBP_GX_COEF"):
-        monkeypatch.delenv(var, raising=False)
+    binding.reset_options()
     rng = np.random.default_rng(2024)
     for _ in range(150):
         patch = int(rng.choice([2, 4, 8, 8, 8, 16]))
