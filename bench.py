@@ -9,6 +9,16 @@ that are already resident in HBM.  The default workload is the ViT-B MLP fc1 bac
 Consecutive steps rotate over several distinct sets of buffers so that the working set exceeds the
 256 MB last-level cache (cache-cold timing); --warm-cache reuses one set.
 
+Timing protocol.  `ms_per_step` (and `value`) is the contract's loop: W untimed steps, then exactly
+K steps between two events, bracketed by device synchronisation.  Every other figure -- the stages,
+the roofline kernels, the comparison points, the sweep -- comes from at least 100 launches whatever
+K is, timed in batches of 10 back-to-back launches, every batch between its own pair of events on
+the launch stream, and is the MEDIAN over the batches of the time per launch.  (An event between
+two launches costs about 2 us here: beside the roofline kernels `single_launch_us` gives the median
+with every launch between its own events, for comparison.)  All calls go to the library
+through argument lists built once per buffer set, so the host side of a launch is a few
+microseconds and the loops are bound by the GPU.
+
 Prints ONE JSON line.  `value` is the Table-1 FLOPs of LBP-WHT (projection + low-rank products +
 reverse projection, per patch, summed over the batch) per second.  The line also carries:
   full_bp_ms / speedup_vs_full_bp   the same-style exact backward (Eq. 2) from this library,
@@ -19,19 +29,27 @@ reverse projection, per patch, summed over the batch) per second.  The line also
   library_gemm_lowrank_products_ms  the two low-rank products through torch.matmul, to set beside
                                     stages.products_us,
   preprojected_x_ms_per_step        lbp_wht_backward_preprojected: x^ kept from the forward pass,
-  stages                            each part of a call timed by itself, back to back (projection; the two
-                                    products as the call launches them; each product launched alone),
+  stages                            each part of a call timed by itself (projection; the two products as the
+                                    call launches them; each product launched alone),
   roofline                          the kernel that takes the larger share of a step: the two products
                                     (one grouped launch at the default workload; `kernel` says what the
-                                    planner launches at this rank; bf16 MFMA: algorithmic FLOPs / average
-                                    duration) or the projection of gy and x (HBM: algorithmic bytes /
-                                    average duration); roofline_second is the other one; `traffic` is
-                                    filled in only where profiles/ holds counters for this workload and rank,
+                                    planner launches at this rank; bf16 MFMA: algorithmic FLOPs / median
+                                    launch duration) or the projection of gy and x (HBM: algorithmic bytes /
+                                    median launch duration); roofline_second is the other one; `traffic` is
+                                    the stored rocprofv3 counter reading under profiles/ for this workload and
+                                    rank (`traffic_source` names the file), null where there is none,
   warm_cache_ms_per_step            the same step on one buffer set over and over (cache-warm), labelled,
+  sweep                             one row per benchmark configuration, rank and basis order: time of the
+                                    low-rank backward, of the exact backward, their ratio, and the roofline
+                                    fractions of the projection (of the 8 TB/s HBM peak) and of the products (of
+                                    the dense bf16 matrix-core peak; fp32 rows: of the 157.3 TFLOP/s vector
+                                    peak); inputs drawn on the device with the workload's distributions;
+                                    --no-sweep skips it,
   cpu_baseline                      the CPU oracle timed on this machine's host cores (all threads; beside it one
                                     thread, and the oracle's exact backward).
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -42,6 +60,8 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+MIN_LAUNCHES = 100             # medians are taken over at least this many launches
+BATCH = 10                     # ... timed in batches of this many back-to-back launches
 
 
 def lbp_flops(wl, r):
@@ -70,6 +90,218 @@ def read_traffic(name, r, order):
     return None
 
 
+def sweep_cases(workloads):
+    """(workload name, rank, order) of every benchmark row: the five configurations' ranks and
+    orders (the tiny fp32 exactness case included), the 49-token maps and the 197-token sequences."""
+    for name, wl in workloads.WORKLOADS.items():
+        for r in wl.ranks:
+            for order in wl.orders:
+                yield name, r, order
+
+
+class Timer:
+    """Event timing on torch's current stream, which is the stream every library call is given."""
+
+    def __init__(self, torch):
+        self.torch = torch
+
+    def loop(self, step, steps, warmup):
+        """The contract's loop: `warmup` untimed steps, then exactly `steps` between two events."""
+        torch = self.torch
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(steps):
+            step(warmup + i)
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+    def launches(self, step, n=MIN_LAUNCHES, warmup=10, batch=BATCH):
+        """At least n launches in batches of `batch` back-to-back launches, every batch between its
+        own pair of events: (median over the batches of the time per launch, mean over all launches,
+        median of the same number of launches each between its own pair of events), in ms.  An event
+        between two launches costs about 2 us on this machine (its packet drains the queue), which
+        the third figure carries on every launch and the first on every tenth."""
+        torch = self.torch
+        nb = (max(n, MIN_LAUNCHES) + batch - 1) // batch
+        for i in range(warmup):
+            step(i)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(nb + 1)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for b in range(nb):
+            for i in range(batch):
+                step(warmup + b * batch + i)
+            ev[b + 1].record()
+        torch.cuda.synchronize()
+        t = np.array([ev[b].elapsed_time(ev[b + 1]) for b in range(nb)]) / batch
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(nb * batch + 1)]
+        ev[0].record()
+        for i in range(nb * batch):
+            step(warmup + i)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        single = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(nb * batch)])
+        return float(np.median(t)), float(t.mean()), float(np.median(single))
+
+
+class Case:
+    """One (workload, rank, order) on the device: rotating buffer sets and, per set, the argument
+    list of every library call the benchmark makes (built once; a launch is then one ctypes call)."""
+
+    def __init__(self, torch, binding, workloads, wl, r, order, seeded=True, warm=False):
+        self.torch, self.binding, self.wl, self.r, self.order = torch, binding, wl, r, order
+        self.lib = binding.load()
+        self.idx = binding.select_bases(wl.patch, r, order)
+        self.seq = wl.extra > 0
+        self.esz = 4 if wl.dtype == "f32" else 2
+        T = wl.H * wl.W + wl.extra
+        self.host = None
+        if seeded:
+            self.host = workloads.make_token_inputs(wl, wl.extra) if self.seq else workloads.make_inputs(wl)
+            base = {k: self._to_dev(v, workloads) for k, v in self.host.items()}
+        else:
+            base = self._device_inputs()
+        set_bytes = sum(t.numel() * t.element_size() for t in base.values()) + base["x"].numel() * self.esz \
+            + base["w"].numel() * 4
+        self.n_sets = 1 if warm else max(2, int(np.ceil(600e6 / set_bytes)))
+        self.sets = []
+        for i in range(self.n_sets):
+            s = {k: (v if i == 0 else v.clone()) for k, v in base.items()}
+            s["gx"] = torch.empty_like(s["x"])
+            s["gW"] = torch.empty(s["w"].shape, dtype=torch.float32, device="cuda")
+            self.sets.append(s)
+        dt = binding.LBP_F32 if wl.dtype == "f32" else binding.LBP_BF16
+        self.shape = binding.LbpShape(wl.N, wl.H, wl.W, wl.Cin, wl.Cout, dt, binding.LBP_F32)
+        # the exact backward sees a token sequence as one long row of a grid
+        self.full_shape = binding.LbpShape(wl.N, 1, T, wl.Cin, wl.Cout, dt, binding.LBP_F32) if self.seq else self.shape
+        self.idx_arr = (ctypes.c_int32 * len(self.idx))(*self.idx)
+        self.stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        Mr = wl.patches * r + wl.N * wl.extra
+        tdt = base["x"].dtype
+        for s in self.sets:
+            s["x_r"] = torch.empty((Mr, wl.Cin), dtype=tdt, device="cuda")
+            s["gy_r"] = torch.empty((Mr, wl.Cout), dtype=tdt, device="cuda")
+        self.calls = {k: [self._args(k, s) for s in self.sets] for k in
+                      ("lbp", "full", "full_gx", "full_gw", "pre", "proj", "prod", "prod_gw", "prod_gx")}
+        # fill x_r / gy_r of every set once (the products-alone and kept-projection calls read them)
+        for i in range(self.n_sets):
+            self.run("proj", i)
+        torch.cuda.synchronize()
+
+    def _to_dev(self, a, workloads):
+        torch = self.torch
+        if self.wl.dtype == "f32":
+            return torch.from_numpy(a).cuda()
+        return torch.from_numpy(workloads.bf16_bits(a).reshape(a.shape).view(np.int16)).cuda().view(torch.bfloat16)
+
+    def _device_inputs(self):
+        """Inputs of the workload's distributions drawn on the device (timing rows of the sweep: the
+        values only have to look like the seeded ones; nothing is compared)."""
+        torch, wl = self.torch, self.wl
+        gen = torch.Generator(device="cuda").manual_seed(wl.seed)
+        x = torch.nn.functional.gelu(torch.randn((wl.N, wl.H, wl.W, wl.Cin), generator=gen, device="cuda"))
+        w = 0.02 * torch.randn((wl.Cout, wl.Cin), generator=gen, device="cuda")
+        coarse = 1e-2 * torch.randn((wl.N, wl.Cout, 4, 4), generator=gen, device="cuda")
+        gy = torch.nn.functional.interpolate(coarse, size=(wl.H, wl.W), mode="bilinear", align_corners=True)
+        gy = gy.permute(0, 2, 3, 1).contiguous()
+        gy += 1e-3 * torch.randn(gy.shape, generator=gen, device="cuda")
+        del coarse
+        if self.seq:
+            xe = torch.nn.functional.gelu(torch.randn((wl.N, wl.extra, wl.Cin), generator=gen, device="cuda"))
+            ge = 1e-2 * torch.randn((wl.N, wl.extra, wl.Cout), generator=gen, device="cuda")
+            x = torch.cat([xe, x.view(wl.N, -1, wl.Cin)], dim=1).contiguous()
+            gy = torch.cat([ge, gy.view(wl.N, -1, wl.Cout)], dim=1).contiguous()
+        if wl.dtype == "f32":
+            return {"x": x, "gy": gy, "w": w}
+        return {"x": x.to(torch.bfloat16), "gy": gy.to(torch.bfloat16), "w": w.to(torch.bfloat16)}
+
+    def _args(self, kind, s):
+        """[(C function, argument tuple), ...] of one benchmark call on buffer set s."""
+        lib, wl, P = self.lib, self.wl, ctypes.c_void_p
+        p = {k: P(v.data_ptr()) for k, v in s.items()}
+        sh, fsh = ctypes.byref(self.shape), ctypes.byref(self.full_shape)
+        idx, r, st, patch, none = self.idx_arr, self.r, self.stream, wl.patch, None
+        dt = self.shape.dtype
+        if kind == "lbp":
+            if self.seq:
+                return [(lib.lbp_wht_backward_tokens, (p["x"], p["gy"], p["w"], sh, wl.extra, patch, idx, r, p["gx"], p["gW"], st))]
+            return [(lib.lbp_wht_backward, (p["x"], p["gy"], p["w"], sh, patch, idx, r, p["gx"], p["gW"], st))]
+        if kind == "full":
+            return [(lib.full_bp_backward, (p["x"], p["gy"], p["w"], fsh, p["gx"], p["gW"], st))]
+        if kind == "full_gx":
+            return [(lib.full_bp_backward, (p["x"], p["gy"], p["w"], fsh, p["gx"], none, st))]
+        if kind == "full_gw":
+            return [(lib.full_bp_backward, (p["x"], p["gy"], p["w"], fsh, none, p["gW"], st))]
+        if kind == "pre":
+            if self.seq:
+                return [(lib.lbp_wht_backward_tokens_preprojected,
+                         (p["x_r"], p["gy"], p["w"], sh, wl.extra, patch, idx, r, p["gx"], p["gW"], st))]
+            return [(lib.lbp_wht_backward_preprojected, (p["x_r"], p["gy"], p["w"], sh, patch, idx, r, p["gx"], p["gW"], st))]
+        if kind == "proj":
+            if self.seq:      # no two-tensor entry point for sequences: one projection call per tensor
+                return [(lib.lbp_wht_project_tokens, (p[a], wl.N, wl.H, wl.W, wl.extra, c, dt, patch, idx, r, p[b], st))
+                        for a, b, c in (("x", "x_r", wl.Cin), ("gy", "gy_r", wl.Cout))]
+            return [(lib.lbp_wht_project_pair, (p["x"], p["gy"], sh, patch, idx, r, p["x_r"], p["gy_r"], st))]
+        if self.seq:
+            return []         # lbp_wht_products takes grids only
+        gx, gW = (none if kind == "prod_gw" else p["gx"]), (none if kind == "prod_gx" else p["gW"])
+        return [(lib.lbp_wht_products, (p["x_r"], p["gy_r"], p["w"], sh, patch, idx, r, gx, gW, st))]
+
+    def run(self, kind, i):
+        for fn, a in self.calls[kind][i % self.n_sets]:
+            rc = fn(*a)
+            if rc != 0:
+                raise self.binding.LbpError(rc, self.binding.strerror(rc), self.lib.lbp_last_hip_error())
+
+    def step(self, kind):
+        return lambda i: self.run(kind, i)
+
+    # ---- algorithmic work of the two kernels the roofline is about
+    @property
+    def Mr(self):
+        return self.wl.patches * self.r + self.wl.N * self.wl.extra
+
+    def proj_bytes(self):
+        """Projection launch: read gy and x once, write the r/p^2 fraction of each (and the tokens
+        outside the grid as they are)."""
+        wl = self.wl
+        return self.esz * (wl.tokens + self.Mr) * (wl.Cout + wl.Cin)
+
+    def products_flops(self):
+        """Both products: 2 * M_r * Cin * Cout each."""
+        return 4.0 * self.Mr * self.wl.Cin * self.wl.Cout
+
+    def products_bytes(self):
+        wl = self.wl
+        return self.esz * (self.Mr * (wl.Cin + wl.Cout) + wl.Cin * wl.Cout + wl.tokens * wl.Cin) + 4 * wl.Cin * wl.Cout
+
+    def plan_text(self):
+        return self.binding.describe_plan(self.shape, self.wl.patch, self.idx, extra=self.wl.extra)
+
+
+def sweep_row(case, timer, full_us):
+    """One row of the per-(configuration, rank, order) table; times are medians of >= 100 launches."""
+    wl = case.wl
+    lbp = timer.launches(case.step("lbp"))[0] * 1e3
+    proj = timer.launches(case.step("proj"))[0] * 1e3
+    peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else 157.3      # fp32 products run on the vector units
+    row = {"workload": wl.name, "dtype": wl.dtype, "r": case.r, "order": case.order, "lbp_us": round(lbp, 1),
+           "full_bp_us": round(full_us, 1), "speedup": round(full_us / lbp, 2), "proj_us": round(proj, 1),
+           "proj_frac_hbm": round(case.proj_bytes() / (proj * 1e-6) / 1e9 / HBM_PEAK_GBS, 3),
+           "prod_us": None, "prod_frac_peak": None}
+    if not case.seq:
+        prod = timer.launches(case.step("prod"))[0] * 1e3
+        row["prod_us"] = round(prod, 1)
+        row["prod_frac_peak"] = round(case.products_flops() / (prod * 1e-6) / 1e12 / peak, 3)
+    return row
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +313,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-library-gemm", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the per-(configuration, rank, order) table")
+    ap.add_argument("--sweep-table", default=None, help="also write the sweep as a text table to this file")
     ap.add_argument("--warm-cache", action="store_true", help="reuse one buffer set (cache-warm timing)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for the HBM byte counters)")
@@ -95,128 +329,45 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+    timer = Timer(torch)
     wl = workloads.WORKLOADS[args.workload]
     r = args.rank or wl.ranks[0]
-    idx = binding.select_bases(wl.patch, r, args.order)
-    esz = 4 if wl.dtype == "f32" else 2
+    case = Case(torch, binding, workloads, wl, r, args.order, seeded=True, warm=args.warm_cache)
+    seq, n_sets, sets, idx = case.seq, case.n_sets, case.sets, case.idx
 
-    # token-sequence workloads ([N, extra + H*W, C], a class token in front of the grid) go through
-    # the *_tokens entry points; the exact backward sees the same tokens as one long row of a grid
-    seq = wl.extra > 0
-    T = wl.H * wl.W + wl.extra
-    host = workloads.make_token_inputs(wl, wl.extra) if seq else workloads.make_inputs(wl)
-
-    def dev(a):
-        if wl.dtype == "f32":
-            return torch.from_numpy(a).cuda()
-        return torch.from_numpy(workloads.bf16_bits(a).reshape(a.shape).view(np.int16)).cuda().view(torch.bfloat16)
-
-    base = {k: dev(v) for k, v in host.items()}
-    set_bytes = sum(t.numel() * t.element_size() for t in base.values()) + base["x"].numel() * esz \
-        + base["w"].numel() * 4
-    n_sets = 1 if args.warm_cache else max(2, int(np.ceil(600e6 / set_bytes)))
-    sets = []
-    for i in range(n_sets):
-        s = {k: (v if i == 0 else v.clone()) for k, v in base.items()}
-        s["gx"] = torch.empty_like(s["x"])
-        s["gW"] = torch.empty(s["w"].shape, dtype=torch.float32, device="cuda")
-        sets.append(s)
-
-    grid = (wl.H, wl.W)
-
-    def as_grid(t):      # [N, T, C] -> [N, 1, T, C] for the entry points that take grids
-        return t.view(wl.N, 1, T, t.shape[-1]) if seq else t
-
-    def lbp_step(i):
-        s = sets[i % n_sets]
-        if seq:
-            binding.lbp_wht_backward_tokens(s["x"], s["gy"], s["w"], grid, wl.patch, idx, gx=s["gx"], gW=s["gW"])
-        else:
-            binding.lbp_wht_backward(s["x"], s["gy"], s["w"], wl.patch, idx, gx=s["gx"], gW=s["gW"])
-
-    def full_step(i):
-        s = sets[i % n_sets]
-        binding.full_bp_backward(as_grid(s["x"]), as_grid(s["gy"]), s["w"], gx=as_grid(s["gx"]), gW=s["gW"])
-
-    def lib_step(i):
-        s = sets[i % n_sets]
-        G = s["gy"].view(-1, wl.Cout)
-        torch.matmul(G, s["w"], out=s["gx"].view(-1, wl.Cin))
-        torch.matmul(G.t(), s["x"].view(-1, wl.Cin))      # allocates its result: the library's habit, not timed apart
-
-    def timed(fn, steps, warmup):
-        for i in range(warmup):
-            fn(i)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record()
-        for i in range(steps):
-            fn(warmup + i)
-        e1.record()
-        torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3
-        return e0.elapsed_time(e1) / steps, wall_ms / steps
-
-    if seq:      # no two-tensor entry point for sequences: one projection call per tensor
-        proj_bufs = [(binding.wht_project_tokens(s["x"], grid, wl.patch, idx),
-                      binding.wht_project_tokens(s["gy"], grid, wl.patch, idx)) for s in sets]
-    else:
-        proj_bufs = [binding.wht_project_pair(s["x"], s["gy"], wl.patch, idx) for s in sets]
-
-    def proj_step(i):
-        s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
-        if seq:
-            binding.wht_project_tokens(s["x"], grid, wl.patch, idx, out=xr)
-            binding.wht_project_tokens(s["gy"], grid, wl.patch, idx, out=gyr)
-        else:
-            binding.wht_project_pair(s["x"], s["gy"], wl.patch, idx, x_r=xr, gy_r=gyr)
-
-    def pre_step(i):
-        s, (xr, _) = sets[i % n_sets], proj_bufs[i % n_sets]
-        if seq:
-            binding.lbp_wht_backward_tokens_preprojected(xr, s["gy"], s["w"], grid, wl.patch, idx, gx=s["gx"], gW=s["gW"])
-        else:
-            binding.lbp_wht_backward_preprojected(xr, s["gy"], s["w"], wl.patch, idx, gx=s["gx"], gW=s["gW"])
-
-    def prod_step(i):      # the products alone, from projected tensors (grid workloads)
-        s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
-        binding.lbp_wht_products(xr, gyr, s["w"], (wl.N, wl.H, wl.W), wl.patch, idx, gx=s["gx"], gW=s["gW"])
-
-    ms_lbp, wall_lbp = timed(lbp_step, args.steps, args.warmup)
+    # per-launch medians first (they also bring clocks and caches to their steady state), then the
+    # contract's loop of exactly --steps steps
+    med_lbp, mean_lbp, b2b_lbp = timer.launches(case.step("lbp"))
+    ms_lbp, wall_lbp = timer.loop(case.step("lbp"), args.steps, args.warmup)
     # the cache-warm number beside it, labelled: one buffer set over and over
-    ms_warm = None if args.warm_cache else timed(lambda i: lbp_step(0), max(20, args.steps // 2), max(5, args.warmup // 2))[0]
+    ms_warm = None if args.warm_cache else timer.launches(lambda i: case.run("lbp", 0))[0]
     # the same steps recorded once into a HIP graph (one step per buffer set) and replayed: what a
     # training loop that captures its backward pass sees; launch gaps between the kernels shrink
     ms_graph = None
     if not args.no_graph:
         graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for i in range(n_sets):
-                lbp_step(i)
-        reps = max(1, args.steps // n_sets)
-        ms_graph, _ = timed(lambda i: graph.replay(), reps, max(1, args.warmup // n_sets))
-        ms_graph /= n_sets
+        with torch.cuda.graph(graph):      # capture runs on a stream of its own: the binding passes the current one
+            for s in sets:
+                if seq:
+                    binding.lbp_wht_backward_tokens(s["x"], s["gy"], s["w"], (wl.H, wl.W), wl.patch, idx, gx=s["gx"], gW=s["gW"])
+                else:
+                    binding.lbp_wht_backward(s["x"], s["gy"], s["w"], wl.patch, idx, gx=s["gx"], gW=s["gW"])
+        ms_graph = timer.launches(lambda i: graph.replay(), 30, batch=1)[0] / n_sets
     # the variant that keeps x^ from the forward pass (never reads x)
-    ms_pre, _ = timed(pre_step, args.steps, args.warmup)
-    # the dominant kernel by itself, back to back on the launch stream (same rotation of buffers)
-    ms_proj, _ = timed(proj_step, args.steps, args.warmup)
-    ms_prod = None if seq else timed(prod_step, args.steps, args.warmup)[0]
-    ms_full, _ = timed(full_step, max(10, args.steps // 4), max(3, args.warmup // 4))
-    ms_lib = ms_lib_lowrank = ms_best_full = None
+    ms_pre = timer.launches(case.step("pre"))[0]
+    # the two kernels of a call, each by itself on the launch stream (same rotation of buffers)
+    med_proj, mean_proj, b2b_proj = timer.launches(case.step("proj"))
+    med_prod = mean_prod = b2b_prod = None
+    if not seq:
+        med_prod, mean_prod, b2b_prod = timer.launches(case.step("prod"))
+    ms_full = timer.launches(case.step("full"))[0]
+    ms_lib = ms_lib_lowrank = ms_best_full = full_parts = None
     if not args.no_library_gemm:
-        ms_lib, _ = timed(lib_step, max(10, args.steps // 4), max(3, args.warmup // 4))
-        # the strongest exact backward on hand: each of its two products from whichever of this
-        # library and the vendor's is faster, each timed alone
-        n_q, w_q = max(10, args.steps // 4), max(3, args.warmup // 4)
-
-        def own_gx(i):
+        def lib_step(i):
             s = sets[i % n_sets]
-            binding.full_bp_backward(as_grid(s["x"]), as_grid(s["gy"]), s["w"], gx=as_grid(s["gx"]), want_gw=False)
-
-        def own_gw(i):
-            s = sets[i % n_sets]
-            binding.full_bp_backward(as_grid(s["x"]), as_grid(s["gy"]), s["w"], gW=s["gW"], want_gx=False)
+            G = s["gy"].view(-1, wl.Cout)
+            torch.matmul(G, s["w"], out=s["gx"].view(-1, wl.Cin))
+            torch.matmul(G.t(), s["x"].view(-1, wl.Cin))      # allocates its result: the library's habit, not timed apart
 
         def lib_gx(i):
             s = sets[i % n_sets]
@@ -226,36 +377,30 @@ def main():
             s = sets[i % n_sets]
             torch.matmul(s["gy"].view(-1, wl.Cout).t(), s["x"].view(-1, wl.Cin))
 
-        full_parts = {"own_gx_ms": timed(own_gx, n_q, w_q)[0], "own_gw_ms": timed(own_gw, n_q, w_q)[0],
-                      "library_gx_ms": timed(lib_gx, n_q, w_q)[0], "library_gw_ms": timed(lib_gw, n_q, w_q)[0]}
+        ms_lib = timer.launches(lib_step)[0]
+        # the strongest exact backward on hand: each of its two products from whichever of this
+        # library and the vendor's is faster, each timed alone
+        full_parts = {"own_gx_ms": timer.launches(case.step("full_gx"))[0], "own_gw_ms": timer.launches(case.step("full_gw"))[0],
+                      "library_gx_ms": timer.launches(lib_gx)[0], "library_gw_ms": timer.launches(lib_gw)[0]}
         ms_best_full = min(full_parts["own_gx_ms"], full_parts["library_gx_ms"]) + \
             min(full_parts["own_gw_ms"], full_parts["library_gw_ms"])
         if not seq:
             # the two LOW-RANK products through the vendor GEMM library, from the projected tensors
             # (no reverse projection, no 1/p^2): what a library call costs on shapes this small
-            lr_out = [torch.empty((xr.shape[0], wl.Cin), dtype=xr.dtype, device="cuda") for xr, _ in proj_bufs]
+            lr_out = [torch.empty((case.Mr, wl.Cin), dtype=s["x_r"].dtype, device="cuda") for s in sets]
 
             def lib_lowrank_step(i):
-                s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
-                torch.matmul(gyr, s["w"], out=lr_out[i % n_sets])
-                torch.matmul(gyr.t(), xr)
+                s = sets[i % n_sets]
+                torch.matmul(s["gy_r"], s["w"], out=lr_out[i % n_sets])
+                torch.matmul(s["gy_r"].t(), s["x_r"])
 
-            ms_lib_lowrank, _ = timed(lib_lowrank_step, max(20, args.steps // 2), max(5, args.warmup // 2))
+            ms_lib_lowrank = timer.launches(lib_lowrank_step)[0]
 
-    # where the time of a call goes: each part timed by itself, back to back on the launch stream
-    # (the projection loop and the products loop above; here the two products launched alone)
+    # where the time of a call goes: the two products launched alone
     ms_gw = ms_gx = None
     if not seq:
-        def gw_step(i):
-            s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
-            binding.lbp_wht_products(xr, gyr, s["w"], (wl.N, wl.H, wl.W), wl.patch, idx, gW=s["gW"], want_gx=False)
-
-        def gx_step(i):
-            s, (xr, gyr) = sets[i % n_sets], proj_bufs[i % n_sets]
-            binding.lbp_wht_products(xr, gyr, s["w"], (wl.N, wl.H, wl.W), wl.patch, idx, gx=s["gx"], want_gw=False)
-
-        ms_gw, _ = timed(gw_step, max(20, args.steps // 2), max(5, args.warmup // 2))
-        ms_gx, _ = timed(gx_step, max(20, args.steps // 2), max(5, args.warmup // 2))
+        ms_gw = timer.launches(case.step("prod_gw"))[0]
+        ms_gx = timer.launches(case.step("prod_gx"))[0]
 
     if args.calibration_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -264,47 +409,48 @@ def main():
         torch.cuda.synchronize()
 
     flops = lbp_flops(wl, r)
-    Mr = wl.patches * r + wl.N * wl.extra
-    # dominant kernel: the projection launch.  Algorithmic bytes: read gy and x once, write the r/p^2
-    # fraction of each (and the tokens outside the grid as they are).
-    proj_bytes = esz * (wl.tokens + Mr) * (wl.Cout + wl.Cin)
-    proj_gbs = proj_bytes / (ms_proj * 1e-3) / 1e9
+    proj_bytes = case.proj_bytes()
+    proj_gbs = proj_bytes / (med_proj * 1e-3) / 1e9
+    traffic_file = f"wht_project_{wl.name}_hbm_traffic.txt"
     roof_proj = {"bound": "hbm", "kernel": "projection of gy and x (one launch per tensor, token sequences)" if seq
                  else "projection of gy and x (one launch)",
-                "achieved": round(proj_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(proj_gbs / HBM_PEAK_GBS, 4),
-                "traffic": read_traffic(f"wht_project_{wl.name}_hbm_traffic.txt", r, args.order),
-                "algorithmic_bytes": proj_bytes, "avg_launch_us": round(ms_proj * 1e3, 2)}
-    gemm_flops = 2.0 * Mr * wl.Cin * wl.Cout
-    # what the planner launches for the products of this call (tiles, one launch or several)
-    shape = binding.LbpShape(wl.N, wl.H, wl.W, wl.Cin, wl.Cout, binding.LBP_F32 if wl.dtype == "f32" else binding.LBP_BF16,
-                             binding.LBP_F32)
-    plan_text = binding.describe_plan(shape, wl.patch, idx, extra=wl.extra)
-    plan_products = plan_text.split("products: ", 1)[-1].split("; workspace", 1)[0]
+                 "achieved": round(proj_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                 "frac": round(proj_gbs / HBM_PEAK_GBS, 4),
+                 "traffic": read_traffic(traffic_file, r, args.order),
+                 "traffic_source": f"profiles/{traffic_file} (stored rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE reading, not measured in this run)",
+                 "algorithmic_bytes": proj_bytes, "avg_launch_us": round(med_proj * 1e3, 2),
+                 "mean_launch_us": round(mean_proj * 1e3, 2), "single_launch_us": round(b2b_proj * 1e3, 2),
+                 "launches": MIN_LAUNCHES}
+    gemm_flops = case.products_flops() / 2
+    plan_products = case.plan_text().split("products: ", 1)[-1].split("; workspace", 1)[0]
     # the two products (one grouped launch where the planner groups them; with the reverse projection
     # in the epilogue where it can be fused): 2 * M_r * Cin * Cout FLOPs each against the dense bf16
-    # (fp32: vector fp32) peak; timed back to back from projected tensors on the launch stream
+    # (fp32: vector fp32) peak; launched from projected tensors
     roof_prod = None
-    if ms_prod is not None:
+    if med_prod is not None:
         peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else 157.3
-        tf = 2.0 * gemm_flops / (ms_prod * 1e-3) / 1e12
+        tf = 2.0 * gemm_flops / (med_prod * 1e-3) / 1e12
+        traffic_file = f"gemm_products_{wl.name}_hbm_traffic.txt"
         roof_prod = {"bound": "mfma" if wl.dtype == "bf16" else "alu",
                      "kernel": "the two products of a call, g^y W with the reverse projection of Eq. 7 and g^y^T x^ (" + plan_products + ")",
                      "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
-                     "traffic": read_traffic(f"gemm_products_{wl.name}_hbm_traffic.txt", r, args.order),
-                     "algorithmic_flops": 2.0 * gemm_flops, "avg_launch_us": round(ms_prod * 1e3, 2)}
+                     "traffic": read_traffic(traffic_file, r, args.order),
+                     "traffic_source": f"profiles/{traffic_file} (stored rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE reading, not measured in this run)",
+                     "algorithmic_flops": 2.0 * gemm_flops, "avg_launch_us": round(med_prod * 1e3, 2),
+                     "mean_launch_us": round(mean_prod * 1e3, 2), "single_launch_us": round(b2b_prod * 1e3, 2),
+                     "launches": MIN_LAUNCHES}
         # the other candidate bound: operands read once, outputs written once
-        prod_bytes = esz * (Mr * (wl.Cin + wl.Cout) + wl.Cin * wl.Cout + wl.tokens * wl.Cin) + 4 * wl.Cin * wl.Cout
+        prod_bytes = case.products_bytes()
         roof_prod["algorithmic_bytes"] = prod_bytes
-        roof_prod["frac_of_hbm_peak"] = round(prod_bytes / (ms_prod * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        roof_prod["frac_of_hbm_peak"] = round(prod_bytes / (med_prod * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     # `roofline` is the kernel that takes the larger share of a step, `roofline_second` the other
-    if roof_prod is not None and ms_prod > ms_proj:
+    if roof_prod is not None and med_prod > med_proj:
         roofline, roofline_second = roof_prod, roof_proj
     else:
         roofline, roofline_second = roof_proj, roof_prod
     stages = None if seq else {
-        "projection_us": round(ms_proj * 1e3, 2),
-        "products_us": round(ms_prod * 1e3, 2),
+        "projection_us": round(med_proj * 1e3, 2),
+        "products_us": round(med_prod * 1e3, 2),
         "gw_product_alone_us": round(ms_gw * 1e3, 2),
         "gx_product_reverse_projection_alone_us": round(ms_gx * 1e3, 2),
         "gw_product_alone_frac_of_mfma_peak": round(gemm_flops / (ms_gw * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
@@ -314,6 +460,7 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
+        host, grid = case.host, (wl.H, wl.W)
         # bounded sample: as many leading images as keep the oracle's work near 20 GFLOP
         n_s = int(max(1, min(wl.N, round(wl.N * 20e9 / max(flops, 1.0)))))
         sample = {k: (v[:n_s] if k != "w" else v) for k, v in host.items()}
@@ -352,6 +499,36 @@ def main():
         cpu["full_bp_oracle_ms_per_step_scaled_to_full"] = round(t_full * 1e3 * wl.N / n_f, 1)
         cpu["side_samples"] = f"one thread: first {n_1} images, {t_one:.2f} s; exact backward on {threads} threads: first {n_f} images, {t_full:.2f} s"
 
+    config = {"workload": wl.name, "N": wl.N, "grid": [wl.H, wl.W], "extra_tokens": wl.extra, "Cin": wl.Cin,
+              "Cout": wl.Cout, "patch": wl.patch, "r": r, "order": args.order,
+              "cache": "warm" if args.warm_cache else f"cold ({n_sets} rotating buffer sets)"}
+
+    # the table the benchmark spec asks for: every configuration, rank and order
+    sweep = None
+    if not args.no_sweep:
+        del case, sets
+        torch.cuda.empty_cache()
+        sweep, full_us, last = [], {}, None
+        for name, rr, order in sweep_cases(workloads):
+            w2 = workloads.WORKLOADS[name]
+            c = Case(torch, binding, workloads, w2, rr, order, seeded=False)
+            if name not in full_us:
+                full_us[name] = timer.launches(c.step("full"))[0] * 1e3
+            sweep.append(sweep_row(c, timer, full_us[name]))
+            del c
+            if last != name:
+                torch.cuda.empty_cache()
+                last = name
+        if args.sweep_table:
+            with open(args.sweep_table, "w") as f:
+                f.write(f"{'workload':22s} {'r':>3s} {'order':>5s} {'lbp_us':>8s} {'full_us':>8s} {'speedup':>7s} "
+                        f"{'proj_us':>7s} {'hbm':>5s} {'prod_us':>7s} {'peak':>5s}\n")
+                for row in sweep:
+                    pu = "-" if row["prod_us"] is None else f"{row['prod_us']:.1f}"
+                    pf = "-" if row["prod_frac_peak"] is None else f"{row['prod_frac_peak']:.3f}"
+                    f.write(f"{row['workload']:22s} {row['r']:3d} {row['order']:>5s} {row['lbp_us']:8.1f} {row['full_bp_us']:8.1f} "
+                            f"{row['speedup']:7.2f} {row['proj_us']:7.1f} {row['proj_frac_hbm']:5.3f} {pu:>7s} {pf:>5s}\n")
+
     out = {
         "metric": "lbp_wht_linear_backward_tflops",
         "value": round(flops / (ms_lbp * 1e-3) / 1e12, 3),
@@ -365,10 +542,11 @@ def main():
         "vs_baseline": None,
         "dtype": wl.dtype,
         "data": "synthetic",
-        "config": {"workload": wl.name, "N": wl.N, "grid": [wl.H, wl.W], "extra_tokens": wl.extra, "Cin": wl.Cin,
-                   "Cout": wl.Cout,
-                   "patch": wl.patch, "r": r, "order": args.order,
-                   "cache": "warm" if args.warm_cache else f"cold ({n_sets} rotating buffer sets)"},
+        "config": config,
+        "timing": f"ms_per_step: exactly --steps steps between two events after --warmup steps; every other figure: median over "
+                  f"{MIN_LAUNCHES // BATCH} batches of {BATCH} back-to-back launches, each batch between its own pair of events",
+        "ms_per_step_median": round(med_lbp, 5),
+        "ms_per_step_single_launches": round(b2b_lbp, 5),
         "lbp_flops_per_step": flops,
         "bp_equivalent_tflops": round(full_bp_flops(wl) / (ms_lbp * 1e-3) / 1e12, 3),
         "full_bp_ms": round(ms_full, 5),
@@ -378,7 +556,7 @@ def main():
         "speedup_vs_library_gemm_full_bp": None if ms_lib is None else round(ms_lib / ms_lbp, 3),
         "best_of_both_full_bp_ms": None if ms_best_full is None else round(ms_best_full, 5),
         "speedup_vs_best_of_both_full_bp": None if ms_best_full is None else round(ms_best_full / ms_lbp, 3),
-        "full_bp_products_alone_ms": None if ms_best_full is None else {k: round(v, 5) for k, v in full_parts.items()},
+        "full_bp_products_alone_ms": None if full_parts is None else {k: round(v, 5) for k, v in full_parts.items()},
         "library_gemm_lowrank_products_ms": None if ms_lib_lowrank is None else round(ms_lib_lowrank, 5),
         "preprojected_x_ms_per_step": round(ms_pre, 5),
         "preprojected_x_speedup_vs_full_bp": round(ms_full / ms_pre, 3),
@@ -388,6 +566,7 @@ def main():
         "stages": stages,
         "roofline": roofline,
         "roofline_second": roofline_second,
+        "sweep": sweep,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

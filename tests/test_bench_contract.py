@@ -50,5 +50,19 @@ def test_one_json_line_with_the_agreed_keys():
         assert key in roof, key
     assert roof["bound"] in ("hbm", "mfma", "alu")
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
+    # measurement protocol: medians over at least 100 launches whatever --steps says, so the parts
+    # of a call cannot exceed the whole
+    st = j["stages"]
+    assert st["projection_us"] + st["products_us"] <= 1.1 * j["ms_per_step"] * 1e3, (st, j["ms_per_step"])
+    assert roof["launches"] >= 100 and abs(roof["avg_launch_us"] - roof["mean_launch_us"]) <= 0.1 * roof["avg_launch_us"]
+    # the table of every configuration, rank and order
+    rows = {(r["workload"], r["r"], r["order"]) for r in j["sweep"]}
+    sys.path.insert(0, ROOT)
+    import bench
+    from paper_2309_15275_amd import workloads
+    assert rows == set(bench.sweep_cases(workloads)) and len(rows) == 23
+    for row in j["sweep"]:
+        assert row["lbp_us"] > 0 and row["full_bp_us"] > 0 and abs(row["speedup"] - row["full_bp_us"] / row["lbp_us"]) < 0.02
+        assert 0 < row["proj_frac_hbm"] < 1
     cpu = j["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["sample"]
