@@ -102,6 +102,24 @@ hipError_t prepare(const GemmArgs &a, int *tile_out, mfma::Params *out, int *lp_
         p.extra = a.extra > 0 ? a.extra : 1;
     }
     p.tiles_m = (a.M + p.bm_step - 1) / p.bm_step;
+    // The tiles of one XCD (T / 8 of them) as an xcd_a x xcd_b block of the output: the block shape
+    // whose strips of A and B together are the fewest bytes for that XCD's L2 to fetch.
+    p.xcd_a = p.xcd_b = 0;
+    const int T = p.tiles_m * p.tiles_n;
+    if (T % 8 == 0) {
+        double best = 1e300;
+        for (int xa = 1; xa <= p.tiles_m; ++xa) {
+            if ((T / 8) % xa || p.tiles_m % xa) continue;
+            const int xb = T / 8 / xa;
+            if (xb > p.tiles_n || p.tiles_n % xb) continue;
+            const double bytes = (double)xa * p.bm_step + (double)xb * t.bn;      // times K * 2 bytes
+            if (bytes < best) {
+                best = bytes;
+                p.xcd_a = xa;
+                p.xcd_b = xb;
+            }
+        }
+    }
     *tile_out = tile;
     *out = p;
     *lp_out = lp;

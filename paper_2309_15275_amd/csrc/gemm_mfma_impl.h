@@ -49,6 +49,7 @@ struct Params {
     int k_per_split;      // multiple of BK
     int bm_step;          // rows of the output one tile advances by (BM, or a multiple of r below BM)
     int tiles_m, tiles_n;
+    int xcd_a, xcd_b;     // tiles of one XCD form an xcd_a x xcd_b block of the output (0: plain numbering)
     void *C;
     float scale;
     // fused reverse projection
@@ -62,6 +63,19 @@ struct Params {
     int mfma_epilogue;    // 1: the selection cannot be pooled, Eq. 7 runs on the matrix cores in the epilogue
     int store_bf16;       // EPI_PLAIN: 1 stores bf16, 0 stores fp32 (slice by slice)
 };
+
+// Scheduling hint for one sub-step of the main loop: N matrix instructions with R LDS reads spread
+// evenly between them (the arguments of the builtin must be constants, hence the recursion).
+template <int I, int N, int R>
+__device__ __forceinline__ void interleave_mfma_with_lds_reads()
+{
+    if constexpr (I < N) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // one matrix instruction
+        constexpr int share = (R * (I + 1)) / N - (R * I) / N;
+        if constexpr (share > 0) __builtin_amdgcn_sched_group_barrier(0x100, share, 0);      // its share of the LDS reads
+        interleave_mfma_with_lds_reads<I + 1, N, R>();
+    }
+}
 
 // Reverse projection of one tile held in LDS as fp32 ct[row][cts]; rows are (patch, basis).
 template <int LP, int MH, int MW, int BN, int NT>
@@ -163,11 +177,24 @@ __device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, co
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave - wm * WGN;
 
-    // XCD-aware tile numbering: workgroup ids go round-robin over the 8 XCDs
-    const int T = p.tiles_m * p.tiles_n;
-    int t = tile_id;
-    if ((T & 7) == 0) t = (t & 7) * (T >> 3) + (t >> 3);
-    const int tm = t / p.tiles_n, tn = t - tm * p.tiles_n;
+    // XCD-aware tile numbering: workgroup ids go round-robin over the 8 XCDs, each of which has an
+    // L2 of its own; the tiles of one XCD form an xcd_a x xcd_b block of the output, so that they
+    // share xcd_a strips of A and xcd_b strips of B (chosen on the host to make that sum smallest)
+    int tm, tn;
+    if (p.xcd_a > 0) {
+        const int x = tile_id & 7, i = tile_id >> 3;
+        const int bn = p.tiles_n / p.xcd_b;           // blocks along n
+        const int xm = x / bn, xn = x - xm * bn;
+        const int im = i / p.xcd_b, in = i - im * p.xcd_b;
+        tm = xm * p.xcd_a + im;
+        tn = xn * p.xcd_b + in;
+    } else {
+        const int T = p.tiles_m * p.tiles_n;          // no such block: a contiguous run of tiles per XCD
+        int t = tile_id;
+        if ((T & 7) == 0) t = (t & 7) * (T >> 3) + (t >> 3);
+        tm = t / p.tiles_n;
+        tn = t - tm * p.tiles_n;
+    }
     const int m0 = tm * p.bm_step, n0 = tn * BN;
     const int kbeg = slice * p.k_per_split;
     const int kend = min(p.K, kbeg + p.k_per_split);
@@ -260,33 +287,63 @@ __device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, co
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    auto multiply = [&](const unsigned char *s) {
+    // One 16-deep sub-step of fragments: TM of A and TN of B, 8 reduction values per lane each.
+    auto load_frags = [&](const unsigned char *s, int ks, bf16x8_t (&a)[TM], bf16x8_t (&b)[TN]) {
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t a[TM], b[TN];
-#pragma unroll
-            for (int mi = 0; mi < TM; ++mi) {
-                if (A_KFAST) {
-                    a[mi] = *reinterpret_cast<const bf16x8_t *>(s + a_off[mi] + ks * 32);
-                } else {
-                    const unsigned char *q = s + a_off[mi] + ks * 16 * SA;
-                    i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q));
-                    i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q + 4 * SA));
-                    a[mi] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                }
-            }
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni) {
-                const unsigned char *q = s + b_off[ni] + ks * 16 * SB;
+        for (int mi = 0; mi < TM; ++mi) {
+            if (A_KFAST) {
+                a[mi] = *reinterpret_cast<const bf16x8_t *>(s + a_off[mi] + ks * 32);
+            } else {
+                const unsigned char *q = s + a_off[mi] + ks * 16 * SA;
                 i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q));
-                i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q + 4 * SB));
-                b[ni] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q + 4 * SA));
+                a[mi] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
+        }
 #pragma unroll
-            for (int mi = 0; mi < TM; ++mi)
+        for (int ni = 0; ni < TN; ++ni) {
+            const unsigned char *q = s + b_off[ni] + ks * 16 * SB;
+            i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q));
+            i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, q + 4 * SB));
+            b[ni] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    };
+    // PIPELINED: the fragments of sub-step ks+1 are requested before the matrix instructions of
+    // sub-step ks are issued, into a second register set, and the scheduler is told to spread those
+    // LDS reads between the matrix instructions, so that a wavefront keeps the matrix cores and the
+    // LDS pipe busy at the same time by itself.  That pays where a SIMD holds one wavefront of the
+    // workgroup (4-wavefront tiles: +8 % on the 128 x 128 weight-gradient product) and on the 256-row
+    // tiles with 64 x 64 wavefront tiles (+2-5 %); with two wavefronts per SIMD and small wavefront
+    // tiles the other wavefront already fills the gaps and the second register set only costs
+    // (128 x 128 and 64 x 128 with 8 wavefronts: -1 to -6 %), and 256 x 256 has no registers left for it.
+    constexpr bool PIPELINED = (WGM * WGN == 4) || (BM == 256 && BN < 256);
+    constexpr int DS_READS = TM * (A_KFAST ? 1 : 2) + TN * 2;       // LDS read instructions per sub-step
+    constexpr int MFMAS = TM * TN;
+    auto multiply = [&](const unsigned char *s) {
+        if constexpr (PIPELINED) {
+            bf16x8_t a[2][TM], b[2][TN];
+            load_frags(s, 0, a[0], b[0]);
 #pragma unroll
-                for (int ni = 0; ni < TN; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                if (ks + 1 < BK / 16) load_frags(s, ks + 1, a[(ks + 1) & 1], b[(ks + 1) & 1]);
+#pragma unroll
+                for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < TN; ++ni)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][mi], b[ks & 1][ni], acc[mi][ni], 0, 0, 0);
+                if (ks + 1 < BK / 16) interleave_mfma_with_lds_reads<0, MFMAS, DS_READS>();
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                bf16x8_t a[TM], b[TN];
+                load_frags(s, ks, a, b);
+#pragma unroll
+                for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < TN; ++ni)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+            }
         }
     };
 
