@@ -244,14 +244,9 @@ class Case:
                          (p["x_r"], p["gy"], p["w"], sh, wl.extra, patch, idx, r, p["gx"], p["gW"], st))]
             return [(lib.lbp_wht_backward_preprojected, (p["x_r"], p["gy"], p["w"], sh, patch, idx, r, p["gx"], p["gW"], st))]
         if kind == "proj":
-            if self.seq:      # no two-tensor entry point for sequences: one projection call per tensor
-                return [(lib.lbp_wht_project_tokens, (p[a], wl.N, wl.H, wl.W, wl.extra, c, dt, patch, idx, r, p[b], st))
-                        for a, b, c in (("x", "x_r", wl.Cin), ("gy", "gy_r", wl.Cout))]
-            return [(lib.lbp_wht_project_pair, (p["x"], p["gy"], sh, patch, idx, r, p["x_r"], p["gy_r"], st))]
-        if self.seq:
-            return []         # lbp_wht_products takes grids only
+            return [(lib.lbp_wht_project_pair_tokens, (p["x"], p["gy"], sh, wl.extra, patch, idx, r, p["x_r"], p["gy_r"], st))]
         gx, gW = (none if kind == "prod_gw" else p["gx"]), (none if kind == "prod_gx" else p["gW"])
-        return [(lib.lbp_wht_products, (p["x_r"], p["gy_r"], p["w"], sh, patch, idx, r, gx, gW, st))]
+        return [(lib.lbp_wht_products_tokens, (p["x_r"], p["gy_r"], p["w"], sh, wl.extra, patch, idx, r, gx, gW, st))]
 
     def run(self, kind, i):
         for fn, a in self.calls[kind][i % self.n_sets]:
@@ -295,10 +290,9 @@ def sweep_row(case, timer, full_us):
            "full_bp_us": round(full_us, 1), "speedup": round(full_us / lbp, 2), "proj_us": round(proj, 1),
            "proj_frac_hbm": round(case.proj_bytes() / (proj * 1e-6) / 1e9 / HBM_PEAK_GBS, 3),
            "prod_us": None, "prod_frac_peak": None}
-    if not case.seq:
-        prod = timer.launches(case.step("prod"))[0] * 1e3
-        row["prod_us"] = round(prod, 1)
-        row["prod_frac_peak"] = round(case.products_flops() / (prod * 1e-6) / 1e12 / peak, 3)
+    prod = timer.launches(case.step("prod"))[0] * 1e3
+    row["prod_us"] = round(prod, 1)
+    row["prod_frac_peak"] = round(case.products_flops() / (prod * 1e-6) / 1e12 / peak, 3)
     return row
 
 
@@ -357,9 +351,7 @@ def main():
     ms_pre = timer.launches(case.step("pre"))[0]
     # the two kernels of a call, each by itself on the launch stream (same rotation of buffers)
     med_proj, mean_proj, b2b_proj = timer.launches(case.step("proj"))
-    med_prod = mean_prod = b2b_prod = None
-    if not seq:
-        med_prod, mean_prod, b2b_prod = timer.launches(case.step("prod"))
+    med_prod, mean_prod, b2b_prod = timer.launches(case.step("prod"))
     ms_full = timer.launches(case.step("full"))[0]
     ms_lib = ms_lib_lowrank = ms_best_full = full_parts = None
     if not args.no_library_gemm:
@@ -384,23 +376,20 @@ def main():
                       "library_gx_ms": timer.launches(lib_gx)[0], "library_gw_ms": timer.launches(lib_gw)[0]}
         ms_best_full = min(full_parts["own_gx_ms"], full_parts["library_gx_ms"]) + \
             min(full_parts["own_gw_ms"], full_parts["library_gw_ms"])
-        if not seq:
-            # the two LOW-RANK products through the vendor GEMM library, from the projected tensors
-            # (no reverse projection, no 1/p^2): what a library call costs on shapes this small
-            lr_out = [torch.empty((case.Mr, wl.Cin), dtype=s["x_r"].dtype, device="cuda") for s in sets]
+        # the two LOW-RANK products through the vendor GEMM library, from the projected tensors
+        # (no reverse projection, no 1/p^2): what a library call costs on shapes this small
+        lr_out = [torch.empty((case.Mr, wl.Cin), dtype=s["x_r"].dtype, device="cuda") for s in sets]
 
-            def lib_lowrank_step(i):
-                s = sets[i % n_sets]
-                torch.matmul(s["gy_r"], s["w"], out=lr_out[i % n_sets])
-                torch.matmul(s["gy_r"].t(), s["x_r"])
+        def lib_lowrank_step(i):
+            s = sets[i % n_sets]
+            torch.matmul(s["gy_r"], s["w"], out=lr_out[i % n_sets])
+            torch.matmul(s["gy_r"].t(), s["x_r"])
 
-            ms_lib_lowrank = timer.launches(lib_lowrank_step)[0]
+        ms_lib_lowrank = timer.launches(lib_lowrank_step)[0]
 
     # where the time of a call goes: the two products launched alone
-    ms_gw = ms_gx = None
-    if not seq:
-        ms_gw = timer.launches(case.step("prod_gw"))[0]
-        ms_gx = timer.launches(case.step("prod_gx"))[0]
+    ms_gw = timer.launches(case.step("prod_gw"))[0]
+    ms_gx = timer.launches(case.step("prod_gx"))[0]
 
     if args.calibration_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -412,8 +401,7 @@ def main():
     proj_bytes = case.proj_bytes()
     proj_gbs = proj_bytes / (med_proj * 1e-3) / 1e9
     traffic_file = f"wht_project_{wl.name}_hbm_traffic.txt"
-    roof_proj = {"bound": "hbm", "kernel": "projection of gy and x (one launch per tensor, token sequences)" if seq
-                 else "projection of gy and x (one launch)",
+    roof_proj = {"bound": "hbm", "kernel": "projection of gy and x (one launch)",
                  "achieved": round(proj_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                  "frac": round(proj_gbs / HBM_PEAK_GBS, 4),
                  "traffic": read_traffic(traffic_file, r, args.order),
@@ -426,29 +414,27 @@ def main():
     # the two products (one grouped launch where the planner groups them; with the reverse projection
     # in the epilogue where it can be fused): 2 * M_r * Cin * Cout FLOPs each against the dense bf16
     # (fp32: vector fp32) peak; launched from projected tensors
-    roof_prod = None
-    if med_prod is not None:
-        peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else 157.3
-        tf = 2.0 * gemm_flops / (med_prod * 1e-3) / 1e12
-        traffic_file = f"gemm_products_{wl.name}_hbm_traffic.txt"
-        roof_prod = {"bound": "mfma" if wl.dtype == "bf16" else "alu",
-                     "kernel": "the two products of a call, g^y W with the reverse projection of Eq. 7 and g^y^T x^ (" + plan_products + ")",
-                     "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
-                     "traffic": read_traffic(traffic_file, r, args.order),
-                     "traffic_source": f"profiles/{traffic_file} (stored rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE reading, not measured in this run)",
-                     "algorithmic_flops": 2.0 * gemm_flops, "avg_launch_us": round(med_prod * 1e3, 2),
-                     "mean_launch_us": round(mean_prod * 1e3, 2), "single_launch_us": round(b2b_prod * 1e3, 2),
-                     "launches": MIN_LAUNCHES}
-        # the other candidate bound: operands read once, outputs written once
-        prod_bytes = case.products_bytes()
-        roof_prod["algorithmic_bytes"] = prod_bytes
-        roof_prod["frac_of_hbm_peak"] = round(prod_bytes / (med_prod * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else 157.3
+    tf = 2.0 * gemm_flops / (med_prod * 1e-3) / 1e12
+    traffic_file = f"gemm_products_{wl.name}_hbm_traffic.txt"
+    roof_prod = {"bound": "mfma" if wl.dtype == "bf16" else "alu",
+                 "kernel": "the two products of a call, g^y W with the reverse projection of Eq. 7 and g^y^T x^ (" + plan_products + ")",
+                 "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
+                 "traffic": read_traffic(traffic_file, r, args.order),
+                 "traffic_source": f"profiles/{traffic_file} (stored rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE reading, not measured in this run)",
+                 "algorithmic_flops": 2.0 * gemm_flops, "avg_launch_us": round(med_prod * 1e3, 2),
+                 "mean_launch_us": round(mean_prod * 1e3, 2), "single_launch_us": round(b2b_prod * 1e3, 2),
+                 "launches": MIN_LAUNCHES}
+    # the other candidate bound: operands read once, outputs written once
+    prod_bytes = case.products_bytes()
+    roof_prod["algorithmic_bytes"] = prod_bytes
+    roof_prod["frac_of_hbm_peak"] = round(prod_bytes / (med_prod * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     # `roofline` is the kernel that takes the larger share of a step, `roofline_second` the other
-    if roof_prod is not None and med_prod > med_proj:
+    if med_prod > med_proj:
         roofline, roofline_second = roof_prod, roof_proj
     else:
         roofline, roofline_second = roof_proj, roof_prod
-    stages = None if seq else {
+    stages = {
         "projection_us": round(med_proj * 1e3, 2),
         "products_us": round(med_prod * 1e3, 2),
         "gw_product_alone_us": round(ms_gw * 1e3, 2),

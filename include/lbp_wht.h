@@ -188,6 +188,19 @@ int lbp_wht_backward_tokens_preprojected(const void *x_r, const void *gy, const 
                                          void *stream);
 /* lbp_wht_energy on such sequences: the spectrum of the grid tokens; the extra tokens have no
  * coefficients and are skipped.  Same workspace as lbp_wht_energy. */
+/*
+ * The first two statements of Algorithm 1 for token sequences, both tensors in ONE launch, and
+ * statements 3-6 from their results (lbp_wht_project_pair / lbp_wht_products with `extra` tokens
+ * per image in front of the grid).  x_r is [P*r + N*extra][Cin], gy_r [P*r + N*extra][Cout]: the
+ * coefficient rows, then the tokens outside the grid image by image -- x's as they are, g_y's
+ * multiplied by patch^2 (exact; the 1/patch^2 of both products removes it), which is the form
+ * lbp_wht_products_tokens expects.  lbp_wht_products_tokens on these gives the bits of
+ * lbp_wht_backward_tokens.
+ */
+int lbp_wht_project_pair_tokens(const void *x, const void *gy, const lbp_shape_t *shape, int extra, int patch,
+                                const int32_t *basis_idx, int r, void *x_r, void *gy_r, void *stream);
+int lbp_wht_products_tokens(const void *x_r, const void *gy_r, const void *W, const lbp_shape_t *shape, int extra,
+                            int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream);
 int lbp_wht_energy_tokens(const void *in, int N, int H, int W, int extra, int C, int dtype, int patch,
                           double *energy, void *stream);
 /* Workspace of the backward calls above (lbp_wht_workspace_bytes with `extra` tokens per image). */

@@ -21,7 +21,8 @@ EXPORTS = ("lbp_wht_select_bases", "lbp_wht_select_lhe", "lbp_wht_energy", "lbp_
            "lbp_wht_project_pair", "lbp_wht_unproject", "lbp_wht_workspace_bytes", "lbp_set_workspace",
            "lbp_release_workspace", "lbp_strerror", "lbp_last_hip_error", "lbp_version",
            "lbp_wht_backward_tokens", "lbp_wht_project_tokens", "lbp_wht_backward_tokens_preprojected",
-           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products", "lbp_wht_energy_tokens", "lbp_wht_describe_plan", "lbp_wht_backward_static", "lbp_set_option")
+           "lbp_wht_workspace_bytes_tokens", "lbp_wht_products", "lbp_wht_energy_tokens", "lbp_wht_describe_plan", "lbp_wht_backward_static", "lbp_set_option",
+           "lbp_wht_project_pair_tokens", "lbp_wht_products_tokens")
 
 
 class LbpShape(ctypes.Structure):
@@ -69,6 +70,8 @@ def load():
     lib.lbp_wht_project.argtypes = [vp] + [ctypes.c_int] * 6 + [i32p, ctypes.c_int, vp, vp]
     lib.lbp_wht_unproject.argtypes = [vp] + [ctypes.c_int] * 6 + [i32p, ctypes.c_int, vp, vp]
     lib.lbp_wht_project_pair.argtypes = [vp, vp, shp, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.lbp_wht_project_pair_tokens.argtypes = [vp, vp, shp, ctypes.c_int, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
+    lib.lbp_wht_products_tokens.argtypes = [vp, vp, vp, shp, ctypes.c_int, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
     lib.lbp_wht_backward_tokens.argtypes = [vp, vp, vp, shp, ctypes.c_int, ctypes.c_int, i32p, ctypes.c_int, vp, vp, vp]
     lib.lbp_wht_backward_tokens_preprojected.argtypes = lib.lbp_wht_backward_tokens.argtypes
     lib.lbp_wht_project_tokens.argtypes = [vp] + [ctypes.c_int] * 7 + [i32p, ctypes.c_int, vp, vp]
@@ -322,6 +325,53 @@ def wht_project_tokens(t, grid, patch, basis_idx, out=None, stream=None):
         _check(load().lbp_wht_project_tokens(_dev_tensor(t, "t"), N, H, W, extra, C, _DTYPES[t.dtype], int(patch),
                                              idx, r, _dev_tensor(out, "out", t.dtype), _stream_ptr(stream)))
     return out
+
+
+def wht_project_pair_tokens(x, gy, grid, patch, basis_idx, x_r=None, gy_r=None, stream=None):
+    """Both projections of token sequences x [N,T,Cin], gy [N,T,Cout] in one launch; the T - H*W leading
+    tokens of every image follow the coefficient rows (gy's times patch^2).  Returns (x_r, gy_r)."""
+    N, T, Cin = x.shape
+    Cout = gy.shape[-1]
+    H, W = grid
+    extra = T - H * W
+    if extra < 0 or tuple(gy.shape[:2]) != (N, T):
+        raise ValueError("x and gy must be [N, extra + H*W, C]")
+    idx, r = _idx_array(basis_idx)
+    rows = patch_count(N, H, W, patch) * r + N * extra
+    if x_r is None:
+        x_r = torch.empty((rows, Cin), dtype=x.dtype, device=x.device)
+    if gy_r is None:
+        gy_r = torch.empty((rows, Cout), dtype=x.dtype, device=x.device)
+    shape = LbpShape(N, H, W, Cin, Cout, _DTYPES[x.dtype], LBP_F32)
+    with torch.cuda.device(x.device):
+        _check(load().lbp_wht_project_pair_tokens(_dev_tensor(x, "x"), _dev_tensor(gy, "gy", x.dtype), ctypes.byref(shape),
+                                                  extra, int(patch), idx, r, _dev_tensor(x_r, "x_r", x.dtype),
+                                                  _dev_tensor(gy_r, "gy_r", x.dtype), _stream_ptr(stream)))
+    return x_r, gy_r
+
+
+def lbp_wht_products_tokens(x_r, gy_r, w, grid_shape, extra, patch, basis_idx, gx=None, gW=None, want_gx=True,
+                            want_gw=True, gw_dtype=torch.float32, stream=None):
+    """Statements 3-6 of Algorithm 1 from wht_project_pair_tokens' tensors; grid_shape = (N, H, W).
+    Returns (gx [N, extra + H*W, Cin], gW)."""
+    N, H, W = grid_shape
+    Cout, Cin = w.shape
+    idx, r = _idx_array(basis_idx)
+    rows = patch_count(N, H, W, patch) * r + N * extra
+    if tuple(x_r.shape) != (rows, Cin) or tuple(gy_r.shape) != (rows, Cout):
+        raise ValueError("shapes must be x_r[P*r + N*extra,Cin], gy_r[P*r + N*extra,Cout], w[Cout,Cin]")
+    shape = LbpShape(N, H, W, Cin, Cout, _DTYPES[gy_r.dtype], _DTYPES[gw_dtype])
+    if want_gx and gx is None:
+        gx = torch.empty((N, extra + H * W, Cin), dtype=gy_r.dtype, device=gy_r.device)
+    if want_gw and gW is None:
+        gW = torch.empty(w.shape, dtype=gw_dtype, device=w.device)
+    with torch.cuda.device(gy_r.device):
+        _check(load().lbp_wht_products_tokens(
+            _dev_tensor(x_r, "x_r", gy_r.dtype), _dev_tensor(gy_r, "gy_r"), _dev_tensor(w, "w", gy_r.dtype),
+            ctypes.byref(shape), int(extra), int(patch), idx, r,
+            _dev_tensor(gx, "gx", gy_r.dtype) if gx is not None else None,
+            _dev_tensor(gW, "gW", gw_dtype) if gW is not None else None, _stream_ptr(stream)))
+    return gx, gW
 
 
 def lbp_wht_backward_tokens_preprojected(x_r, gy, w, grid, patch, basis_idx, gx=None, gW=None, want_gx=True,

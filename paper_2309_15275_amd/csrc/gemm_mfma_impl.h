@@ -453,7 +453,16 @@ __device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, co
                                               (ch * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2;
                     i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, qd));
                     i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LBP_LDS_PTR(i16x4_t, qd + 4 * S_CO));
-                    bf16x8_t b = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                    i16x8_t bv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    // a last step that is not full reads rows of the next patch (or the zero rows behind
+                    // the tile): they must not reach the product even times a zero sign, or a coefficient
+                    // that is not finite there would turn this patch's tokens into NaN
+                    if ((ks + 1) * 16 > p.r) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (ks * 16 + kg * 8 + e >= p.r) bv[e] = 0;
+                    }
+                    bf16x8_t b = __builtin_bit_cast(bf16x8_t, bv);
 #pragma unroll
                     for (int m = 0; m < MTW; ++m)      // rows of the product = channels, columns = tokens
                         o[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, sgn[m][ks], o[m], 0, 0, 0);

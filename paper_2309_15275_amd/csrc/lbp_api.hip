@@ -320,10 +320,17 @@ int lbp_wht_project_tokens(const void *in, int N, int H, int W, int extra, int C
 int lbp_wht_project_pair(const void *x, const void *gy, const lbp_shape_t *shape, int patch,
                          const int32_t *basis_idx, int r, void *x_r, void *gy_r, void *stream)
 {
+    return lbp_wht_project_pair_tokens(x, gy, shape, 0, patch, basis_idx, r, x_r, gy_r, stream);
+}
+
+int lbp_wht_project_pair_tokens(const void *x, const void *gy, const lbp_shape_t *shape, int extra, int patch,
+                                const int32_t *basis_idx, int r, void *x_r, void *gy_r, void *stream)
+{
     if (!x || !gy || !x_r || !gy_r || !basis_idx || !shape) return LBP_ERR_NULL;
     int rc = lbp::validate_shape(shape, patch);
     if (rc) return rc;
     if (lbp::patch_log2(patch) < 0) return LBP_ERR_PATCH;
+    if (!tokens_ok(shape, extra)) return LBP_ERR_SHAPE;
     lbp::BasisPlan plan;
     rc = lbp::make_basis_plan(patch, basis_idx, r, &plan);
     if (rc) return rc;
@@ -331,7 +338,8 @@ int lbp_wht_project_pair(const void *x, const void *gy, const lbp_shape_t *shape
     rc = lbp::validate_alignment(ptrs, 4);
     if (rc) return rc;
     const size_t esz = lbp::dtype_size(shape->dtype);
-    const size_t M = (size_t)shape->N * shape->H * shape->W, Mr = (size_t)lbp::patch_count(shape->N, shape->H, shape->W, patch) * r;
+    const size_t M = (size_t)shape->N * ((size_t)shape->H * shape->W + extra);
+    const size_t Mr = (size_t)lbp::patch_count(shape->N, shape->H, shape->W, patch) * r + (size_t)shape->N * extra;
     const void *bufs[4] = {x, gy, x_r, gy_r};
     const size_t bytes[4] = {M * shape->Cin * esz, M * shape->Cout * esz, Mr * shape->Cin * esz,
                              Mr * shape->Cout * esz};
@@ -342,8 +350,11 @@ int lbp_wht_project_pair(const void *x, const void *gy, const lbp_shape_t *shape
     DeviceState *st;
     rc = current_device(&dev, &st);
     if (rc) return rc;
+    // tokens outside the grid follow the coefficient rows: x's as they are, g_y's times patch^2 (exact),
+    // which the 1/patch^2 of both products takes away again
     LBP_HIP(lbp::launch_project_pair(gy, gy_r, shape->Cout, x, x_r, shape->Cin, shape->N, shape->H, shape->W,
-                                     shape->dtype, plan, wht_path_option(), (hipStream_t)stream));
+                                     shape->dtype, plan, wht_path_option(), (hipStream_t)stream, extra,
+                                     (float)(patch * patch), 1.0f));
     return LBP_OK;
 }
 
@@ -447,7 +458,7 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
     // rows of the projected tensors: (patch, basis) pairs first, then the tokens outside the grid
     const long Mq = lbp::patch_count(shape->N, shape->H, shape->W, patch) * r;
     const long Mr = Mq + (long)shape->N * extra;
-    if (gy_projected && (!x_projected || extra != 0)) return LBP_ERR_SHAPE;
+    if (gy_projected && !x_projected) return LBP_ERR_SHAPE;
     rc = validate_buffers(x, gy, W, shape, gx, gW, x_projected ? (size_t)Mr : 0, extra, gy_projected ? (size_t)Mr : 0);
     if (rc) return rc;
 
@@ -629,6 +640,12 @@ int lbp_wht_products(const void *x_r, const void *gy_r, const void *W, const lbp
                      const int32_t *basis_idx, int r, void *gx, void *gW, void *stream)
 {
     return backward_impl(x_r, gy_r, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr, true, 0, true);
+}
+
+int lbp_wht_products_tokens(const void *x_r, const void *gy_r, const void *W, const lbp_shape_t *shape, int extra,
+                            int patch, const int32_t *basis_idx, int r, void *gx, void *gW, void *stream)
+{
+    return backward_impl(x_r, gy_r, W, shape, patch, basis_idx, r, gx, gW, stream, nullptr, true, extra, true);
 }
 
 int lbp_wht_backward_tokens(const void *x, const void *gy, const void *W, const lbp_shape_t *shape, int extra,

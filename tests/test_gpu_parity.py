@@ -307,6 +307,28 @@ def test_grouped_launch_on_ragged_shapes(case, fuse, tile):
     assert_matches(gW1, gWo, TOL["bf16"], "gW")
 
 
+@pytest.mark.parametrize("fuse", ["1", "0"])
+@pytest.mark.parametrize("r", [8, 21, 36, 64])
+def test_a_non_finite_gradient_stays_inside_its_patch(r, fuse):
+    # g~x of a patch depends on g_y of that patch only (Eq. 6, Eq. 7 are per patch): an infinite g_y in one
+    # patch may make that patch's g~x non-finite, every other token must keep its bits.  (The fused
+    # matrix-core epilogue reads 16 coefficient rows at a time, which at r = 21 or 36 reach into the
+    # next patch's rows.)
+    binding.set_option("LBP_FUSE_UNPROJECT", fuse)
+    wl = small("inf", 3, 16, 24, 136, 264, 8, "bf16", 470 + r)
+    host, dev = device_inputs(wl)
+    idx = oracle.select_bases(8, r, "l1")
+    gx_a, _ = lbp_backward(dev, 8, idx)
+    bad = dev["gy"].clone()
+    bad[1, 8 + 3, 16 + 5, 7] = float("inf")          # image 1, patch row 1, patch column 2
+    gx_b = torch.full_like(dev["x"], float("nan"))
+    binding.lbp_wht_backward(dev["x"], bad, dev["w"], 8, idx, gx=gx_b, want_gw=False)
+    inside = torch.zeros((3, 16, 24), dtype=torch.bool, device="cuda")
+    inside[1, 8:16, 16:24] = True
+    assert not bool(torch.isfinite(gx_b[inside]).all())
+    assert torch.equal(gx_b[~inside].view(torch.int16), gx_a[~inside].view(torch.int16))
+
+
 def test_split_k_partial_sums_feed_the_reverse_projection():
     # few rows, long reduction: the planner splits the input-gradient product over K and the
     # reverse-projection kernel adds the slices up

@@ -90,6 +90,36 @@ def test_projection_kept_from_the_forward_pass_gives_the_same_bits(case, dtype):
     assert torch.equal(a[0].view(bits), b[0].view(bits)) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [0, 1, 2, 3, 5])
+def test_two_tensor_projection_and_products_of_token_sequences(case, dtype):
+    # lbp_wht_project_pair_tokens + lbp_wht_products_tokens are lbp_wht_backward_tokens in two calls
+    wl, extra, host, dev, idx = run_case(case, dtype, 670 + case)
+    grid, pp = (wl.H, wl.W), wl.patch * wl.patch
+    rows = binding.patch_count(wl.N, wl.H, wl.W, wl.patch) * len(idx)
+    x_r = torch.full((rows + wl.N * extra, wl.Cin), float("nan"), dtype=dev["x"].dtype, device="cuda")
+    gy_r = torch.full((rows + wl.N * extra, wl.Cout), float("nan"), dtype=dev["x"].dtype, device="cuda")
+    binding.wht_project_pair_tokens(dev["x"], dev["gy"], grid, wl.patch, idx, x_r=x_r, gy_r=gy_r)
+    tol = 1e-6 if dtype == "f32" else 4e-3
+    for name, t, C, scale in (("x", x_r, wl.Cin, 1.0), ("gy", gy_r, wl.Cout, float(pp))):
+        g = np.ascontiguousarray(host[name][:, extra:]).reshape(wl.N, wl.H, wl.W, C)
+        assert_matches(t[:rows], oracle.project_padded(g, wl.patch, idx), tol, name + " coefficients")
+        # the tokens outside the grid follow, image by image; gy's carry patch^2 (exact)
+        assert torch.equal(t[rows:].view(wl.N, extra, C), dev[name][:, :extra] * scale)
+    # the single-tensor call writes the same bits for x
+    assert torch.equal(x_r, binding.wht_project_tokens(dev["x"], grid, wl.patch, idx))
+    T = extra + wl.H * wl.W
+    gx = torch.full((wl.N, T, wl.Cin), float("nan"), dtype=dev["x"].dtype, device="cuda")
+    gW = torch.full((wl.Cout, wl.Cin), float("nan"), dtype=torch.float32, device="cuda")
+    binding.lbp_wht_products_tokens(x_r, gy_r, dev["w"], (wl.N, wl.H, wl.W), extra, wl.patch, idx, gx=gx, gW=gW)
+    ref = binding.lbp_wht_backward_tokens(dev["x"], dev["gy"], dev["w"], grid, wl.patch, idx)
+    bits = torch.int32 if dtype == "f32" else torch.int16
+    assert torch.equal(gx.view(bits), ref[0].view(bits)) and torch.equal(gW.view(torch.int32), ref[1].view(torch.int32))
+    gx0, gW0 = oracle.lbp_wht_backward_tokens(host["x"], host["gy"], host["w"], grid, wl.patch, idx)
+    assert_matches(gx, gx0, TOL[dtype], "gx")
+    assert_matches(gW, gW0, TOL[dtype], "gW")
+
+
 def test_no_extra_tokens_is_the_grid_call():
     wl, extra, host, dev, idx = run_case(0, "bf16", 660)
     xg = dev["x"][:, extra:].contiguous().view(wl.N, wl.H, wl.W, wl.Cin)

@@ -179,6 +179,26 @@ def test_token_sequence_entry_points_check_their_arguments(lib):
     assert binding.workspace_bytes(sh, 8, 4, extra=-1) == 0
 
 
+def test_token_pair_entry_points_check_their_arguments(lib):
+    sh = binding.LbpShape(2, 14, 14, 64, 128, 1, 0)
+    idx = (ctypes.c_int32 * 4)(0, 1, 8, 9)
+    P = ctypes.c_void_p
+    X, GY, XR, GYR, W_, GX, GW = (0x10000000 + i * 0x1000000 for i in range(7))
+    f = lib.lbp_wht_project_pair_tokens
+    assert f(None, P(GY), ctypes.byref(sh), 1, 8, idx, 4, P(XR), P(GYR), None) == -1
+    assert f(P(X), P(GY), ctypes.byref(sh), -1, 8, idx, 4, P(XR), P(GYR), None) == -2
+    assert f(P(X), P(GY), ctypes.byref(sh), 1, 3, idx, 4, P(XR), P(GYR), None) == -3
+    assert f(P(X), P(GY), ctypes.byref(sh), 1, 8, idx, 65, P(XR), P(GYR), None) == -4
+    assert f(P(X), P(GY), ctypes.byref(sh), 1, 8, idx, 4, P(X + 64), P(GYR), None) == -7
+    assert f(P(X), P(GY), ctypes.byref(sh), 1, 8, idx, 4, P(XR + 4), P(GYR), None) == -8
+    assert f(P(X), P(GY), ctypes.byref(sh), 1, 8, idx, 4, P(XR), P(GYR), None) in (0, -11)
+    g = lib.lbp_wht_products_tokens
+    assert g(P(XR), P(GYR), P(W_), ctypes.byref(sh), 1, 8, idx, 4, None, None, None) == -1
+    assert g(P(XR), P(GYR), P(W_), ctypes.byref(sh), -3, 8, idx, 4, P(GX), P(GW), None) == -2
+    assert g(P(XR), P(GYR), P(W_), ctypes.byref(sh), 1, 8, idx, 4, P(GX), P(XR), None) == -7
+    assert g(P(XR), P(GYR), P(W_), ctypes.byref(sh), 1, 8, idx, 4, P(GX), P(GW), None) in (0, -11)
+
+
 def test_products_entry_point_checks_its_arguments(lib):
     sh = binding.LbpShape(2, 16, 16, 64, 128, 1, 0)
     idx = (ctypes.c_int32 * 4)(0, 1, 8, 9)
