@@ -105,6 +105,15 @@ class Timer:
     def __init__(self, torch):
         self.torch = torch
 
+    def settle(self, step, seconds=0.05):
+        """Untimed launches for `seconds`: clocks and caches reach their steady state before anything is timed."""
+        t0, i = time.perf_counter(), 0
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(10):
+                step(i)
+                i += 1
+            self.torch.cuda.synchronize()
+
     def loop(self, step, steps, warmup):
         """The contract's loop: `warmup` untimed steps, then exactly `steps` between two events."""
         torch = self.torch
@@ -329,8 +338,8 @@ def main():
     case = Case(torch, binding, workloads, wl, r, args.order, seeded=True, warm=args.warm_cache)
     seq, n_sets, sets, idx = case.seq, case.n_sets, case.sets, case.idx
 
-    # per-launch medians first (they also bring clocks and caches to their steady state), then the
-    # contract's loop of exactly --steps steps
+    # medians first, then the contract's loop of exactly --steps steps
+    timer.settle(case.step("lbp"))
     med_lbp, mean_lbp, b2b_lbp = timer.launches(case.step("lbp"))
     ms_lbp, wall_lbp = timer.loop(case.step("lbp"), args.steps, args.warmup)
     # the cache-warm number beside it, labelled: one buffer set over and over

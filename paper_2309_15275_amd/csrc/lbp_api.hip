@@ -204,7 +204,7 @@ int weight_gradient(const void *A, const void *B, int Cout, int Cin, long K, int
 
 extern "C" {
 
-int lbp_version(void) { return 100; }
+int lbp_version(void) { return 200; }
 
 const char *lbp_strerror(int code) { return lbp::status_string(code); }
 
