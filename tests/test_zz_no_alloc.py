@@ -58,3 +58,29 @@ def test_static_scratch_backward_rejects_what_does_not_fit():
     assert e.value.code == -10
     torch.cuda.synchronize()
     assert bool((gx == 3.0).all()) and bool((gW == 3.0).all())      # nothing was launched
+
+
+def test_static_scratch_backward_inside_a_captured_graph():
+    # what the entry point is for: a caller under graph capture.  After one eager call (kernel attributes
+    # set) the call is recorded and replayed with new inputs in the same buffers; every replay must
+    # reproduce the eager lbp_wht_backward bit for bit.
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    wl, host, dev, idx = _case(4, 16, 16, 136, 264, 8, 8, 815)
+    gx, gW = nan_outputs(dev["x"].shape, dev["x"].dtype, dev["w"].shape)
+    binding.lbp_wht_backward_static(dev["x"], dev["gy"], dev["w"], wl.patch, idx, gx, gW)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.lbp_wht_backward_static(dev["x"], dev["gy"], dev["w"], wl.patch, idx, gx, gW)
+    for rep in range(3):
+        with torch.no_grad():
+            dev["gy"].mul_(-0.5 if rep % 2 else 2.0)           # exact in bf16: new inputs, same buffers
+            dev["x"].copy_(dev["x"].roll(1, dims=0))
+        gx.fill_(float("nan"))
+        gW.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        ref_gx, ref_gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], wl.patch, idx)
+        torch.cuda.synchronize()
+        assert torch.equal(gx, ref_gx) and torch.equal(gW, ref_gW), rep
