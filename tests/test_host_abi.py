@@ -301,3 +301,18 @@ def test_reported_workspace_covers_every_plan_on_random_shapes(lib):
                 used = int(t.rsplit("workspace ", 1)[1].split()[0])
                 if cus == 256:      # workspace_bytes plans for the current device, else for 256 units
                     assert used <= need, (N, H, W, Cin, Cout, patch, r, extra, t)
+
+
+def test_the_public_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 on its own (no C++ , no HIP, no torch types)
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "lbp_wht.h"\n'
+                   "int main(void) { lbp_shape_t s = {1, 8, 8, 8, 8, LBP_BF16, LBP_F32}; int32_t idx[4];\n"
+                   "  return lbp_wht_select_bases(8, 4, LBP_ORDER_L1, idx) + (int)s.N - 1 + (int)(LBP_STATIC_SCRATCH_BYTES == 0); }\n")
+    res = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", os.path.join(ROOT, "include"), str(src)],
+                         capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
