@@ -461,7 +461,7 @@ def main():
         sample = {k: (v[:n_s] if k != "w" else v) for k, v in host.items()}
         wl_s = workloads.scaled(wl, N=n_s)
         best = 1e30
-        for _ in range(2):
+        for _ in range(5):
             t0 = time.perf_counter()
             if seq:
                 oracle.lbp_wht_backward_tokens(sample["x"], sample["gy"], sample["w"], grid, wl.patch, np.asarray(idx))
@@ -471,7 +471,7 @@ def main():
         threads = oracle.max_threads()
         cpu = {"value": round(lbp_flops(wl_s, r) / best / 1e12, 6), "unit": "TFLOP/s",
                "cores": threads, "kind": "oracle",
-               "sample": f"first {n_s} of {wl.N} images of the same workload, best of 2 calls, {best:.2f} s each",
+               "sample": f"first {n_s} of {wl.N} images of the same workload, best of 5 calls, {best:.2f} s each",
                "ms_per_step_scaled_to_full": round(best * 1e3 * wl.N / n_s, 1)}
         # beside it: the same oracle call on one thread, and the oracle's exact backward (Eq. 2) on
         # all threads, each on a sample bounded to a few seconds, scaled to the full batch
