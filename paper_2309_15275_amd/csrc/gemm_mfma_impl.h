@@ -159,13 +159,27 @@ struct Smem {
     static constexpr int TOTAL = 2 * STAGE;
 };
 
-// First row and column of output tile `tile_id`, numbered XCD-aware: workgroup ids go round-robin
-// over the 8 XCDs, each of which has an L2 of its own; the tiles of one XCD form an xcd_a x xcd_b
-// block of the output, so that they share xcd_a strips of A and xcd_b strips of B (chosen on the
-// host to make that sum smallest).
-template <int BN>
-__device__ __forceinline__ void tile_origin(const Params &p, const int tile_id, int &m0, int &n0)
+// One workgroup's share of a product: output tile `tile_id` (before the XCD renumbering), split-K
+// slice `slice`; `smem` is the workgroup's dynamic LDS (at least Smem<BM, BN, A_KFAST>::TOTAL bytes).
+template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
+__device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, const int slice, unsigned char *smem)
 {
+    static_assert(PF == 2 || PF == 4, "prefetch depth must be even");
+    using S = Smem<BM, BN, A_KFAST>;
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int SA = S::SA, SB = S::SB, A_BYTES = S::A_BYTES, STAGE = S::STAGE;
+    constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;       // 16-byte chunks per thread per step
+    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile does not divide over the threads");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 tiles");
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave - wm * WGN;
+
+    // XCD-aware tile numbering: workgroup ids go round-robin over the 8 XCDs, each of which has an
+    // L2 of its own; the tiles of one XCD form an xcd_a x xcd_b block of the output, so that they
+    // share xcd_a strips of A and xcd_b strips of B (chosen on the host to make that sum smallest)
     int tm, tn;
     if (p.xcd_a > 0) {
         const int x = tile_id & 7, i = tile_id >> 3;
@@ -181,30 +195,9 @@ __device__ __forceinline__ void tile_origin(const Params &p, const int tile_id, 
         tm = t / p.tiles_n;
         tn = t - tm * p.tiles_n;
     }
-    m0 = tm * p.bm_step;
-    n0 = tn * BN;
-}
-
-// The reduction range [kbeg, kend) of the output tile at (m0, n0), accumulated into `acc` (which
-// is cleared first); `smem` is the workgroup's dynamic LDS (at least Smem<BM, BN, A_KFAST>::TOTAL
-// bytes).  Ends with a barrier: no wavefront reads the operand stages any more.
-template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST>
-__device__ __forceinline__ void gemm_mainloop(const Params &p, const int m0, const int n0, const int kbeg,
-                                              const int kend, unsigned char *smem,
-                                              f32x16_t (&acc)[BM / WGM / 32][BN / WGN / 32])
-{
-    static_assert(PF == 2 || PF == 4, "prefetch depth must be even");
-    using S = Smem<BM, BN, A_KFAST>;
-    constexpr int NT = 64 * WGM * WGN;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int SA = S::SA, SB = S::SB, A_BYTES = S::A_BYTES, STAGE = S::STAGE;
-    constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;       // 16-byte chunks per thread per step
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile does not divide over the threads");
-    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 tiles");
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave - wm * WGN;
+    const int m0 = tm * p.bm_step, n0 = tn * BN;
+    const int kbeg = slice * p.k_per_split;
+    const int kend = min(p.K, kbeg + p.k_per_split);
 
     // ---- per-thread load descriptors (rows / columns clamped into the matrix)
     const unsigned short *ga[A_CH];
@@ -286,6 +279,7 @@ __device__ __forceinline__ void gemm_mainloop(const Params &p, const int m0, con
         b_off[ni] = A_BYTES + (8 * (grp >> 1) + (i16 >> 2)) * SB +
                     (((wn * WN + ni * 32 + 16 * (grp & 1) + 4 * (i16 & 3)) * 2) ^ (S::B_SWZ ? (i16 >> 2) << 6 : 0));
 
+    f32x16_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -392,22 +386,6 @@ __device__ __forceinline__ void gemm_mainloop(const Params &p, const int m0, con
         __syncthreads();
     }
 
-}
-
-// What one workgroup does with the finished accumulators of the tile at (m0, n0): one of the stores,
-// or the fused reverse projection.  `slice` is the split-K slice (fp32 stores only).
-template <int BM, int BN, int WGM, int WGN, bool A_KFAST, int EPI, int LP>
-__device__ __forceinline__ void gemm_epilogue(const Params &p, const int m0, const int n0, const int slice,
-                                              unsigned char *smem, f32x16_t (&acc)[BM / WGM / 32][BN / WGN / 32])
-{
-    using S = Smem<BM, BN, A_KFAST>;
-    constexpr int NT = 64 * WGM * WGN;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int TM = WM / 32, TN = WN / 32;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave - wm * WGN;
-    const int li = lane & 31, kg = lane >> 5, grp = lane >> 4, i16 = lane & 15;
     // accumulator element 4*g4 + e of a 32x32 tile: row 8*g4 + 4*(lane/32) + e, column lane%32
     if constexpr (EPI == EPI_UNPROJECT_MFMA) {
         // Eq. 7 for selections that cannot be pooled (patch 8): per patch, tokens[64][BN] =
@@ -606,20 +584,6 @@ __device__ __forceinline__ void gemm_epilogue(const Params &p, const int m0, con
                     }
             }
     }
-}
-
-// One workgroup's share of a product: output tile `tile_id` (before the XCD renumbering), split-K
-// slice `slice`.
-template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
-__device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, const int slice, unsigned char *smem)
-{
-    int m0, n0;
-    tile_origin<BN>(p, tile_id, m0, n0);
-    const int kbeg = slice * p.k_per_split;
-    const int kend = min(p.K, kbeg + p.k_per_split);
-    f32x16_t acc[BM / WGM / 32][BN / WGN / 32];
-    gemm_mainloop<BM, BN, WGM, WGN, PF, A_KFAST>(p, m0, n0, kbeg, kend, smem, acc);
-    gemm_epilogue<BM, BN, WGM, WGN, A_KFAST, EPI, LP>(p, m0, n0, slice, smem, acc);
 }
 
 template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
