@@ -285,7 +285,8 @@ int lbp_release_workspace(void);
  *   "LBP_GEMM_PATH"       "simple"                          plain cross-check products
  *   "LBP_GEMM_TILE"       "0" .. "7"                        one tile shape for every product
  *   "LBP_FUSE_UNPROJECT"  "0" | "1"                         reverse projection never / always fused where possible
- *   "LBP_GEMM_GROUP"      "0" | "1"                         the two products in separate launches / grouped where possible
+ *   "LBP_GEMM_GROUP"      "0" | "1" | "2"                   the two products in separate launches / grouped where possible /
+ *                                                           grouped with the weight-gradient workgroups always first
  *   "LBP_GX_COEF"         "f32" | "bf16"                    coefficients handed to an unfused reverse projection
  * Returns LBP_ERR_NULL (name is NULL) or LBP_ERR_OPTION (unknown name or value).  No HIP call.
  */

@@ -632,7 +632,8 @@ hipError_t launch_one(const Params &p, int splits, hipStream_t stream)
 // bit-identical to separate launches.
 struct PairParams {
     Params first, second;
-    int blocks_first;
+    int blocks_first, blocks_second;
+    int second_leads;     // 1: the workgroups of `second` have the lower indices (are dispatched first)
 };
 
 template <int WGM, int WGN, int PF, int BM1, int BN1, bool KF1, int EPI1, int LP1, int BM2, int BN2, bool KF2,
@@ -640,7 +641,10 @@ template <int WGM, int WGN, int PF, int BM1, int BN1, bool KF1, int EPI1, int LP
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pair_kernel(PairParams pp)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int b = blockIdx.x;
+    // (both orders keep a tile's workgroup index modulo 8, hence its XCD, a function of its tile id only)
+    const int b = pp.second_leads ? (blockIdx.x < (unsigned)pp.blocks_second ? (int)blockIdx.x + pp.blocks_first
+                                                                             : (int)blockIdx.x - pp.blocks_second)
+                                  : (int)blockIdx.x;
     if (b < pp.blocks_first) {
         const int T = pp.first.tiles_m * pp.first.tiles_n;
         const int z = b / T;
@@ -656,7 +660,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pair_kernel(PairParams pp
 template <int WGM, int WGN, int PF, int BM1, int BN1, bool KF1, int EPI1, int LP1, int BM2, int BN2, bool KF2,
           int EPI2, int LP2>
 hipError_t launch_pair(const Params &first, int splits_first, const Params &second, int splits_second,
-                       hipStream_t stream)
+                       hipStream_t stream, bool second_leads = false)
 {
     constexpr int L1 = Smem<BM1, BN1, KF1>::TOTAL, L2 = Smem<BM2, BN2, KF2>::TOTAL;
     constexpr int LDS = L1 > L2 ? L1 : L2;
@@ -668,7 +672,9 @@ hipError_t launch_pair(const Params &first, int splits_first, const Params &seco
     pp.first = first;
     pp.second = second;
     pp.blocks_first = first.tiles_m * first.tiles_n * splits_first;
-    const unsigned blocks = (unsigned)(pp.blocks_first + second.tiles_m * second.tiles_n * splits_second);
+    pp.blocks_second = second.tiles_m * second.tiles_n * splits_second;
+    pp.second_leads = second_leads ? 1 : 0;
+    const unsigned blocks = (unsigned)(pp.blocks_first + pp.blocks_second);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(64 * WGM * WGN), LDS, stream, pp);
     return hipGetLastError();
 }
@@ -716,9 +722,9 @@ hipError_t mfma_tile_256x192(const mfma::Params &p, bool a_kfast, GemmOut out, i
 // weight-gradient product `w` (A reduction-slow, 128x128 tile with 8 wavefronts, fp32 or bf16 store
 // by w.store_bf16).  hipErrorInvalidValue for a combination that is not instantiated.
 hipError_t mfma_pair_w8(const mfma::Params &x, int bm_x, GemmOut out_x, int splits_x, const mfma::Params &w,
-                        int splits_w, hipStream_t s);
+                        int splits_w, hipStream_t s, bool w_leads = false);
 // The same for 64 x 64 tiles with 4 wavefronts on both products (pooled fused epilogue only).
 hipError_t mfma_pair_64x64(const mfma::Params &x, GemmOut out_x, int splits_x, const mfma::Params &w, int splits_w,
-                           hipStream_t s);
+                           hipStream_t s, bool w_leads = false);
 
 }  // namespace lbp

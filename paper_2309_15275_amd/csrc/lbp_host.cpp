@@ -419,6 +419,7 @@ int apply_option(Options *o, const char *name, const char *value)
     } else if (!std::strcmp(name, "LBP_GEMM_GROUP")) {
         if (reset || is("1")) o->gemm_group = 1;
         else if (is("0")) o->gemm_group = 0;
+        else if (is("2")) o->gemm_group = 2;
         else return LBP_ERR_OPTION;
     } else if (!std::strcmp(name, "LBP_GX_COEF")) {
         if (reset) o->gx_coef = def.gx_coef;

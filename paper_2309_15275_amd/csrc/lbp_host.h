@@ -139,7 +139,7 @@ struct Options {
     int gemm_simple = 0;       // 1: plain cross-check products
     int gemm_tile = -1;        // >= 0: one tile shape for every product
     int fuse_unproject = -1;   // -1 planner, 0 never, 1 wherever the kernel supports the selection
-    int gemm_group = 1;        // 0: the two products of a call in separate launches
+    int gemm_group = 1;        // 0: the two products of a call in separate launches; 2: one launch, weight gradient first
     int gx_coef = 1;           // 1 planner, 0 fp32 slices, 2 bf16 wherever the kernels allow
 };
 // The current switches; the first call reads the LBP_* environment variables, once per process.

@@ -302,6 +302,10 @@ def test_grouped_launch_on_ragged_shapes(case, fuse, tile):
     gx1, gW1 = lbp_backward(dev, patch, idx)
     assert torch.equal(gx0.view(torch.int16), gx1.view(torch.int16))
     assert torch.equal(gW0.view(torch.int32), gW1.view(torch.int32))
+    binding.set_option("LBP_GEMM_GROUP", "2")       # the same launch with the weight-gradient workgroups first
+    gx2, gW2 = lbp_backward(dev, patch, idx)
+    assert torch.equal(gx0.view(torch.int16), gx2.view(torch.int16))
+    assert torch.equal(gW0.view(torch.int32), gW2.view(torch.int32))
     gxo, gWo = oracle.lbp_wht_backward(host["x"], host["gy"], host["w"], patch, idx)
     assert_matches(gx1, gxo, TOL["bf16"], "gx")
     assert_matches(gW1, gWo, TOL["bf16"], "gW")

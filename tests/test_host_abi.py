@@ -256,7 +256,7 @@ def test_option_switches_check_their_arguments(lib):
     assert f(b"LBP_FUSE_UNPROJECT", b"2") == -12 and f(b"LBP_GEMM_GROUP", b"yes") == -12
     for name, values in (("LBP_WHT_PATH", ("generic", "register", "mfma", "auto")), ("LBP_GEMM_PATH", ("simple", "auto")),
                          ("LBP_GEMM_TILE", tuple(str(i) for i in range(8))), ("LBP_FUSE_UNPROJECT", ("0", "1")),
-                         ("LBP_GEMM_GROUP", ("0", "1")), ("LBP_GX_COEF", ("f32", "bf16"))):
+                         ("LBP_GEMM_GROUP", ("0", "1", "2")), ("LBP_GX_COEF", ("f32", "bf16"))):
         for v in values:
             assert f(name.encode(), v.encode()) == 0, (name, v)
         assert f(name.encode(), None) == 0
