@@ -298,7 +298,20 @@ static int plan_workspace_uncached(const lbp_shape_t *s, int patch, int r, int n
         double est = 0.85 * (w.est_us + x[pick].est_us);
         if (!fuse) est += 8.0 + ((double)Mr * s->Cin * 4 + (double)M * s->Cin * esz) / 4.0e6;
         const double launch_gap = 3.0;
-        if (w.est_us < 1e200 && x[pick].est_us < 1e200 && n_w + n_x[pick] <= 4L * num_cus &&
+        // Larger launches (up to eight workgroups per unit) are grouped too when the weight-gradient
+        // product has to be split along its reduction: that means few output tiles with long
+        // reductions and no stores, which, dispatched first, run beside the input-gradient
+        // workgroups and fill the matrix cores during their store bursts (measured: -7 % at 131072
+        // tokens x 768 channels r=16 and at the 49-token maps r=36; an unsplit weight-gradient product
+        // fills the device by itself and loses 5 % in a launch of that size).  Only where the
+        // input-gradient product keeps the tile and epilogue it would have had on its own: trading
+        // its 256-row tile for the pair's 128 x 128 costs more than the overlap gains (ViT-B fc1, r=36
+        // and 48: +5 to +7 %).
+        // Nor where the weight-gradient product on its own would run on 256 x 256 tiles (r=48: +4 %).
+        const bool same_gx = ws->gx.tile == x[pick].tile && ws->gx_fused == fuse;
+        const bool big_gw = kGemmTiles[ws->gw.tile].bm * kGemmTiles[ws->gw.tile].bn >= 256 * 256;
+        const long group_limit = (w.splits > 1 && same_gx && !big_gw ? 8L : 4L) * num_cus;
+        if (w.est_us < 1e200 && x[pick].est_us < 1e200 && n_w + n_x[pick] <= group_limit &&
             est < ws->gw.est_us + ws->gx.est_us + launch_gap) {
             ws->gw = w;
             ws->gx = x[pick];

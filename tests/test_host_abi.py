@@ -235,6 +235,14 @@ def test_launch_plans_of_the_benchmark_configurations(lib):
     assert "separate launches" in t and "fp32 64x64" in t and "fused" not in t
     t = plan(vitb, 8, 8, want_gx=False)
     assert "separate launches" in t and "gx:" not in t and "gW:" in t
+    # launches of four to eight workgroups per compute unit: one grouped launch if the weight-gradient
+    # product is split along its reduction and the input-gradient product keeps its own tile
+    t = plan(S(128, 32, 32, 768, 768, 1, 0), 8, 16)     # 131072 tokens x 768 channels: 1536 + 252 workgroups
+    assert "one grouped launch" in t and "split-K 7" in t and "fused (matrix-core epilogue)" in t
+    t = plan(S(128, 7, 7, 3072, 768, 1, 0), 8, 36)      # 49-token maps
+    assert "one grouped launch" in t and "split-K 3" in t
+    t = plan(S(32, 16, 16, 4096, 1024, 1, 0), 8, 32)    # the weight-gradient product fills the device alone
+    assert "separate launches" in t and "split-K 1;" in t
     # the switches change the plan at once (the plan cache is keyed on what they decide)
     grouped = plan(vitb, 8, 8)
     binding.set_option("LBP_GEMM_GROUP", "0")
