@@ -288,6 +288,8 @@ int lbp_release_workspace(void);
  *   "LBP_GEMM_GROUP"      "0" | "1" | "2"                   the two products in separate launches / grouped where possible /
  *                                                           grouped with the weight-gradient workgroups always first
  *   "LBP_GX_COEF"         "f32" | "bf16"                    coefficients handed to an unfused reverse projection
+ *   "LBP_GX_JOIN"         "1" .. "8"                        slices of the fused input-gradient product's reduction that
+ *                                                           combine inside the grouped launch (default: chosen per shape)
  * Returns LBP_ERR_NULL (name is NULL) or LBP_ERR_OPTION (unknown name or value).  No HIP call.
  */
 int lbp_set_option(const char *name, const char *value);

@@ -106,7 +106,7 @@ def version():
     return int(load().lbp_version())
 
 
-OPTIONS = ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_GEMM_TILE", "LBP_FUSE_UNPROJECT", "LBP_GEMM_GROUP", "LBP_GX_COEF")
+OPTIONS = ("LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_GEMM_TILE", "LBP_FUSE_UNPROJECT", "LBP_GEMM_GROUP", "LBP_GX_COEF", "LBP_GX_JOIN")
 
 
 def set_option(name, value):

@@ -4,7 +4,25 @@
 #include "gemm_mfma_impl.h"
 
 namespace lbp {
+// Tile counters of the split reductions that combine inside a launch: zero whenever no such launch is
+// running (the device image loads them as zeros and every launch leaves them so).  Each device has its
+// own copy, found on first use.  Launches that overlap in time on one device must not both use them.
+static __device__ unsigned join_counters[kJoinMaxTiles];
+
 namespace {
+
+unsigned *join_counter_ptr()
+{
+    static unsigned *ptrs[mfma::kMaxLaunchDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= mfma::kMaxLaunchDevices) return nullptr;
+    if (!ptrs[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(join_counters)) != hipSuccess) return nullptr;
+        ptrs[dev] = static_cast<unsigned *>(ptr);
+    }
+    return ptrs[dev];
+}
 
 int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
@@ -55,7 +73,9 @@ hipError_t prepare(const GemmArgs &a, int *tile_out, mfma::Params *out, int *lp_
     // rows of a k-fast A are clamped one by one (any M); a k-slow A and B are read in 8-element pieces
     if (a.M < (a.a_kfast ? 1 : 8) || a.N < 8 || a.K < 1) return hipErrorInvalidValue;
     if (a.N % 8 || a.ldb % 8 || a.lda % 8 || (a.a_kfast ? a.K % 8 : a.M % 8)) return hipErrorInvalidValue;
-    if (a.out != GemmOut::kF32 && a.splits != 1) return hipErrorInvalidValue;
+    // split reductions: fp32 slices for a reduction kernel, or a fused reverse projection whose slices combine in the launch
+    if (a.out != GemmOut::kF32 && a.splits != 1 && !(a.out == GemmOut::kUnproject && a.join_parts && a.splits <= 16))
+        return hipErrorInvalidValue;
     int tile = options().gemm_tile;     // testing: force one tile shape for every product
     if (tile >= 0 && a.out == GemmOut::kUnproject &&
         (!kGemmTiles[tile].fused || (a.plan && !gemm_unproject_pooled(*a.plan) && kGemmTiles[tile].bn != 128)))
@@ -102,6 +122,16 @@ hipError_t prepare(const GemmArgs &a, int *tile_out, mfma::Params *out, int *lp_
         p.extra = a.extra > 0 ? a.extra : 1;
     }
     p.tiles_m = (a.M + p.bm_step - 1) / p.bm_step;
+    p.splits = 1;
+    if (a.out == GemmOut::kUnproject && a.splits > 1) {
+        if ((long)p.tiles_m * p.tiles_n > kJoinMaxTiles) return hipErrorInvalidValue;
+        if ((long)(a.splits - 1) * p.k_per_split >= a.K) return hipErrorInvalidValue;       // no empty slice
+        if ((size_t)p.tiles_m * p.tiles_n * a.splits * t.bm * t.bn * sizeof(float) > a.join_bytes) return hipErrorInvalidValue;
+        p.splits = a.splits;
+        p.parts = static_cast<float *>(a.join_parts);
+        p.counters = join_counter_ptr();
+        if (!p.counters) return hipErrorInvalidSymbol;
+    }
     // The tiles of one XCD (T / 8 of them) as an xcd_a x xcd_b block of the output: the block shape
     // whose strips of A and B together are the fewest bytes for that XCD's L2 to fetch.
     p.xcd_a = p.xcd_b = 0;
@@ -139,12 +169,23 @@ bool pair_tiles_ok(int tx, int tw)
 
 }  // namespace
 
+size_t gemm_join_bytes(int tile, long M_rows, long N, int r, int splits)
+{
+    if (tile < 0 || tile >= kNumGemmTiles || r < 1 || splits < 2) return 0;
+    const GemmTileInfo &t = kGemmTiles[tile];
+    const long bm_step = t.bm / r * r;
+    if (bm_step < 1) return 0;
+    const long tiles = ((M_rows + bm_step - 1) / bm_step) * ((N + t.bn - 1) / t.bn);
+    return (size_t)tiles * splits * t.bm * t.bn * sizeof(float);
+}
+
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
 {
     int tile, lp;
     mfma::Params p;
     hipError_t e = prepare(a, &tile, &p, &lp);
     if (e != hipSuccess) return e;
+    if (a.out == GemmOut::kUnproject && a.splits != 1) return hipErrorInvalidValue;       // grouped launches only
     return kLaunch[tile](p, a.a_kfast, a.out, lp, a.splits, stream);
 }
 
@@ -157,7 +198,7 @@ bool gemm_pair_supported(const GemmArgs &x, const GemmArgs &w, GemmPath path)
     int tx, tw, lp;
     mfma::Params p;
     if (prepare(x, &tx, &p, &lp) != hipSuccess || prepare(w, &tw, &p, &lp) != hipSuccess) return false;
-    if (tw == kPairTileThin && x.out == GemmOut::kUnproject && !gemm_unproject_pooled(*x.plan)) return false;
+    if (tw == kPairTileThin && x.out == GemmOut::kUnproject && (!gemm_unproject_pooled(*x.plan) || x.splits != 1)) return false;
     return pair_tiles_ok(tx, tw);
 }
 

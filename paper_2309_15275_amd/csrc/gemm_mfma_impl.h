@@ -62,6 +62,10 @@ struct Params {
     unsigned char nat[64];   // natural (Sylvester) index of every selected basis (matrix-core epilogue, patch 8)
     int mfma_epilogue;    // 1: the selection cannot be pooled, Eq. 7 runs on the matrix cores in the epilogue
     int store_bf16;       // EPI_PLAIN: 1 stores bf16, 0 stores fp32 (slice by slice)
+    // reduction split over `splits` workgroups per tile that combine inside the launch (JOIN kernels only)
+    int splits;           // slices per tile
+    float *parts;         // [tile][slice][BM * BN] partial accumulators
+    unsigned *counters;   // one per tile, zero between launches
 };
 
 // Scheduling hint for one sub-step of the main loop: N matrix instructions with R LDS reads spread
@@ -159,9 +163,52 @@ struct Smem {
     static constexpr int TOTAL = 2 * STAGE;
 };
 
+// Split reductions that are combined inside the launch.  Every workgroup of a tile stores its partial
+// accumulators, then counts itself in on the tile's counter; whichever comes last adds all the parts
+// in slice order (so the sum does not depend on who came last) and goes on to the epilogue.  Nobody
+// waits.  Parts travel from one XCD's L2 to another's: they are written and read with device-scope
+// accesses (8 bytes per lane), which go to the point where the XCDs are coherent, so that no cache has
+// to be written back or invalidated as a whole, which is what a device-scope fence would cost
+// (measured: tens of microseconds per launch).  The last workgroup leaves the counter at zero.
+template <int TM, int TN>
+__device__ __forceinline__ void store_part(float *slot, const f32x16_t (&acc)[TM][TN])
+{
+    unsigned long long *dst = reinterpret_cast<unsigned long long *>(slot) + threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                const unsigned long long v = (unsigned long long)__float_as_uint(acc[i][j][2 * g]) |
+                                             ((unsigned long long)__float_as_uint(acc[i][j][2 * g + 1]) << 32);
+                __hip_atomic_store(dst + (size_t)((i * TN + j) * 8 + g) * blockDim.x, v, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+}
+
+template <int TM, int TN>
+__device__ __forceinline__ void add_part(float *slot, f32x16_t (&sum)[TM][TN])
+{
+    unsigned long long *src = reinterpret_cast<unsigned long long *>(slot) + threadIdx.x;
+    unsigned long long v[TM * TN * 8];            // all loads of the part in flight together
+#pragma unroll
+    for (int q = 0; q < TM * TN * 8; ++q)
+        v[q] = __hip_atomic_load(src + (size_t)q * blockDim.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                sum[i][j][2 * g] += __uint_as_float((unsigned)v[(i * TN + j) * 8 + g]);
+                sum[i][j][2 * g + 1] += __uint_as_float((unsigned)(v[(i * TN + j) * 8 + g] >> 32));
+            }
+}
+
 // One workgroup's share of a product: output tile `tile_id` (before the XCD renumbering), split-K
 // slice `slice`; `smem` is the workgroup's dynamic LDS (at least Smem<BM, BN, A_KFAST>::TOTAL bytes).
-template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
+template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP, bool JOIN = false>
 __device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, const int slice, unsigned char *smem)
 {
     static_assert(PF == 2 || PF == 4, "prefetch depth must be even");
@@ -386,6 +433,29 @@ __device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, co
         __syncthreads();
     }
 
+    if constexpr (JOIN) {
+        if (p.splits > 1) {
+            __shared__ unsigned arrived;
+            float *const tile_parts = p.parts + (size_t)tile_id * p.splits * (BM * BN);
+            store_part<TM, TN>(tile_parts + (size_t)slice * (BM * BN), acc);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0);        // every lane's part has arrived before the workgroup counts itself in
+            __syncthreads();
+            if (tid == 0)
+                arrived = __hip_atomic_fetch_add(p.counters + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            if (arrived != (unsigned)(p.splits - 1)) return;      // the same for every lane of the workgroup
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int z = 0; z < p.splits; ++z) add_part<TM, TN>(tile_parts + (size_t)z * (BM * BN), acc);
+            if (tid == 0) __hip_atomic_store(p.counters + tile_id, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
     // accumulator element 4*g4 + e of a 32x32 tile: row 8*g4 + 4*(lane/32) + e, column lane%32
     if constexpr (EPI == EPI_UNPROJECT_MFMA) {
         // Eq. 7 for selections that cannot be pooled (patch 8): per patch, tokens[64][BN] =
@@ -637,7 +707,7 @@ struct PairParams {
 };
 
 template <int WGM, int WGN, int PF, int BM1, int BN1, bool KF1, int EPI1, int LP1, int BM2, int BN2, bool KF2,
-          int EPI2, int LP2>
+          int EPI2, int LP2, bool JOIN1 = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pair_kernel(PairParams pp)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -648,7 +718,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pair_kernel(PairParams pp
     if (b < pp.blocks_first) {
         const int T = pp.first.tiles_m * pp.first.tiles_n;
         const int z = b / T;
-        gemm_body<BM1, BN1, WGM, WGN, PF, KF1, EPI1, LP1>(pp.first, b - z * T, z, smem);
+        gemm_body<BM1, BN1, WGM, WGN, PF, KF1, EPI1, LP1, JOIN1>(pp.first, b - z * T, z, smem);
     } else {
         const int c = b - pp.blocks_first;
         const int T = pp.second.tiles_m * pp.second.tiles_n;
@@ -658,13 +728,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pair_kernel(PairParams pp
 }
 
 template <int WGM, int WGN, int PF, int BM1, int BN1, bool KF1, int EPI1, int LP1, int BM2, int BN2, bool KF2,
-          int EPI2, int LP2>
+          int EPI2, int LP2, bool JOIN1 = false>
 hipError_t launch_pair(const Params &first, int splits_first, const Params &second, int splits_second,
                        hipStream_t stream, bool second_leads = false)
 {
     constexpr int L1 = Smem<BM1, BN1, KF1>::TOTAL, L2 = Smem<BM2, BN2, KF2>::TOTAL;
     constexpr int LDS = L1 > L2 ? L1 : L2;
-    auto kern = gemm_pair_kernel<WGM, WGN, PF, BM1, BN1, KF1, EPI1, LP1, BM2, BN2, KF2, EPI2, LP2>;
+    auto kern = gemm_pair_kernel<WGM, WGN, PF, BM1, BN1, KF1, EPI1, LP1, BM2, BN2, KF2, EPI2, LP2, JOIN1>;
     static bool configured[kMaxLaunchDevices] = {};
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), LDS, configured);
     if (e != hipSuccess) return e;

@@ -6,10 +6,11 @@ namespace lbp {
 namespace {
 using namespace mfma;
 
-template <int BMX, int EPIX, int LPX>
+template <int BMX, int EPIX, int LPX, bool JOINX = false>
 hipError_t pair(const Params &x, int splits_x, const Params &w, int splits_w, hipStream_t s, bool w_leads)
 {
-    return launch_pair<2, 4, 2, BMX, 128, true, EPIX, LPX, 128, 128, false, EPI_PLAIN, 0>(x, splits_x, w, splits_w, s, w_leads);
+    return launch_pair<2, 4, 2, BMX, 128, true, EPIX, LPX, 128, 128, false, EPI_PLAIN, 0, JOINX>(x, splits_x, w, splits_w, s,
+                                                                                                 w_leads);
 }
 
 template <int BMX>
@@ -17,7 +18,11 @@ hipError_t pair_bm(const Params &x, GemmOut out_x, int splits_x, const Params &w
                    bool w_leads)
 {
     if (out_x == GemmOut::kUnproject) {
-        if (splits_x != 1) return hipErrorInvalidValue;
+        if (splits_x != 1) {        // the slices of a tile combine inside the launch, the last one runs the epilogue
+            if (!x.parts || !x.counters || x.splits != splits_x) return hipErrorInvalidValue;
+            if (x.mfma_epilogue) return pair<BMX, EPI_UNPROJECT_MFMA, 3, true>(x, splits_x, w, splits_w, s, w_leads);
+            return pair<BMX, EPI_UNPROJECT, 3, true>(x, splits_x, w, splits_w, s, w_leads);
+        }
         if (x.mfma_epilogue) return pair<BMX, EPI_UNPROJECT_MFMA, 3>(x, 1, w, splits_w, s, w_leads);
         return pair<BMX, EPI_UNPROJECT, 3>(x, 1, w, splits_w, s, w_leads);
     }

@@ -156,7 +156,7 @@ int plan_call(const lbp_shape_t *shape, int extra, int patch, int r, const lbp::
         !lbp::unproject_bf16_supported(plan, static_cast<lbp::WhtPath>(opt.wht_path), shape->dtype, shape->Cin))
         coef16 = 0;
     return lbp::plan_workspace(shape, patch, r, num_cus, can_fuse, fuse_env == 1, ws,
-                               !lbp::gemm_unproject_pooled(plan), allow_group, extra, coef16);
+                               !lbp::gemm_unproject_pooled(plan), allow_group, extra, coef16, opt.gx_join);
 }
 
 // Describes the weight-gradient product; returns true when it leaves fp32 partial sums in `part`
@@ -238,11 +238,14 @@ size_t lbp_wht_workspace_bytes_tokens(const lbp_shape_t *shape, int extra, int p
     // both gradients are requested: report the largest
     size_t total = 0;
     for (int v = 0; v < 24; ++v) {
-        lbp::WorkspacePlan ws;
-        if (lbp::plan_workspace(shape, patch, r, cus, (v & 1) != 0, false, &ws, (v & 2) != 0, (v & 4) != 0, extra,
-                                v >> 3) != LBP_OK)
-            return 0;
-        if (ws.total > total) total = ws.total;
+        for (int join = 0; join <= 8; ++join) {      // (0: the planner's choice; 1..8: what LBP_GX_JOIN can force)
+            lbp::WorkspacePlan ws;
+            if (lbp::plan_workspace(shape, patch, r, cus, (v & 1) != 0, false, &ws, (v & 2) != 0, (v & 4) != 0, extra,
+                                    v >> 3, join) != LBP_OK)
+                return 0;
+            if (ws.total > total) total = ws.total;
+            if (patch == 0 || !(v & 4)) break;       // only grouped plans have joined slices
+        }
         if (patch == 0) break;
     }
     if (patch == 0 && shape->dtype == LBP_BF16)   // staging of gx for the plain cross-check kernels
@@ -528,6 +531,16 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
             g.plan = &plan;
             g.extra = extra;
             g.extra_rows = N * extra;
+            if (ws.grouped && gW && ws.gx_join > 1) {       // slices that combine inside the grouped launch
+                g.splits = ws.gx_join;
+                g.join_parts = gx_r;
+                g.join_bytes = ws.gx_join_bytes;
+                if (!lbp::gemm_pair_supported(g, gw_args, gpath)) {     // (the planner only asks where the kernels exist)
+                    g.splits = 1;
+                    g.join_parts = nullptr;
+                    g.join_bytes = 0;
+                }
+            }
         } else if (ws.gx_coef16) {
             g.splits = 1;
             g.out = lbp::GemmOut::kBF16;
@@ -619,8 +632,10 @@ int lbp_wht_describe_plan(const lbp_shape_t *shape, int extra, int patch, const 
                       ws.gw.splits, ws.gw.splits > 1 ? " + reduction kernel" : "");
     if (want_gx) {
         if (ws.gx_fused)
-            std::snprintf(gxs, sizeof gxs, "gx: tile %s, reverse projection fused (%s epilogue); ",
-                          lbp::kGemmTiles[ws.gx.tile].name, lbp::gemm_unproject_pooled(plan) ? "pooled" : "matrix-core");
+            std::snprintf(gxs, sizeof gxs, "gx: tile %s, reverse projection fused (%s epilogue)%s%.0d%s; ",
+                          lbp::kGemmTiles[ws.gx.tile].name, lbp::gemm_unproject_pooled(plan) ? "pooled" : "matrix-core",
+                          ws.gx_join > 1 ? ", reduction in " : "", ws.gx_join > 1 ? ws.gx_join : 0,
+                          ws.gx_join > 1 ? " slices joined in the launch" : "");
         else if (ws.gx_coef16)
             std::snprintf(gxs, sizeof gxs, "gx: tile %s, bf16 coefficients + %s reverse-projection kernel; ",
                           lbp::kGemmTiles[ws.gx.tile].name,

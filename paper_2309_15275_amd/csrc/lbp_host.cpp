@@ -224,11 +224,32 @@ long gemm_workgroups(const GemmPlan &g, long M, long N, int fused_r)
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+double grouped_launch_estimate(long n_x, double cost_x, long n_w, double cost_w, int num_cus, bool w_first)
+{
+    if (num_cus < 1) num_cus = 256;
+    // unit j gets the workgroups j, j + num_cus, j + 2 num_cus, ... of the dispatch order; count how many of
+    // each kind that is for the fullest unit of each residue class
+    const long n_first = w_first ? n_w : n_x, n_second = w_first ? n_x : n_w;
+    const double c_first = w_first ? cost_w : cost_x, c_second = w_first ? cost_x : cost_w;
+    double worst = 0.0;
+    for (int j = 0; j < num_cus; ++j) {
+        // indices i = j + k num_cus below n_first are of the first kind, the rest up to n_first + n_second of the second
+        const long total = n_first + n_second;
+        if (j >= total) break;
+        const long mine = (total - 1 - j) / num_cus + 1;
+        const long mine_first = j < n_first ? (n_first - 1 - j) / num_cus + 1 : 0;
+        const double load = mine_first * c_first + (mine - mine_first) * c_second;
+        if (load > worst) worst = load;
+    }
+    return worst;
+}
+
 static int plan_workspace_uncached(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
                                    bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group, int extra,
-                                   int coef16)
+                                   int coef16, int gx_join)
 {
     std::memset(ws, 0, sizeof *ws);
+    ws->gx_join = 1;
     if (num_cus < 1) num_cus = 256;
     const size_t esz = dtype_size(s->dtype);
     const int gw_bytes = (int)dtype_size(s->gw_dtype);
@@ -318,6 +339,49 @@ static int plan_workspace_uncached(const lbp_shape_t *s, int patch, int r, int n
             ws->gx.est_us = est - w.est_us;
             ws->gx_fused = fuse;
             ws->grouped = true;
+            // A fused input-gradient product cannot hand split-K slices to a reduction kernel, so with few
+            // low-rank rows and many output channels it is a handful of workgroups walking a long reduction
+            // while the rest of the device waits.  Its kernel can split the reduction over workgroups that
+            // combine inside the launch (the last one of a tile to finish adds the parts and runs the
+            // epilogue).  Whether that pays is decided with a model of the launch fitted to measurements
+            // (times in microseconds: a 64-deep step of a 64- or 128-row tile 0.40 / 0.60, of the weight
+            // gradient 0.70; the epilogue's stores at 45 GB/s per workgroup; storing a part 2, reading the
+            // parts back 3 + s / 4): ViT-L fc1 r=4 32.2 -> 23.0 us with four slices, r=8 38.4 -> 33.7 with
+            // two, ViT-B fc1 with 8 images 23.4 -> 16.3 with four; ViT-B fc1 with 64 images, ViT-L fc1 r=16
+            // and ViT-L fc2 lose 10-30 % with any split and the model keeps them whole.
+            if (fuse && !thin) {
+                const GemmTileInfo &tx = kGemmTiles[x[pick].tile];
+                const long bm_step = tx.bm / r * r;
+                const long steps_x = (s->Cout + 63) / 64;
+                const long steps_w = ((Mr + w.splits - 1) / w.splits + 63) / 64;
+                const double t_x = tx.bm <= 64 ? 0.40 : 0.60;
+                const double epi_x = (double)(bm_step / r) * patch * patch * tx.bn * esz / 45.0e3;
+                const double cost_w = steps_w * 0.70 + 2.0;
+                const long n_wg_w = n_w;        // gemm_workgroups counts the slices
+                auto estimate = [&](int sl) {
+                    const long st = ((s->Cout + sl - 1) / sl + 63) / 64;
+                    const double cost_x = st * t_x + epi_x + (sl > 1 ? 5.0 + 0.25 * sl : 0.0);
+                    const long n = n_x[pick] * sl;
+                    return grouped_launch_estimate(n, cost_x, n_wg_w, cost_w, num_cus, n + n_wg_w > 2L * num_cus);
+                };
+                int best = 1;
+                double best_us = estimate(1);
+                const double whole_us = best_us;
+                for (int sl = 2; sl <= 8; ++sl) {
+                    if (gx_join > 0 && sl != gx_join) continue;
+                    const long k_slice = ((s->Cout + sl - 1) / sl + 63) / 64 * 64;
+                    if (k_slice < 4 * 64 || (long)(sl - 1) * k_slice >= s->Cout) continue;     // no short or empty slice
+                    if (n_x[pick] > 16384) continue;
+                    const double us = estimate(sl);
+                    if (gx_join > 0 || us < best_us) {
+                        best_us = us;
+                        best = sl;
+                    }
+                }
+                (void)steps_x;
+                if (gx_join == 1 || (gx_join == 0 && best_us > 0.9 * whole_us)) best = 1;     // a split has to gain a tenth
+                ws->gx_join = best;
+            }
         }
     }
     // Where the reverse projection stays a kernel of its own, the product can hand it bf16
@@ -341,6 +405,19 @@ static int plan_workspace_uncached(const lbp_shape_t *s, int patch, int r, int n
     off += align_up((size_t)Mr * s->Cin * esz, 256);
     ws->gx_r = off;
     if (!ws->gx_fused) off += align_up((size_t)ws->gx.splits * Mr * s->Cin * (ws->gx_coef16 ? 2 : 4), 256);
+    else if (ws->gx_join > 1) {      // the slices' partial tiles, for either tile the grouped launch may run them on
+        size_t need = 0;
+        for (int t : {4, 5}) {
+            const GemmTileInfo &tx = kGemmTiles[t];
+            const long bm_step = tx.bm / r * r;
+            if (bm_step < 1) continue;
+            const long tiles = ((Mr + bm_step - 1) / bm_step) * ((s->Cin + tx.bn - 1) / tx.bn);
+            const size_t bytes = (size_t)tiles * ws->gx_join * tx.bm * tx.bn * 4;
+            if (bytes > need) need = bytes;
+        }
+        ws->gx_join_bytes = need;
+        off += align_up(need, 256);
+    }
     ws->splitk = off;
     off += align_up((size_t)ws->gw.splits * s->Cout * s->Cin * 4, 256);
     ws->total = off;
@@ -351,7 +428,7 @@ static int plan_workspace_uncached(const lbp_shape_t *s, int patch, int r, int n
 // factors; a training loop calls with the same few layers over and over, so the last plans are kept.
 namespace {
 struct PlanKey {
-    int32_t v[16];
+    int32_t v[20];
     bool operator==(const PlanKey &o) const { return std::memcmp(v, o.v, sizeof v) == 0; }
 };
 struct PlanSlot {
@@ -366,11 +443,13 @@ unsigned g_plan_next = 0;
 }  // namespace
 
 int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can_fuse,
-                   bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group, int extra, int coef16)
+                   bool force_fuse, WorkspacePlan *ws, bool fused_wide, bool allow_group, int extra, int coef16,
+                   int gx_join)
 {
     if (!s || !ws) return LBP_ERR_NULL;
+    if (gx_join < 0 || gx_join > 8) return LBP_ERR_OPTION;
     const PlanKey key{{s->N, s->H, s->W, s->Cin, s->Cout, s->dtype, s->gw_dtype, patch, r, num_cus, can_fuse,
-                       force_fuse, fused_wide, allow_group, extra, coef16}};
+                       force_fuse, fused_wide, allow_group, extra, coef16, gx_join}};
     {
         std::lock_guard<std::mutex> lock(g_plan_mutex);
         for (const PlanSlot &slot : g_plan_cache)
@@ -380,7 +459,7 @@ int plan_workspace(const lbp_shape_t *s, int patch, int r, int num_cus, bool can
             }
     }
     const int rc = plan_workspace_uncached(s, patch, r, num_cus, can_fuse, force_fuse, ws, fused_wide, allow_group,
-                                           extra, coef16);
+                                           extra, coef16, gx_join);
     if (rc != LBP_OK) return rc;
     std::lock_guard<std::mutex> lock(g_plan_mutex);
     PlanSlot &slot = g_plan_cache[g_plan_next++ % kPlanSlots];
@@ -397,7 +476,7 @@ Options g_opt;
 bool g_opt_env_read = false;
 
 const char *const kOptionNames[] = {"LBP_WHT_PATH", "LBP_GEMM_PATH", "LBP_GEMM_TILE", "LBP_FUSE_UNPROJECT",
-                                    "LBP_GEMM_GROUP", "LBP_GX_COEF"};
+                                    "LBP_GEMM_GROUP", "LBP_GX_COEF", "LBP_GX_JOIN"};
 
 // Applies one switch to `o`; value NULL or "" restores the default.
 int apply_option(Options *o, const char *name, const char *value)
@@ -434,6 +513,14 @@ int apply_option(Options *o, const char *name, const char *value)
         else if (is("0")) o->gemm_group = 0;
         else if (is("2")) o->gemm_group = 2;
         else return LBP_ERR_OPTION;
+    } else if (!std::strcmp(name, "LBP_GX_JOIN")) {
+        if (reset) o->gx_join = def.gx_join;
+        else {
+            char *end = nullptr;
+            const long v = std::strtol(value, &end, 10);
+            if (*end || end == value || v < 1 || v > 8) return LBP_ERR_OPTION;
+            o->gx_join = (int)v;
+        }
     } else if (!std::strcmp(name, "LBP_GX_COEF")) {
         if (reset) o->gx_coef = def.gx_coef;
         else if (is("f32")) o->gx_coef = 0;

@@ -118,6 +118,9 @@ struct WorkspacePlan {
     bool grouped;                      // both products run in one launch (tiles chosen for that)
     bool gx_coef16;                    // not fused: the product stores its coefficients as bf16 in one
                                        // piece (no split-K) and the reverse projection reads those
+    int gx_join;                       // fused and grouped: slices of the input-gradient product's reduction that
+                                       // combine inside the launch (1: none); their partial tiles live at gx_r,
+    size_t gx_join_bytes;              // in this many bytes
 };
 
 // num_cus: compute units of the device (the GEMM plans depend on it); pass 256 when unknown.
@@ -127,9 +130,16 @@ struct WorkspacePlan {
 // extra: tokens per image in front of the grid (tensors are [N][extra + H*W][C]);
 // coef16: 1 = the caller has a reverse projection that reads bf16 coefficients (gx_coef16 may be
 // chosen), 2 = take it whenever the reverse projection is not fused, 0 = never.
+// gx_join: 0 = choose the number of joined slices of a fused, grouped input-gradient product, n = take n.
 int plan_workspace(const lbp_shape_t *shape, int patch, int r, int num_cus, bool can_fuse,
                    bool force_fuse, WorkspacePlan *ws, bool fused_wide = false, bool allow_group = false,
-                   int extra = 0, int coef16 = 0);
+                   int extra = 0, int coef16 = 0, int gx_join = 0);
+
+// Estimated length in microseconds of a grouped launch on `num_cus` compute units: n_x workgroups of the
+// input-gradient product (cost_x each) and n_w of the weight-gradient product (cost_w each), dispatched
+// in that order (or the other way round), the i-th workgroup to unit i mod num_cus, workgroups on one
+// unit sharing it.
+double grouped_launch_estimate(long n_x, double cost_x, long n_w, double cost_w, int num_cus, bool w_first);
 
 const char *status_string(int code);
 
@@ -141,6 +151,7 @@ struct Options {
     int fuse_unproject = -1;   // -1 planner, 0 never, 1 wherever the kernel supports the selection
     int gemm_group = 1;        // 0: the two products of a call in separate launches; 2: one launch, weight gradient first
     int gx_coef = 1;           // 1 planner, 0 fp32 slices, 2 bf16 wherever the kernels allow
+    int gx_join = 0;           // 0 planner, 1..8: that many joined slices wherever the grouped fused launch runs
 };
 // The current switches; the first call reads the LBP_* environment variables, once per process.
 Options options();

@@ -284,6 +284,82 @@ def test_every_gemm_tile_shape_matches_oracle(case, tile):
     assert_matches(gW, gW0, 5e-3, "exact gW")
 
 
+# (N, H, W, Cin, Cout, patch, r, order, tokens in front of the grid): reductions over Cout long enough to cut
+JOINED = [
+    (2, 16, 16, 72, 520, 8, 8, "l1", 0),        # pooled epilogue, tails in every dimension
+    (3, 16, 24, 136, 776, 8, 4, "l1", 0),
+    (2, 16, 16, 72, 520, 8, 21, "l1", 0),       # matrix-core epilogue, 126-row tiles
+    (2, 14, 14, 264, 1032, 8, 8, "l1", 1),      # zero-padded grid with a class token
+    (4, 7, 7, 136, 512, 8, 15, "l1", 0),        # one padded patch per image
+    (6, 16, 32, 264, 1544, 8, 16, "linf", 0),   # several tiles along every dimension
+]
+
+
+@pytest.mark.parametrize("tile", [None, "4"])        # the planner's 64-row tile for the input gradient, or 128 rows for both
+@pytest.mark.parametrize("slices", ["2", "3", "8"])
+@pytest.mark.parametrize("case", range(len(JOINED)))
+def test_input_gradient_reduction_cut_into_slices_that_join_inside_the_launch(case, slices, tile):
+    # the fused input-gradient product of a grouped launch with its reduction over Cout in 2, 3 or 8 slices: every
+    # slice leaves a partial tile, the last one to finish adds them in slice order and runs the reverse projection
+    N, H, W, Cin, Cout, patch, r, order, extra = JOINED[case]
+    wl = small("join", N, H, W, Cin, Cout, patch, "bf16", 610 + case)
+    idx = oracle.select_bases(patch, r, order)
+    if extra:
+        host = workloads.make_token_inputs(wl, extra)
+        dev = {k: to_device(v, "bf16") for k, v in host.items()}
+        want_gx, want_gw = oracle.lbp_wht_backward_tokens(host["x"], host["gy"], host["w"], (H, W), patch, idx)
+
+        def call():
+            gx = torch.full((N, extra + H * W, Cin), float("nan"), dtype=dev["x"].dtype, device="cuda")
+            gW = torch.full((Cout, Cin), float("nan"), dtype=torch.float32, device="cuda")
+            binding.lbp_wht_backward_tokens(dev["x"], dev["gy"], dev["w"], (H, W), patch, idx, gx=gx, gW=gW)
+            return gx, gW
+    else:
+        host, dev = device_inputs(wl)
+        want_gx, want_gw = oracle.lbp_wht_backward_padded(host["x"], host["gy"], host["w"], patch, idx)
+
+        def call():
+            return lbp_backward(dev, patch, idx)
+    binding.set_option("LBP_GEMM_TILE", tile)
+    binding.set_option("LBP_FUSE_UNPROJECT", "1")
+    shape = binding.LbpShape(N, H, W, Cin, Cout, binding.LBP_BF16, binding.LBP_F32)
+    # a workspace of the test's own, filled with a byte pattern: what a call writes there can be counted
+    binding.set_option("LBP_GX_JOIN", slices)
+    space = torch.empty(binding.workspace_bytes(shape, patch, r, extra=extra) + 256, dtype=torch.uint8, device="cuda")
+    binding.set_workspace(space)
+    try:
+        binding.set_option("LBP_GX_JOIN", "1")
+        space.fill_(0xCD)
+        gx1, gW1 = call()
+        torch.cuda.synchronize()
+        written_whole = int((space != 0xCD).sum())
+        binding.set_option("LBP_GX_JOIN", slices)
+        text = binding.describe_plan(shape, patch, idx, extra=extra)
+        k_slice = -(-(-(-Cout // int(slices))) // 64) * 64
+        cut = k_slice >= 256 and (int(slices) - 1) * k_slice < Cout          # no short and no empty slice
+        assert (f"reduction in {slices} slices joined in the launch" in text) == cut, text
+        assert "one grouped launch" in text, text
+        space.fill_(0xCD)
+        gx2, gW2 = call()
+        torch.cuda.synchronize()
+        written_cut = int((space != 0xCD).sum())
+        gx3, gW3 = call()
+        torch.cuda.synchronize()
+    finally:
+        binding.set_workspace(None)
+    assert torch.equal(gx2.view(torch.int16), gx3.view(torch.int16))      # whoever finishes a tile last, the same bits
+    assert torch.equal(gW1.view(torch.int32), gW2.view(torch.int32))      # the other product is untouched
+    # the slices leave their partial tiles in the workspace: a cut reduction writes more of it (else the launch
+    # silently ran the reduction in one piece)
+    if cut:
+        assert written_cut > written_whole + 64 * 128 * 2, (written_whole, written_cut)
+    else:
+        assert written_cut == written_whole and torch.equal(gx1.view(torch.int16), gx2.view(torch.int16))
+    assert_matches(gx2, want_gx, TOL["bf16"], "gx")
+    assert_matches(gW2, want_gw, TOL["bf16"], "gW")
+    assert_matches(gx1, want_gx, TOL["bf16"], "gx, one slice")
+
+
 @pytest.mark.parametrize("tile", ["4", "6"])
 @pytest.mark.parametrize("fuse", ["1", "0"])
 @pytest.mark.parametrize("case", [0, 3, 5, 10, 13])

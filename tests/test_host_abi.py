@@ -243,6 +243,19 @@ def test_launch_plans_of_the_benchmark_configurations(lib):
     assert "one grouped launch" in t and "split-K 3" in t
     t = plan(S(32, 16, 16, 4096, 1024, 1, 0), 8, 32)    # the weight-gradient product fills the device alone
     assert "separate launches" in t and "split-K 1;" in t
+    # few low-rank rows under a long reduction: the fused input-gradient product is cut into slices that join in the launch
+    vitl = S(32, 16, 16, 1024, 4096, 1, 0)
+    assert "reduction in 4 slices joined in the launch" in plan(vitl, 8, 4)
+    assert "reduction in 2 slices joined in the launch" in plan(vitl, 8, 8)
+    assert "joined" not in plan(vitl, 8, 16) and "joined" not in plan(S(32, 16, 16, 4096, 1024, 1, 0), 8, 4)
+    assert "reduction in 4 slices joined in the launch" in plan(S(8, 16, 16, 768, 3072, 1, 0), 8, 8)      # a small batch
+    assert "joined" not in plan(vitb, 8, 8)
+    binding.set_option("LBP_GX_JOIN", "3")
+    assert "reduction in 3 slices joined in the launch" in plan(vitb, 8, 8)
+    assert binding.workspace_bytes(vitb, 8, 8) >= int(plan(vitb, 8, 8).rsplit("workspace ", 1)[1].split()[0])
+    binding.set_option("LBP_GX_JOIN", "1")
+    assert "joined" not in plan(vitl, 8, 4)
+    binding.set_option("LBP_GX_JOIN", None)
     # the switches change the plan at once (the plan cache is keyed on what they decide)
     grouped = plan(vitb, 8, 8)
     binding.set_option("LBP_GEMM_GROUP", "0")
@@ -262,9 +275,11 @@ def test_option_switches_check_their_arguments(lib):
     assert f(b"LBP_GEMM_TILE", b"8") == -12 and f(b"LBP_GEMM_TILE", b"x") == -12 and f(b"LBP_GEMM_TILE", b"-1") == -12
     assert f(b"LBP_WHT_PATH", b"fast") == -12 and f(b"LBP_GX_COEF", b"f16") == -12
     assert f(b"LBP_FUSE_UNPROJECT", b"2") == -12 and f(b"LBP_GEMM_GROUP", b"yes") == -12
+    assert f(b"LBP_GX_JOIN", b"0") == -12 and f(b"LBP_GX_JOIN", b"9") == -12
     for name, values in (("LBP_WHT_PATH", ("generic", "register", "mfma", "auto")), ("LBP_GEMM_PATH", ("simple", "auto")),
                          ("LBP_GEMM_TILE", tuple(str(i) for i in range(8))), ("LBP_FUSE_UNPROJECT", ("0", "1")),
-                         ("LBP_GEMM_GROUP", ("0", "1", "2")), ("LBP_GX_COEF", ("f32", "bf16"))):
+                         ("LBP_GEMM_GROUP", ("0", "1", "2")), ("LBP_GX_COEF", ("f32", "bf16")),
+                         ("LBP_GX_JOIN", tuple(str(i) for i in range(1, 9)))):
         for v in values:
             assert f(name.encode(), v.encode()) == 0, (name, v)
         assert f(name.encode(), None) == 0
