@@ -92,7 +92,7 @@ def read_traffic(name, r, order):
 
 def sweep_cases(workloads):
     """(workload name, rank, order) of every benchmark row: the five configurations' ranks and
-    orders (the tiny fp32 exactness case included), the 49-token maps and the 197-token sequences."""
+    orders (the tiny fp32 exactness case included), the 49-token maps, the 197-token sequences and two small batches."""
     for name, wl in workloads.WORKLOADS.items():
         for r in wl.ranks:
             for order in wl.orders:

@@ -316,7 +316,47 @@ static int plan_workspace_uncached(const lbp_shape_t *s, int patch, int r, int n
         else if (n_w + n_x[1] <= num_cus) pick = 1;
         else if (n_w + n_x[0] <= 2 * num_cus) pick = 0;
         else pick = 1;
-        double est = 0.85 * (w.est_us + x[pick].est_us);
+        // A fused input-gradient product cannot hand split-K slices to a reduction kernel, so with few
+        // low-rank rows and many output channels it is a handful of workgroups walking a long reduction
+        // while the rest of the device waits.  Its kernel can split the reduction over workgroups that
+        // combine inside the launch (the last one of a tile to finish adds the parts and runs the
+        // epilogue).  Whether that pays is decided with a model of the launch fitted to measurements
+        // (times in microseconds: a 64-deep step of a 64- or 128-row tile 0.40 / 0.60, of the weight
+        // gradient 0.70; the epilogue's stores at 45 GB/s per workgroup; storing a part 2, reading the
+        // parts back 3 + s / 4): ViT-L fc1 r=4 32.2 -> 23.0 us with four slices, r=8 38.4 -> 33.7 with
+        // two, ViT-B fc1 with 8 images 23.4 -> 16.3 with four; ViT-B fc1 with 64 images, ViT-L fc1 r=16
+        // and ViT-L fc2 lose 10-30 % with any split and the model keeps them whole.
+        int join = 1;
+        double join_gain = 1.0;          // estimated time with the chosen slices over the time in one piece
+        if (fuse && !thin && n_x[pick] <= 16384) {
+            const GemmTileInfo &tx = kGemmTiles[x[pick].tile];
+            const long bm_step = tx.bm / r * r;
+            const long steps_w = ((Mr + w.splits - 1) / w.splits + 63) / 64;
+            const double t_x = tx.bm <= 64 ? 0.40 : 0.60;
+            const double epi_x = (double)(bm_step / r) * patch * patch * tx.bn * esz / 45.0e3;
+            const double cost_w = steps_w * 0.70 + 2.0;
+            auto estimate = [&](int sl) {
+                const long st = ((s->Cout + sl - 1) / sl + 63) / 64;
+                const double cost_x = st * t_x + epi_x + (sl > 1 ? 5.0 + 0.25 * sl : 0.0);
+                const long n = n_x[pick] * sl;      // (n_w counts the weight gradient's own slices)
+                return grouped_launch_estimate(n, cost_x, n_w, cost_w, num_cus, n + n_w > 2L * num_cus);
+            };
+            const double whole_us = estimate(1);
+            double best_us = whole_us;
+            for (int sl = 2; sl <= 8; ++sl) {
+                if (gx_join > 0 && sl != gx_join) continue;
+                const long k_slice = ((s->Cout + sl - 1) / sl + 63) / 64 * 64;
+                if (k_slice < 4 * 64 || (long)(sl - 1) * k_slice >= s->Cout) continue;     // no short or empty slice
+                const double us = estimate(sl);
+                if (gx_join > 0 || us < best_us) {
+                    best_us = us;
+                    join = sl;
+                }
+            }
+            if (gx_join == 0 && best_us > 0.9 * whole_us) join = 1;       // a split has to gain a tenth
+            if (join > 1 && gx_join == 0) join_gain = best_us / whole_us;     // (a forced count leaves the grouping as it was)
+        }
+        double est = 0.85 * (w.est_us + x[pick].est_us) * join_gain;
         if (!fuse) est += 8.0 + ((double)Mr * s->Cin * 4 + (double)M * s->Cin * esz) / 4.0e6;
         const double launch_gap = 3.0;
         // Larger launches (up to eight workgroups per unit) are grouped too when the weight-gradient
@@ -339,49 +379,7 @@ static int plan_workspace_uncached(const lbp_shape_t *s, int patch, int r, int n
             ws->gx.est_us = est - w.est_us;
             ws->gx_fused = fuse;
             ws->grouped = true;
-            // A fused input-gradient product cannot hand split-K slices to a reduction kernel, so with few
-            // low-rank rows and many output channels it is a handful of workgroups walking a long reduction
-            // while the rest of the device waits.  Its kernel can split the reduction over workgroups that
-            // combine inside the launch (the last one of a tile to finish adds the parts and runs the
-            // epilogue).  Whether that pays is decided with a model of the launch fitted to measurements
-            // (times in microseconds: a 64-deep step of a 64- or 128-row tile 0.40 / 0.60, of the weight
-            // gradient 0.70; the epilogue's stores at 45 GB/s per workgroup; storing a part 2, reading the
-            // parts back 3 + s / 4): ViT-L fc1 r=4 32.2 -> 23.0 us with four slices, r=8 38.4 -> 33.7 with
-            // two, ViT-B fc1 with 8 images 23.4 -> 16.3 with four; ViT-B fc1 with 64 images, ViT-L fc1 r=16
-            // and ViT-L fc2 lose 10-30 % with any split and the model keeps them whole.
-            if (fuse && !thin) {
-                const GemmTileInfo &tx = kGemmTiles[x[pick].tile];
-                const long bm_step = tx.bm / r * r;
-                const long steps_x = (s->Cout + 63) / 64;
-                const long steps_w = ((Mr + w.splits - 1) / w.splits + 63) / 64;
-                const double t_x = tx.bm <= 64 ? 0.40 : 0.60;
-                const double epi_x = (double)(bm_step / r) * patch * patch * tx.bn * esz / 45.0e3;
-                const double cost_w = steps_w * 0.70 + 2.0;
-                const long n_wg_w = n_w;        // gemm_workgroups counts the slices
-                auto estimate = [&](int sl) {
-                    const long st = ((s->Cout + sl - 1) / sl + 63) / 64;
-                    const double cost_x = st * t_x + epi_x + (sl > 1 ? 5.0 + 0.25 * sl : 0.0);
-                    const long n = n_x[pick] * sl;
-                    return grouped_launch_estimate(n, cost_x, n_wg_w, cost_w, num_cus, n + n_wg_w > 2L * num_cus);
-                };
-                int best = 1;
-                double best_us = estimate(1);
-                const double whole_us = best_us;
-                for (int sl = 2; sl <= 8; ++sl) {
-                    if (gx_join > 0 && sl != gx_join) continue;
-                    const long k_slice = ((s->Cout + sl - 1) / sl + 63) / 64 * 64;
-                    if (k_slice < 4 * 64 || (long)(sl - 1) * k_slice >= s->Cout) continue;     // no short or empty slice
-                    if (n_x[pick] > 16384) continue;
-                    const double us = estimate(sl);
-                    if (gx_join > 0 || us < best_us) {
-                        best_us = us;
-                        best = sl;
-                    }
-                }
-                (void)steps_x;
-                if (gx_join == 1 || (gx_join == 0 && best_us > 0.9 * whole_us)) best = 1;     // a split has to gain a tenth
-                ws->gx_join = best;
-            }
+            ws->gx_join = join;
         }
     }
     // Where the reverse projection stays a kernel of its own, the product can hand it bf16

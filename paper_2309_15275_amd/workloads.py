@@ -64,6 +64,10 @@ WORKLOADS = {
     # ViT-B/16 on 224 x 224 images as the layer really sees it: a class token in front of 14 x 14
     # patch tokens (197 per image); the grid is zero-padded to 16 x 16, the class token kept exact.
     "vitb16_197_fc1": Workload("vitb16_197_fc1", 64, 14, 14, 768, 3072, 8, (8,), ("l1",), "bf16", 1007, 1),
+    # The small batches of on-device training (the setting the paper's experiments aim at): config 2 with
+    # 8 images and with one.  Few low-rank rows under a long reduction over Cout.
+    "vitb_fc1_batch8": Workload("vitb_fc1_batch8", 8, 16, 16, 768, 3072, 8, (8,), ("l1",), "bf16", 1008),
+    "vitb_fc1_batch1": Workload("vitb_fc1_batch1", 1, 16, 16, 768, 3072, 8, (8,), ("l1",), "bf16", 1009),
 }
 
 

@@ -60,7 +60,7 @@ def test_one_json_line_with_the_agreed_keys():
     sys.path.insert(0, ROOT)
     import bench
     from paper_2309_15275_amd import workloads
-    assert rows == set(bench.sweep_cases(workloads)) and len(rows) == 23
+    assert rows == set(bench.sweep_cases(workloads)) and len(rows) == 25
     for row in j["sweep"]:
         assert row["lbp_us"] > 0 and row["full_bp_us"] > 0 and abs(row["speedup"] - row["full_bp_us"] / row["lbp_us"]) < 0.02
         assert 0 < row["proj_frac_hbm"] < 1
