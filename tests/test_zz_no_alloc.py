@@ -84,3 +84,37 @@ def test_static_scratch_backward_inside_a_captured_graph():
         ref_gx, ref_gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], wl.patch, idx)
         torch.cuda.synchronize()
         assert torch.equal(gx, ref_gx) and torch.equal(gW, ref_gW), rep
+
+
+def test_static_scratch_backward_with_a_reduction_cut_inside_the_launch_under_a_graph():
+    # the input-gradient product's reduction in 3 slices that join inside the launch: partial tiles in the scratch
+    # array, tile counters in the library's device image, nothing allocated; replays start from clean counters
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    binding.set_option("LBP_GX_JOIN", "3")
+    try:
+        wl, host, dev, idx = _case(2, 16, 16, 136, 776, 8, 8, 817)
+        text = binding.describe_plan(binding.make_shape(dev["x"], dev["gy"], dev["w"]), wl.patch, idx)
+        assert "reduction in 3 slices joined in the launch" in text, text
+        gx, gW = nan_outputs(dev["x"].shape, dev["x"].dtype, dev["w"].shape)
+        binding.lbp_wht_backward_static(dev["x"], dev["gy"], dev["w"], wl.patch, idx, gx, gW)
+        torch.cuda.synchronize()
+        gx0, gW0 = oracle.lbp_wht_backward(host["x"], host["gy"], host["w"], wl.patch, idx)
+        assert_matches(gx, gx0, TOL["bf16"], "gx")
+        assert_matches(gW, gW0, TOL["bf16"], "gW")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            binding.lbp_wht_backward_static(dev["x"], dev["gy"], dev["w"], wl.patch, idx, gx, gW)
+        for rep in range(3):
+            with torch.no_grad():
+                dev["gy"].mul_(-0.5 if rep % 2 else 2.0)
+                dev["x"].copy_(dev["x"].roll(1, dims=0))
+            gx.fill_(float("nan"))
+            gW.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            ref_gx, ref_gW = binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], wl.patch, idx)
+            torch.cuda.synchronize()
+            assert torch.equal(gx, ref_gx) and torch.equal(gW, ref_gW), rep
+    finally:
+        binding.reset_options()
