@@ -32,10 +32,12 @@
  *            errors are detected on the host before any HIP call is made, so they can be provoked
  *            and tested on a machine without a GPU.  There is no CPU fallback: without a usable
  *            gfx950 device the compute entry points return LBP_ERR_HIP.
- *   Threads  entry points may be called from several host threads; calls that use the library's
- *            internal workspace on the same device are serialised by the caller's stream order
- *            only, so concurrent calls on different streams of one device must each bring their
- *            own workspace (lbp_set_workspace is per process, see below).
+ *   Threads  entry points may be called from several host threads, but backward calls on one
+ *            device are ordered by the caller's stream order only: they share that device's
+ *            workspace (the internal one or the one set with lbp_set_workspace, which is per
+ *            process) and a small array of tile counters inside the library, so two backward
+ *            calls must not overlap in time on one device (different streams need an event
+ *            between them).
  */
 #ifndef LBP_WHT_H
 #define LBP_WHT_H
