@@ -179,13 +179,23 @@ size_t gemm_join_bytes(int tile, long M_rows, long N, int r, int splits)
     return (size_t)tiles * splits * t.bm * t.bn * sizeof(float);
 }
 
+bool gemm_join_supported(const GemmArgs &a, GemmPath path)
+{
+    if (path == GemmPath::kSimple || a.out != GemmOut::kUnproject || a.splits < 2 || !a.plan || a.plan->patch != 8) return false;
+    int tile, lp;
+    mfma::Params p;
+    if (prepare(a, &tile, &p, &lp) != hipSuccess) return false;
+    return tile == kPairTileX0 || tile == kPairTileX1;
+}
+
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t stream)
 {
     int tile, lp;
     mfma::Params p;
     hipError_t e = prepare(a, &tile, &p, &lp);
     if (e != hipSuccess) return e;
-    if (a.out == GemmOut::kUnproject && a.splits != 1) return hipErrorInvalidValue;       // grouped launches only
+    // slices of a fused product join inside the launch on the 8-wavefront 128-wide tiles only
+    if (a.out == GemmOut::kUnproject && a.splits != 1 && tile != kPairTileX0 && tile != kPairTileX1) return hipErrorInvalidValue;
     return kLaunch[tile](p, a.a_kfast, a.out, lp, a.splits, stream);
 }
 

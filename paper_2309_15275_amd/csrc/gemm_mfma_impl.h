@@ -656,11 +656,11 @@ __device__ __forceinline__ void gemm_body(const Params &p, const int tile_id, co
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
+template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP, bool JOIN = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(Params p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    gemm_body<BM, BN, WGM, WGN, PF, A_KFAST, EPI, LP>(p, blockIdx.x, blockIdx.y, smem);
+    gemm_body<BM, BN, WGM, WGN, PF, A_KFAST, EPI, LP, JOIN>(p, blockIdx.x, blockIdx.y, smem);
 }
 
 // A kernel that uses more than 64 KB of dynamic LDS has to be allowed to, once per device (the
@@ -681,11 +681,11 @@ inline hipError_t allow_dynamic_lds(const void *kern, int bytes, bool *configure
     return hipSuccess;
 }
 
-template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP>
+template <int BM, int BN, int WGM, int WGN, int PF, bool A_KFAST, int EPI, int LP, bool JOIN = false>
 hipError_t launch_one(const Params &p, int splits, hipStream_t stream)
 {
     constexpr int LDS = Smem<BM, BN, A_KFAST>::TOTAL;
-    auto kern = gemm_kernel<BM, BN, WGM, WGN, PF, A_KFAST, EPI, LP>;
+    auto kern = gemm_kernel<BM, BN, WGM, WGN, PF, A_KFAST, EPI, LP, JOIN>;
     static bool configured[kMaxLaunchDevices] = {};     // per instantiation
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), LDS, configured);
     if (e != hipSuccess) return e;
@@ -756,6 +756,14 @@ hipError_t launch_tile(const Params &p, bool a_kfast, GemmOut out, int lp, int s
 {
     if (out == GemmOut::kUnproject) {
         if constexpr (FUSED) {
+            if (p.splits > 1) {      // slices that join inside the launch: the 8-wavefront 128-wide tiles, patch 8
+                if constexpr (BN == 128 && WGM * WGN == 8) {
+                    if (lp != 3) return hipErrorInvalidValue;
+                    if (p.mfma_epilogue) return launch_one<BM, BN, WGM, WGN, PF, true, EPI_UNPROJECT_MFMA, 3, true>(p, p.splits, s);
+                    return launch_one<BM, BN, WGM, WGN, PF, true, EPI_UNPROJECT, 3, true>(p, p.splits, s);
+                }
+                return hipErrorInvalidValue;
+            }
             if (p.mfma_epilogue) {
                 if constexpr (BN == 128) {
                     if (lp == 3) return launch_one<BM, BN, WGM, WGN, PF, true, EPI_UNPROJECT_MFMA, 3>(p, 1, s);

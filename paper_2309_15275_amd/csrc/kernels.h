@@ -98,12 +98,14 @@ struct GemmArgs {
     // kUnproject only: `extra` tokens per image in front of the grid; the last extra_rows rows of A
     // are theirs (image-major) and their rows of the product go to those tokens, scaled by 1/patch^2
     int extra = 0, extra_rows = 0;
-    // kUnproject with splits > 1 (grouped launch only): gemm_join_bytes(...) bytes of device memory in
+    // kUnproject with splits > 1 (8-wavefront 128-wide tiles, patch 8): gemm_join_bytes(...) bytes of device memory in
     // which the slices of a tile leave their partial sums for the one that finishes the tile
     void *join_parts = nullptr;
     size_t join_bytes = 0;     // size of that memory: a launch that needs more is refused
 };
 
+// True if launch_gemm runs this kUnproject product with its reduction in a.splits slices that join inside the launch.
+bool gemm_join_supported(const GemmArgs &a, GemmPath path);
 // Bytes of GemmArgs::join_parts for a kUnproject product of `tile` shape, M_rows x N with r bases, in `splits` slices.
 size_t gemm_join_bytes(int tile, long M_rows, long N, int r, int splits);
 // Most tiles such a product may have (one counter each).

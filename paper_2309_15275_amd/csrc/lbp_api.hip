@@ -531,11 +531,12 @@ int backward_impl(const void *x, const void *gy, const void *W, const lbp_shape_
             g.plan = &plan;
             g.extra = extra;
             g.extra_rows = N * extra;
-            if (ws.grouped && gW && ws.gx_join > 1) {       // slices that combine inside the grouped launch
+            if (ws.gx_join > 1) {       // slices that combine inside the launch
                 g.splits = ws.gx_join;
                 g.join_parts = gx_r;
                 g.join_bytes = ws.gx_join_bytes;
-                if (!lbp::gemm_pair_supported(g, gw_args, gpath)) {     // (the planner only asks where the kernels exist)
+                const bool ok = ws.grouped && gW ? lbp::gemm_pair_supported(g, gw_args, gpath) : lbp::gemm_join_supported(g, gpath);
+                if (!ok) {     // (the planner only asks where the kernels exist)
                     g.splits = 1;
                     g.join_parts = nullptr;
                     g.join_bytes = 0;

@@ -382,6 +382,43 @@ static int plan_workspace_uncached(const lbp_shape_t *s, int patch, int r, int n
             ws->gx_join = join;
         }
     }
+    // A fused input-gradient product launched on its own (only g~x wanted, or the grouped launch was not
+    // taken) can cut its reduction the same way, on the 8-wavefront tiles: same model, no second product.
+    if (!ws->grouped && can_fuse && patch == 8 && s->dtype == LBP_BF16 && s->Cin > 64 && gx_join != 1) {
+        int best_tile = -1, best_join = 1;
+        double best_us = 1e300;
+        auto model = [&](int t, int sl) {
+            const GemmTileInfo &tx = kGemmTiles[t];
+            const long bm_step = tx.bm / r * r;
+            const long tiles = ((Mr + bm_step - 1) / bm_step) * ((s->Cin + tx.bn - 1) / tx.bn);
+            const long st = ((s->Cout + sl - 1) / sl + 63) / 64;
+            const double cost = st * (tx.bm <= 64 ? 0.40 : 0.60) + (double)(bm_step / r) * patch * patch * tx.bn * esz / 45.0e3 +
+                                (sl > 1 ? 5.0 + 0.25 * sl : 0.0);
+            return tiles > 16384 ? 1e300 : grouped_launch_estimate(tiles * sl, cost, 0, 0.0, num_cus, false) + 3.0;
+        };
+        for (int t : {5, 4}) {
+            if (r > kGemmTiles[t].bm) continue;
+            for (int sl = 2; sl <= 8; ++sl) {
+                if (gx_join > 0 && sl != gx_join) continue;
+                const long k_slice = ((s->Cout + sl - 1) / sl + 63) / 64 * 64;
+                if (k_slice < 4 * 64 || (long)(sl - 1) * k_slice >= s->Cout) continue;
+                const double us = model(t, sl);
+                if (us < best_us) {
+                    best_us = us;
+                    best_tile = t;
+                    best_join = sl;
+                }
+            }
+        }
+        // against what the plan has: the same model for a fused product on one of these tiles, else the plan's own estimate
+        double cur_us = ws->gx.est_us;
+        if (ws->gx_fused && (ws->gx.tile == 4 || ws->gx.tile == 5)) cur_us = model(ws->gx.tile, 1);
+        if (best_tile >= 0 && (gx_join > 1 || best_us < 0.9 * cur_us)) {
+            ws->gx = GemmPlan{best_tile, 1, best_us};
+            ws->gx_fused = true;
+            ws->gx_join = best_join;
+        }
+    }
     // Where the reverse projection stays a kernel of its own, the product can hand it bf16
     // coefficients in one piece instead of fp32 split-K slices: a quarter of the bytes on the way
     // there and back, and any tile.  (Decided last, so that it only ever replaces the fp32 hand-over.)

@@ -360,6 +360,38 @@ def test_input_gradient_reduction_cut_into_slices_that_join_inside_the_launch(ca
     assert_matches(gx1, want_gx, TOL["bf16"], "gx, one slice")
 
 
+@pytest.mark.parametrize("case,slices", [(1, "2"), (1, "3"), (2, "2"), (5, "2"), (5, "5")])
+def test_input_gradient_alone_with_its_reduction_cut_inside_the_launch(case, slices):
+    # only g~x wanted: the fused product is a launch of its own and cuts its reduction the same way
+    N, H, W, Cin, Cout, patch, r, order, extra = JOINED[case]
+    wl = small("join1", N, H, W, Cin, Cout, patch, "bf16", 650 + case)
+    idx = oracle.select_bases(patch, r, order)
+    host, dev = device_inputs(wl)
+    want_gx, _ = oracle.lbp_wht_backward_padded(host["x"], host["gy"], host["w"], patch, idx, want_gw=False)
+    shape = binding.LbpShape(N, H, W, Cin, Cout, binding.LBP_BF16, binding.LBP_F32)
+    binding.set_option("LBP_FUSE_UNPROJECT", "1")
+    binding.set_option("LBP_GX_JOIN", slices)
+    text = binding.describe_plan(shape, patch, idx, want_gw=False)
+    assert f"reduction in {slices} slices joined in the launch" in text and "gW:" not in text, text
+    space = torch.empty(binding.workspace_bytes(shape, patch, r) + 256, dtype=torch.uint8, device="cuda")
+    binding.set_workspace(space)
+    try:
+        written = []
+        for join in ("1", slices, slices):
+            binding.set_option("LBP_GX_JOIN", join)
+            space.fill_(0xCD)
+            gx = torch.full_like(dev["x"], float("nan"))
+            binding.lbp_wht_backward(dev["x"], dev["gy"], dev["w"], patch, idx, gx=gx, want_gw=False)
+            torch.cuda.synchronize()
+            written.append((int((space != 0xCD).sum()), gx))
+    finally:
+        binding.set_workspace(None)
+    assert written[1][0] > written[0][0] + 64 * 128 * 2, [w[0] for w in written]       # the slices' partial tiles
+    assert torch.equal(written[1][1].view(torch.int16), written[2][1].view(torch.int16))
+    for _, gx in written:
+        assert_matches(gx, want_gx, TOL["bf16"], "gx")
+
+
 @pytest.mark.parametrize("tile", ["4", "6"])
 @pytest.mark.parametrize("fuse", ["1", "0"])
 @pytest.mark.parametrize("case", [0, 3, 5, 10, 13])
