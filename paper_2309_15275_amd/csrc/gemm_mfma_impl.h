@@ -21,6 +21,8 @@
 //     the p x p tokens of that patch with the same pooled butterfly the stand-alone kernel uses.
 //   * Workgroups are numbered so that each of the 8 XCDs (private L2 each) works on a contiguous
 //     run of tiles that share the same rows of A.
+//   * A fused product with few tiles under a long reduction can cut the reduction into slices, one
+//     workgroup each, that combine inside the launch (JOIN instantiations): see store_part below.
 #pragma once
 #include "device_utils.h"
 #include "kernels.h"
