@@ -244,7 +244,7 @@ size_t lbp_wht_workspace_bytes_tokens(const lbp_shape_t *shape, int extra, int p
                                     v >> 3, join) != LBP_OK)
                 return 0;
             if (ws.total > total) total = ws.total;
-            if (patch == 0 || !(v & 4)) break;       // only grouped plans have joined slices
+            if (patch == 0) break;
         }
         if (patch == 0) break;
     }

@@ -339,3 +339,36 @@ def test_the_public_header_is_plain_c(tmp_path):
     res = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", os.path.join(ROOT, "include"), str(src)],
                          capture_output=True, text=True)
     assert res.returncode == 0, res.stderr
+
+
+def test_reported_workspace_size_covers_every_plan_under_every_switch(lib):
+    # lbp_wht_workspace_bytes is what a caller sizes its own workspace with: no plan of the same shape and rank, with
+    # whatever outputs wanted and whatever kernel-choice switch set, may need more (host logic only)
+    rng = np.random.default_rng(20261)
+    checked = 0
+    try:
+        for _ in range(250):
+            patch = int(rng.choice([4, 8, 8, 8, 16]))
+            N = int(rng.integers(1, 70))
+            H = max(1, int(rng.integers(1, 5)) * patch + int(rng.choice([0, 0, -1])))
+            W = int(rng.integers(1, 5)) * patch
+            Cin, Cout = int(rng.integers(1, 520)) * 8, int(rng.integers(1, 520)) * 8
+            r = int(rng.integers(1, patch * patch + 1))
+            idx = binding.select_bases(patch, r, str(rng.choice(["l1", "linf"])))
+            extra = int(rng.choice([0, 0, 1, 2]))
+            shape = binding.LbpShape(N, H, W, Cin, Cout, 1, int(rng.integers(0, 2)))
+            for name, value in ((None, None), ("LBP_GX_JOIN", str(int(rng.integers(1, 9)))),
+                                ("LBP_FUSE_UNPROJECT", str(int(rng.integers(0, 2)))), ("LBP_GEMM_GROUP", str(int(rng.integers(0, 3)))),
+                                ("LBP_GX_COEF", str(rng.choice(["f32", "bf16"])))):
+                binding.reset_options()
+                if name:
+                    binding.set_option(name, value)
+                have = binding.workspace_bytes(shape, patch, r, extra=extra)
+                for want_gx, want_gw in ((True, True), (True, False), (False, True)):
+                    text = binding.describe_plan(shape, patch, idx, extra=extra, want_gx=want_gx, want_gw=want_gw, num_cus=256)
+                    need = int(text.rsplit("workspace ", 1)[1].split()[0])
+                    assert need <= have, (N, H, W, Cin, Cout, patch, r, extra, name, value, want_gx, want_gw, need, have)
+                    checked += 1
+    finally:
+        binding.reset_options()
+    assert checked == 250 * 5 * 3
